@@ -1,0 +1,291 @@
+"""CPU oracle for the Learn2PD decoding loop (arXiv 2509.25188).
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain statement of what the
+decoding path computes.  Only the test-suite, the smoke check and the
+CPU-baseline leg of the benchmark may import it; the product path never does,
+and this file imports nothing from the product.
+
+What it states, in the paper's order and notation:
+
+* the mask predictor M(X) -> logits.  The paper treats the dLLM as a black box
+  (Sec. 3.1.1, "mask predictor p_theta"; Alg. 2, "conf, pre = M(X)"); the
+  architecture here is the LLaDA-style family of the workloads: pre-norm
+  transformer, RMSNorm, rotary position embedding, bidirectional (unmasked)
+  softmax attention, SwiGLU FFN, untied LM head, no biases;
+* greedy estimate  pre_j = argmax_v p_theta(v | X)        (Eq. 3);
+* confidence       conf_j = p_theta(pre_j | X)            (Eq. 4);
+* the filter       p = sigmoid(f_theta(conf)), f_theta a two-layer MLP on the
+  block's confidence vector (Sec. 3.2; Sec. 4.1: 2,112 parameters at block 32);
+* the inference loop: blocks left to right, `while M != {}` per block, unmask j
+  when p_j > tau (Alg. 2);
+* End-of-Text Prediction: after a block's loop ends, stop if an end-of-text
+  token is in the response (Alg. 3, Appendix A; Fig. 4 caption);
+* the prefix KV cache variant (Sec. 4.3 names the technique only): K/V of the
+  prompt and finished blocks come from a forward over that prefix alone and
+  are refreshed once per block; a step recomputes only the active block.
+
+Readings of points the paper leaves open (each also listed in the design notes):
+mask id excluded from the vocabulary distribution; ties -> lowest index;
+already-committed block positions feed the filter the constant 1.0; the masked
+position with the highest confidence is always unmasked (progress guarantee);
+the end-of-text search covers the response region only; after an early stop
+the undecoded tail keeps the mask id.
+
+Parity pins: every function below is pinned by tests/test_oracle_*.py against
+brute-force loops, closed forms and invariants, except the whole trajectory on
+a random-init model, for which the paper prints no worked example:
+PARITY UNPINNED for `generate` beyond its invariants and special cases.
+
+Precision: `dtype` is numpy float32 (default) or float64.  Weights given as
+uint16 arrays are bf16 bit patterns and are widened exactly.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+# --------------------------------------------------------------------------- helpers
+def widen(w, dtype):
+    """Exact widening of a stored weight (float array, or uint16 bf16 bit patterns) to `dtype`."""
+    w = np.asarray(w)
+    if w.dtype == np.uint16:
+        return (w.astype(np.uint32) << 16).view(np.float32).astype(dtype, copy=False)
+    return w.astype(dtype, copy=False)
+
+
+def rmsnorm(x, g, eps):
+    """y = x / sqrt(mean(x^2) + eps) * g, along the last axis."""
+    ms = np.mean(x * x, axis=-1, keepdims=True)
+    return x / np.sqrt(ms + x.dtype.type(eps)) * g
+
+
+def rope(x, pos, base):
+    """Rotary embedding, rotate-half pairing.
+
+    x: [T, H, Dh]; pos: [T] absolute positions.  Feature pair (i, i + Dh/2)
+    is rotated by the angle pos * base^(-2i/Dh).
+    """
+    dh = x.shape[-1]
+    half = dh // 2
+    i = np.arange(half, dtype=np.float64)
+    ang = np.asarray(pos, dtype=np.float64)[:, None] * base ** (-2.0 * i / dh)   # [T, half]
+    cos = np.cos(ang).astype(x.dtype)[:, None, :]
+    sin = np.sin(ang).astype(x.dtype)[:, None, :]
+    x1, x2 = x[..., :half], x[..., half:]
+    return np.concatenate([x1 * cos - x2 * sin, x2 * cos + x1 * sin], axis=-1)
+
+
+def softmax(z, axis=-1):
+    z = z - np.max(z, axis=axis, keepdims=True)
+    e = np.exp(z)
+    return e / np.sum(e, axis=axis, keepdims=True)
+
+
+def attention(q, k, v):
+    """Bidirectional attention.  q: [Tq, H, Dh]; k, v: [Tk, H, Dh] -> [Tq, H, Dh].
+
+    Every query sees every key: there is no causal mask (the dLLM refines the
+    whole sequence at once, Sec. 1).
+    """
+    dh = q.shape[-1]
+    s = np.einsum("qhd,khd->hqk", q, k) / q.dtype.type(np.sqrt(dh))
+    p = softmax(s, axis=-1)
+    return np.einsum("hqk,khd->qhd", p, v)
+
+
+def silu(x):
+    return x / (1.0 + np.exp(-x))
+
+
+def sigmoid(x):
+    return 1.0 / (1.0 + np.exp(-x))
+
+
+# --------------------------------------------------------------------------- mask predictor M(X)
+class Model:
+    """The mask predictor.  `shape` needs n_layers, d_model, n_heads, head_dim, rope_base, rms_eps;
+    `weights` maps tensor names to arrays ([out, in] row-major matrices)."""
+
+    def __init__(self, shape, weights, dtype=np.float32):
+        self.s = shape
+        self.w = weights
+        self.dtype = np.dtype(dtype)
+
+    def W(self, name):
+        return widen(self.w[name], self.dtype)
+
+    def embed(self, tokens):
+        tok = np.asarray(tokens, dtype=np.int64)
+        e = self.w["tok_emb"]
+        return widen(np.asarray(e)[tok], self.dtype)
+
+    def qkv(self, l, h, pos):
+        """Layer l's rotated queries/keys and values for hidden rows h at positions pos."""
+        s, p = self.s, f"layers.{l}."
+        a = rmsnorm(h, self.W(p + "attn_norm_g"), s.rms_eps)
+        t = a.shape[0]
+        q = (a @ self.W(p + "wq").T).reshape(t, s.n_heads, s.head_dim)
+        k = (a @ self.W(p + "wk").T).reshape(t, s.n_heads, s.head_dim)
+        v = (a @ self.W(p + "wv").T).reshape(t, s.n_heads, s.head_dim)
+        return rope(q, pos, s.rope_base), rope(k, pos, s.rope_base), v
+
+    def finish_layer(self, l, h, o):
+        """Attention output projection + residual, then the SwiGLU FFN + residual."""
+        p = f"layers.{l}."
+        h = h + o.reshape(h.shape[0], -1) @ self.W(p + "wo").T
+        f = rmsnorm(h, self.W(p + "ffn_norm_g"), self.s.rms_eps)
+        act = silu(f @ self.W(p + "w_gate").T) * (f @ self.W(p + "w_up").T)
+        return h + act @ self.W(p + "w_down").T
+
+    def head(self, h_rows):
+        return rmsnorm(h_rows, self.W("final_norm_g"), self.s.rms_eps) @ self.W("lm_head").T
+
+    def forward(self, tokens, row_begin=0, row_count=None):
+        """logits[row_count, V] of one sequence `tokens` [T]; full bidirectional forward."""
+        t = len(tokens)
+        if row_count is None:
+            row_count = t - row_begin
+        pos = np.arange(t)
+        h = self.embed(tokens)
+        for l in range(self.s.n_layers):
+            q, k, v = self.qkv(l, h, pos)
+            h = self.finish_layer(l, h, attention(q, k, v))
+        return self.head(h[row_begin:row_begin + row_count])
+
+    # ---- prefix KV cache (Sec. 4.3) ----
+    def prefix_kv(self, tokens_prefix):
+        """Per-layer (K, V) of a forward over the prefix alone (nothing after it is visible)."""
+        c = len(tokens_prefix)
+        pos = np.arange(c)
+        h = self.embed(tokens_prefix)
+        cache = []
+        for l in range(self.s.n_layers):
+            q, k, v = self.qkv(l, h, pos)
+            cache.append((k, v))
+            if l + 1 < self.s.n_layers:
+                h = self.finish_layer(l, h, attention(q, k, v))
+        return cache
+
+    def forward_block_cached(self, cache, block_tokens, c):
+        """logits[s, V] for the active block at positions c..c+s-1: its queries attend to the
+        cached prefix keys/values plus the block's own, and to nothing after the block."""
+        n = len(block_tokens)
+        pos = np.arange(c, c + n)
+        h = self.embed(block_tokens)
+        for l in range(self.s.n_layers):
+            q, k, v = self.qkv(l, h, pos)
+            kc, vc = cache[l]
+            o = attention(q, np.concatenate([kc, k], axis=0), np.concatenate([vc, v], axis=0))
+            h = self.finish_layer(l, h, o)
+        return self.head(h)
+
+
+# --------------------------------------------------------------------------- Eq. 3, Eq. 4
+def conf_pre(logits, mask_id):
+    """pre_j = argmax_v p(v) (Eq. 3) and conf_j = p(pre_j) (Eq. 4) over the data vocabulary.
+
+    The mask token is not a data token, so its logit is removed from the distribution.
+    Ties go to the lowest token id.
+    """
+    z = np.array(logits, copy=True)
+    z[:, mask_id] = -np.inf
+    pre = np.argmax(z, axis=-1)           # numpy returns the first maximum
+    p = softmax(z, axis=-1)
+    conf = p[np.arange(len(pre)), pre]
+    return conf.astype(logits.dtype), pre.astype(np.int64)
+
+
+# --------------------------------------------------------------------------- filter f_theta (Sec. 3.2)
+def filter_prob(conf_in, flt):
+    """sigmoid(W2 relu(W1 c + b1) + b2) for the block's confidence vector c."""
+    dt = conf_in.dtype
+    h = np.maximum(widen(flt["w1"], dt) @ conf_in + widen(flt["b1"], dt), 0)
+    z = widen(flt["w2"], dt) @ h + widen(flt["b2"], dt)
+    return sigmoid(z)
+
+
+def filter_param_count(block_len, hidden):
+    return hidden * block_len + hidden + block_len * hidden + block_len
+
+
+# --------------------------------------------------------------------------- one denoising step (Alg. 2 loop body)
+def apply_bias(logits, gen_pos0, bias):
+    """Test hook of the workloads: add `value` to one token's logit at generation positions >= from."""
+    if bias is None or bias[2] == 0.0:
+        return logits
+    token_id, pos_from, value = bias
+    out = np.array(logits, copy=True)
+    for j in range(out.shape[0]):
+        if gen_pos0 + j >= pos_from:
+            out[j, token_id] += out.dtype.type(value)
+    return out
+
+
+def decide(block_tokens, logits, mask_id, flt, tau):
+    """Unmask decision of one step for one block.
+
+    Returns dict(conf, pre, p, sel).  sel[j] is true when position j is unmasked now:
+    it is masked and p_j > tau (strict), or it is the masked position of highest
+    confidence (lowest index on ties), which is always taken so that the loop ends.
+    """
+    masked = np.asarray(block_tokens) == mask_id
+    conf, pre = conf_pre(logits, mask_id)
+    cin = np.where(masked, conf, conf.dtype.type(1.0))
+    p = filter_prob(cin, flt)
+    sel = masked & (p > p.dtype.type(tau))
+    if masked.any():
+        cm = np.where(masked, conf, -np.inf)
+        sel[int(np.argmax(cm))] = True
+    return dict(conf=conf, pre=pre, p=p, sel=sel, masked=masked)
+
+
+def denoise_step(model, X, prompt_len, b, block_len, mask_id, flt, tau, bias=None, cache=None):
+    """One pass of the while-loop body of Alg. 2 for block b of sequence X (modified in place)."""
+    lo = prompt_len + b * block_len
+    if cache is None:
+        logits = model.forward(X, lo, block_len)
+    else:
+        logits = model.forward_block_cached(cache, X[lo:lo + block_len], lo)
+    logits = apply_bias(logits, b * block_len, bias)
+    d = decide(X[lo:lo + block_len], logits, mask_id, flt, tau)
+    for j in np.nonzero(d["sel"])[0]:
+        X[lo + j] = d["pre"][j]
+    d["logits"] = logits
+    return d
+
+
+# --------------------------------------------------------------------------- Alg. 2 / Alg. 3
+def generate(model, prompt, gen_len, block_len, mask_id, eos_id, flt, tau, eotp=False,
+             bias=None, prefix_cache=False, trace=None):
+    """Decode one prompt.  Returns (response[gen_len], steps, decoded_len).
+
+    `trace`, if a list, receives one record per step: the state before the step and the
+    step's conf / pre / p / sel, for teacher-forced comparison.
+    """
+    assert gen_len % block_len == 0
+    P = len(prompt)
+    X = np.concatenate([np.asarray(prompt, dtype=np.int64),
+                        np.full(gen_len, mask_id, dtype=np.int64)])
+    steps = 0
+    decoded_len = gen_len
+    for b in range(gen_len // block_len):
+        lo = P + b * block_len
+        cache = model.prefix_kv(X[:lo]) if prefix_cache else None
+        while np.any(X[lo:lo + block_len] == mask_id):
+            before = X.copy() if trace is not None else None
+            d = denoise_step(model, X, P, b, block_len, mask_id, flt, tau, bias, cache)
+            steps += 1
+            if trace is not None:
+                d.update(X_before=before, block=b)
+                trace.append(d)
+        if eotp and np.any(X[P:lo + block_len] == eos_id):
+            decoded_len = (b + 1) * block_len
+            break
+    return X[P:P + gen_len].copy(), steps, decoded_len
+
+
+def tail_all_eos(response, eos_id, decoded_len):
+    """True when every decoded position from the first end-of-text token on holds end-of-text."""
+    r = np.asarray(response)[:decoded_len]
+    hit = np.nonzero(r == eos_id)[0]
+    return bool(len(hit) and np.all(r[hit[0]:] == eos_id))

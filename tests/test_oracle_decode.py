@@ -1,0 +1,270 @@
+"""Pins for the oracle's decode rule: Eq. 3 / Eq. 4 closed forms, the filter, Alg. 2 invariants
+and special cases, Alg. 3 (EoTP) stopping, and the values the paper prints."""
+import math
+import os
+import re
+import types
+
+import numpy as np
+import pytest
+
+from oracle import l2pd_oracle as O
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "paper_values.txt")
+
+
+def golden():
+    out = {}
+    for line in open(GOLDEN):
+        m = re.match(r"\s*(\w+)\s*=\s*([-\d.]+)", line)
+        if m:
+            out[m.group(1)] = float(m.group(2))
+    return out
+
+
+class ScriptedModel:
+    """Stands in for M(X): logits depend on the position only (a fixed table)."""
+
+    def __init__(self, table, prompt_len):
+        self.table = table          # [gen_len, V]
+        self.P = prompt_len
+        self.calls = 0
+
+    def forward(self, X, lo, n):
+        self.calls += 1
+        return self.table[lo - self.P: lo - self.P + n].copy()
+
+
+def pass_all_filter(s, h=4, z=+50.0):
+    return dict(w1=np.zeros((h, s)), b1=np.zeros(h), w2=np.zeros((s, h)), b2=np.full(s, z))
+
+
+# ----------------------------------------------------------------- Eq. 3 / Eq. 4
+def test_conf_uniform_logits_closed_form():
+    V, mask = 50, 49
+    conf, pre = O.conf_pre(np.zeros((3, V)), mask)
+    assert list(pre) == [0, 0, 0]                       # lowest id wins ties
+    np.testing.assert_allclose(conf, 1.0 / (V - 1), rtol=1e-14)  # mask id is not a data token
+
+
+def test_conf_one_raised_logit_closed_form():
+    V, mask, beta = 40, 7, 2.5
+    z = np.zeros((1, V))
+    z[0, 11] = beta
+    z[0, mask] = 99.0                                   # must be ignored, however large
+    conf, pre = O.conf_pre(z, mask)
+    assert pre[0] == 11
+    assert conf[0] == pytest.approx(math.exp(beta) / (math.exp(beta) + V - 2), rel=1e-13)
+
+
+def test_conf_is_max_probability_bruteforce():
+    r = np.random.default_rng(0)
+    V, mask = 23, 22
+    z = r.normal(size=(5, V)) * 3
+    conf, pre = O.conf_pre(z, mask)
+    for j in range(5):
+        ex = [math.exp(z[j, v]) for v in range(V) if v != mask]
+        probs = [e / sum(ex) for e in ex]
+        assert pre[j] == int(np.argmax(probs))
+        assert conf[j] == pytest.approx(max(probs), rel=1e-12)
+
+
+# ----------------------------------------------------------------- filter
+def test_filter_hand_example():
+    # c = (0.2, 0.9); W1 = [[1, -1], [2, 0]], b1 = (0.5, -1); hidden pre-act = (-0.2, -0.6) -> relu (0, 0)
+    # second example c = (0.9, 0.2): pre-act = (1.2, 0.8) -> W2 = [[1, 1], [-2, 0.5]], b2 = (0, 1)
+    #   z = (2.0, -2.4 + 0.4 + 1) = (2.0, -1.0)
+    flt = dict(w1=np.array([[1., -1.], [2., 0.]]), b1=np.array([0.5, -1.]),
+               w2=np.array([[1., 1.], [-2., 0.5]]), b2=np.array([0., 1.]))
+    p = O.filter_prob(np.array([0.2, 0.9]), flt)
+    np.testing.assert_allclose(p, [0.5, 1 / (1 + math.exp(-1.0))], rtol=1e-14)
+    p = O.filter_prob(np.array([0.9, 0.2]), flt)
+    np.testing.assert_allclose(p, [1 / (1 + math.exp(-2.0)), 1 / (1 + math.exp(1.0))], rtol=1e-14)
+
+
+def test_filter_param_count_matches_paper():
+    g = golden()
+    assert O.filter_param_count(32, 32) == int(g["filter_params_block32"])
+
+
+# ----------------------------------------------------------------- Alg. 2 invariants and special cases
+def run(table, P, G, s, flt, tau, mask, eos, **kw):
+    m = ScriptedModel(table, P)
+    trace = []
+    out = O.generate(m, np.arange(P) % 5, G, s, mask, eos, flt, tau, trace=trace, **kw)
+    return out, trace, m
+
+
+def rand_table(G, V, seed):
+    return np.random.default_rng(seed).normal(size=(G, V)) * 2.0
+
+
+def test_tau_ge_one_is_one_token_per_step_in_confidence_order():
+    g = golden()
+    P, G, s, V = 3, 64, 32, 30
+    mask, eos = V - 1, V - 2
+    table = rand_table(G, V, 1)
+    table[:, eos] = -30.0
+    flt = dict(w1=np.random.default_rng(2).normal(size=(8, s)), b1=np.zeros(8),
+               w2=np.random.default_rng(3).normal(size=(s, 8)), b2=np.zeros(s))
+    (resp, steps, dlen), trace, m = run(table, P, G, s, flt, 1.0, mask, eos)
+    assert steps == G == m.calls and dlen == G
+    assert steps // (G // s) == int(g["vanilla_decodings_per_block32"])   # 32 decodings per block of 32
+    conf, pre = O.conf_pre(table, mask)
+    np.testing.assert_array_equal(resp, pre)
+    for b in range(G // s):
+        order = [int(np.nonzero(t["sel"])[0][0]) for t in trace if t["block"] == b]
+        assert all(int(t["sel"].sum()) == 1 for t in trace)
+        expect = sorted(range(s), key=lambda j: (-conf[b * s + j], j))
+        assert order == expect                       # = one-token-per-step low-confidence remasking
+
+
+def test_negative_tau_is_one_step_per_block():
+    P, G, s, V = 2, 96, 32, 20
+    table = rand_table(G, V, 4)
+    table[:, V - 2] = -30.0
+    flt = dict(w1=np.zeros((4, s)), b1=np.zeros(4), w2=np.zeros((s, 4)), b2=np.zeros(s))
+    (resp, steps, dlen), trace, _ = run(table, P, G, s, flt, -0.1, V - 1, V - 2)
+    assert steps == G // s
+    assert all(t["sel"].all() for t in trace)
+
+
+def test_strict_threshold_compare():
+    # sigmoid(0) = 0.5 exactly; tau = 0.5 must NOT pass (strict >), so only the forced top-1 goes.
+    P, G, s, V = 1, 8, 8, 12
+    table = rand_table(G, V, 5)
+    table[:, V - 2] = -30.0
+    flt = dict(w1=np.zeros((2, s)), b1=np.zeros(2), w2=np.zeros((s, 2)), b2=np.zeros(s))
+    (_, steps, _), trace, _ = run(table, P, G, s, flt, 0.5, V - 1, V - 2)
+    assert np.all(trace[0]["p"] == 0.5)
+    assert steps == G
+    (_, steps, _), _, _ = run(table, P, G, s, flt, 0.4999, V - 1, V - 2)
+    assert steps == 1
+
+
+def test_never_remask_and_step_bounds():
+    P, G, s, V = 4, 64, 16, 25
+    mask, eos = V - 1, V - 2
+    table = rand_table(G, V, 6) * 2
+    table[:, eos] = -30.0
+    r = np.random.default_rng(7)
+    flt = dict(w1=r.normal(size=(8, s)), b1=r.normal(size=8), w2=r.normal(size=(s, 8)), b2=r.normal(size=s))
+    (resp, steps, dlen), trace, _ = run(table, P, G, s, flt, 0.6, mask, eos)
+    assert G // s <= steps <= G
+    assert not np.any(resp == mask)
+    per_block = {}
+    for t in trace:
+        per_block[t["block"]] = per_block.get(t["block"], 0) + 1
+        before = t["X_before"]
+        assert t["sel"].sum() >= 1                      # progress every step
+        assert np.all(t["masked"][t["sel"]])            # only masked positions are unmasked
+    assert max(per_block.values()) <= s
+    for a, b in zip(trace[:-1], trace[1:]):
+        was = a["X_before"] != mask
+        assert np.all(b["X_before"][was] == a["X_before"][was])   # committed tokens never change
+    # committed positions feed the filter the constant 1.0: check through a filter that copies its input
+    ident = dict(w1=np.eye(s), b1=np.zeros(s), w2=np.eye(s), b2=np.zeros(s))
+    (_, _, _), tr2, _ = run(table, P, G, s, ident, 2.0, mask, eos)
+    for t in tr2:
+        expect = np.where(t["masked"], t["conf"], 1.0)
+        np.testing.assert_allclose(t["p"], 1 / (1 + np.exp(-expect)), rtol=1e-12)
+
+
+def test_identity_filter_is_fixed_confidence_threshold_decoding():
+    # W1 = I, W2 = k I: p_j = sigmoid(k c_j) which is monotone in c_j, so p_j > sigmoid(k c*) <=> c_j > c*.
+    P, G, s, V = 2, 32, 16, 6
+    mask, eos = V - 1, V - 2
+    table = rand_table(G, V, 8) * 3
+    table[:, eos] = -30.0
+    k, cstar = 4.0, 0.55
+    flt = dict(w1=np.eye(s), b1=np.zeros(s), w2=k * np.eye(s), b2=np.zeros(s))
+    tau = 1 / (1 + math.exp(-k * cstar))
+    (_, _, _), trace, _ = run(table, P, G, s, flt, tau, mask, eos)
+    saw_parallel = False
+    for t in trace:
+        want = t["masked"] & (t["conf"] > cstar)
+        top = int(np.argmax(np.where(t["masked"], t["conf"], -np.inf)))
+        want[top] = True
+        np.testing.assert_array_equal(t["sel"], want)
+        saw_parallel |= want.sum() > 1
+    assert saw_parallel
+
+
+def test_forced_top1_lowest_index_on_ties():
+    P, G, s, V = 1, 4, 4, 5
+    table = np.zeros((G, V))                            # every position has the same confidence
+    flt = dict(w1=np.zeros((2, s)), b1=np.zeros(2), w2=np.zeros((s, 2)), b2=np.full(s, -50.0))
+    (_, steps, _), trace, _ = run(table, P, G, s, flt, 0.5, V - 1, V - 2)
+    assert [int(np.nonzero(t["sel"])[0][0]) for t in trace] == [0, 1, 2, 3]
+
+
+# ----------------------------------------------------------------- Alg. 3 (EoTP)
+def test_eotp_stops_after_the_block_that_contains_eos():
+    P, G, s, V = 3, 128, 16, 40
+    mask, eos = V - 1, V - 2
+    table = rand_table(G, V, 9)
+    table[:, eos] = -30.0
+    g0 = 53
+    flt = dict(w1=np.zeros((2, s)), b1=np.zeros(2), w2=np.zeros((s, 2)), b2=np.full(s, -50.0))
+    bias = (eos, g0, 60.0)
+    (r_on, st_on, dl_on), _, _ = run(table, P, G, s, flt, 1.0, mask, eos, eotp=True, bias=bias)
+    (r_off, st_off, dl_off), _, _ = run(table, P, G, s, flt, 1.0, mask, eos, eotp=False, bias=bias)
+    nb = g0 // s + 1
+    assert st_on == nb * s and dl_on == nb * s
+    assert st_off == G and dl_off == G
+    np.testing.assert_array_equal(r_on[:dl_on], r_off[:dl_on])
+    assert np.all(r_on[dl_on:] == mask)                 # the undecoded tail keeps the mask id
+    assert np.all(r_on[g0:dl_on] == eos) and not np.any(r_on[:g0] == eos)
+    assert O.tail_all_eos(r_on, eos, dl_on)
+    # stopping exactly at the first block whose end is reached with an EOS present
+    first = int(np.nonzero(r_off == eos)[0][0])
+    assert dl_on == (first // s + 1) * s
+
+
+def test_eotp_without_eos_equals_off_and_prompt_eos_is_ignored():
+    P, G, s, V = 3, 48, 16, 30
+    mask, eos = V - 1, V - 2
+    table = rand_table(G, V, 10)
+    table[:, eos] = -30.0
+    flt = pass_all_filter(s)
+    m1, m2 = ScriptedModel(table, P), ScriptedModel(table, P)
+    prompt = np.array([eos, 1, eos])                    # EOS in the prompt must not stop decoding
+    a = O.generate(m1, prompt, G, s, mask, eos, flt, 0.5, eotp=True)
+    b = O.generate(m2, prompt, G, s, mask, eos, flt, 0.5, eotp=False)
+    np.testing.assert_array_equal(a[0], b[0])
+    assert a[1:] == b[1:] == (G // s, G)
+
+
+def test_bias_hook_positions():
+    z = np.zeros((4, 6))
+    out = O.apply_bias(z, 10, (2, 12, 5.0))
+    assert out[:, 2].tolist() == [0, 0, 5.0, 5.0] and out.sum() == 10.0
+    assert O.apply_bias(z, 10, None) is z
+
+
+def test_untrained_filter_bce_is_ln2():
+    # Eq. 6 with sigma(z) = 0.5 for every label is ln 2 ~ 0.69: the level the paper's curve starts at.
+    g = golden()
+    p = O.sigmoid(np.zeros(8))
+    y = np.array([0, 1, 1, 0, 1, 0, 0, 1.0])
+    bce = -np.mean(y * np.log(p) + (1 - y) * np.log(1 - p))
+    assert bce == pytest.approx(math.log(2), rel=1e-12)
+    assert abs(bce - g["bce_initial_loss_approx"]) < 0.02
+
+
+# ----------------------------------------------------------------- prefix-cache decode on a real (tiny) model
+def test_generate_with_prefix_cache_one_layer_equals_truncated_full_recompute():
+    from tests.test_oracle_model import tiny_shape, tiny_weights
+    s = tiny_shape(L=1, V=13)
+    w = tiny_weights(s, 11, scale=1.0)
+    m = O.Model(s, w, np.float64)
+    r = np.random.default_rng(12)
+    flt = dict(w1=r.normal(size=(4, 4)), b1=r.normal(size=4), w2=r.normal(size=(4, 4)), b2=r.normal(size=4))
+    prompt = np.array([1, 5, 2])
+    trace = []
+    resp, steps, dl = O.generate(m, prompt, 8, 4, s.mask_id, s.eos_id, flt, 0.6, prefix_cache=True, trace=trace)
+    assert not np.any(resp == s.mask_id) and 2 <= steps <= 8
+    for t in trace:
+        lo = 3 + t["block"] * 4
+        ref = m.forward(t["X_before"][:lo + 4], lo, 4)  # later blocks invisible
+        np.testing.assert_allclose(t["logits"], ref, rtol=1e-9, atol=1e-11)
