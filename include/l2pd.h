@@ -1,0 +1,165 @@
+/*
+ * l2pd.h -- C ABI of the Learn2PD decoding loop for AMD MI355X (gfx950).
+ *
+ * The library runs the semi-autoregressive masked-diffusion decoding loop of
+ * "Learning to Parallel" (arXiv 2509.25188): per denoising step one full
+ * bidirectional transformer forward (the paper's mask predictor M(X)), the
+ * greedy estimate and confidence of the active block (Eq. 3, Eq. 4), the
+ * learned filter f_theta on the block's confidences (Sec. 3.2), the unmask
+ * update (Alg. 2) and End-of-Text Prediction (Sec. 3.3, Alg. 3 in App. A).
+ *
+ * Conventions for every entry point
+ *   - Pointers named *_dev are device (HBM) memory owned by the caller; the
+ *     library never frees or reallocates them.  Pointers without that suffix
+ *     are host memory, read during the call only.
+ *   - `stream` is a hipStream_t passed as void*.  Kernels are enqueued on it;
+ *     outputs are valid once the caller has synchronised the stream.
+ *   - Return value: L2PD_OK (0) or a negative l2pd_status.  Argument checks
+ *     happen on the host before anything is launched.  Nothing throws or aborts.
+ *   - A context serves one call at a time (its workspace is shared state).
+ *   - Weight matrices are row-major [out_features, in_features]; their element
+ *     type is desc.dtype (fp32 or bf16).  Norm gains have the same type.
+ *   - Token ids are int32.  Sequences of a batch are stored [B, T] row-major,
+ *     T = prompt_len + gen_len.
+ */
+#ifndef L2PD_H
+#define L2PD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  L2PD_OK = 0,
+  L2PD_EINVAL = -1,   /* bad argument (NULL pointer, inconsistent sizes, NaN threshold, ...) */
+  L2PD_ENOMEM = -2,   /* workspace too small */
+  L2PD_EHIP = -3,     /* a HIP runtime call failed */
+  L2PD_ENOTIMPL = -4  /* shape outside what the kernels support */
+} l2pd_status;
+
+enum { L2PD_FP32 = 0, L2PD_BF16 = 1 };
+
+/* Shape of the mask predictor.  The paper uses LLaDA-8B as a black box; this is the LLaDA-style
+ * family: pre-norm blocks, RMSNorm, rotary embedding (rotate-half pairing, angle
+ * pos * rope_base^(-2i/head_dim)), bidirectional attention, SwiGLU FFN, untied LM head, no biases.
+ * bf16 models need d_model and d_ffn multiples of 64 and head_dim 64 or 128. */
+typedef struct {
+  int32_t n_layers, d_model, n_heads, head_dim, d_ffn, vocab;
+  int32_t mask_id, eos_id;      /* ids of [MASK] and of the end-of-text token, both in [0, vocab) */
+  float rope_base, rms_eps;
+  int32_t dtype;                /* L2PD_FP32 or L2PD_BF16: storage type of all weights */
+} l2pd_model_desc;
+
+/* Device pointers to the weights.  The per-layer members are HOST arrays of n_layers device
+ * pointers.  The library copies the pointer values at l2pd_create and reads the weights in place. */
+typedef struct {
+  const void* tok_emb_dev;          /* [vocab, d_model] */
+  const void* lm_head_dev;          /* [vocab, d_model] */
+  const void* final_norm_g_dev;     /* [d_model] */
+  const void* const* attn_norm_g;   /* each [d_model] */
+  const void* const* wq;            /* each [d_model, d_model] */
+  const void* const* wk;
+  const void* const* wv;
+  const void* const* wo;
+  const void* const* ffn_norm_g;    /* each [d_model] */
+  const void* const* w_gate;        /* each [d_ffn, d_model] */
+  const void* const* w_up;          /* each [d_ffn, d_model] */
+  const void* const* w_down;        /* each [d_model, d_ffn] */
+} l2pd_weights;
+
+/* The filter f_theta (Sec. 3.2; Sec. 4.1 "two-layer MLP"): p = sigmoid(W2 relu(W1 c + b1) + b2),
+ * c = the block's confidence vector.  All fp32, device memory.  in_dim must equal block_len. */
+typedef struct {
+  int32_t in_dim, hidden;           /* hidden <= 1024 */
+  const float* w1_dev;              /* [hidden, in_dim] */
+  const float* b1_dev;              /* [hidden] */
+  const float* w2_dev;              /* [in_dim, hidden] */
+  const float* b2_dev;              /* [in_dim] */
+} l2pd_filter;
+
+/* Workload hook: add `value` to the logit of `token_id` at generation positions >= gen_pos_from
+ * (position 0 = first generated token).  value == 0 disables it. */
+typedef struct {
+  int32_t token_id, gen_pos_from;
+  float value;
+} l2pd_logit_bias;
+
+/* Decode arguments of Alg. 2 / Alg. 3: generation length L_gen, block size s, threshold tau. */
+typedef struct {
+  int32_t gen_len, block_len;       /* gen_len % block_len == 0, block_len <= 256 */
+  float threshold;                  /* unmask position j when p_j > threshold (strict) */
+  int32_t eotp;                     /* 1: stop after the first finished block whose response holds eos_id */
+  int32_t use_prefix_cache;         /* 1: K/V of prompt + finished blocks cached, refreshed once per block
+                                       (Sec. 4.3, "Prefix Cache"); needs a context created for it */
+  l2pd_logit_bias bias;
+} l2pd_decode_cfg;
+
+typedef struct l2pd_ctx l2pd_ctx;
+
+/* Bytes of device workspace a context needs for batches <= max_batch and sequences <= max_seq
+ * tokens (prompt + generation).  Returns 0 if the description is invalid. */
+size_t l2pd_workspace_bytes(const l2pd_model_desc* desc, int32_t max_batch, int32_t max_seq,
+                            int32_t use_prefix_cache);
+
+/* Creates a context.  workspace_dev must stay valid and untouched by the caller until
+ * l2pd_destroy.  Host-only work: device-side tables are built by the first call that gets a stream. */
+int32_t l2pd_create(const l2pd_model_desc* desc, const l2pd_weights* weights, int32_t max_batch,
+                    int32_t max_seq, int32_t use_prefix_cache, void* workspace_dev,
+                    size_t workspace_bytes, l2pd_ctx** out);
+void l2pd_destroy(l2pd_ctx* ctx);
+
+/* M(X): one full bidirectional forward over tokens_dev [B, T]; writes the fp32 logits of positions
+ * row_begin .. row_begin+row_count-1 of every sequence to logits_out_dev [B, row_count, vocab].
+ * (Alg. 2, "conf, pre = M(X)", before the reduction over the vocabulary.) */
+int32_t l2pd_forward(l2pd_ctx* ctx, const int32_t* tokens_dev, int32_t B, int32_t T,
+                     int32_t row_begin, int32_t row_count, float* logits_out_dev, void* stream);
+
+/* One pass of the while-loop body of Alg. 2 for every sequence of the batch, on device:
+ * forward, confidence / greedy token of the active block (Eq. 3, Eq. 4; the mask id is excluded from
+ * the vocabulary, ties go to the lowest id), filter, unmask where p_j > threshold plus the masked
+ * position of highest confidence, block advance, EoTP check (Alg. 3) when the block completes.
+ *
+ * tokens_dev [B, prompt_len + gen_len] and state_dev [B, 3] = (block_idx, steps, done) are updated
+ * in place.  The batch advances in lock step: the active block is the smallest block_idx among
+ * sequences that are not done; a sequence that has finished that block idles (state unchanged).
+ * Optional taps (NULL to skip), all for the active block, written before the update:
+ *   logits_dev [B, s, vocab] fp32 (bias applied), conf_dev [B, s], pred_dev [B, s],
+ *   filt_dev [B, s] (filter output p), unmask_dev [B, s] (1 where unmasked by this step).
+ * With cfg.use_prefix_cache the call first reads state_dev back (it synchronises the stream) and
+ * rebuilds the prefix cache for the active block. */
+int32_t l2pd_denoise_step(l2pd_ctx* ctx, int32_t* tokens_dev, int32_t B, int32_t prompt_len,
+                          const l2pd_decode_cfg* cfg, const l2pd_filter* filter, int32_t* state_dev,
+                          float* logits_dev, float* conf_dev, int32_t* pred_dev, float* filt_dev,
+                          uint8_t* unmask_dev, void* stream);
+
+/* Alg. 2 / Alg. 3 for a batch of prompts [B, P].  Outputs:
+ *   tokens_out_dev [B, gen_len]: the response slice X[P : P+gen_len]; positions never decoded
+ *     because of an EoTP stop still hold mask_id;
+ *   steps_out_dev [B]: forwards in which the sequence still had a masked position in its active block;
+ *   decoded_len_out_dev [B]: (index of the last decoded block + 1) * block_len.
+ * The step loop, the block pointer and the stop flag live on the device; the host enqueues steps in
+ * small chunks and polls a flag between chunks, so the call returns when the last chunk is enqueued. */
+int32_t l2pd_generate(l2pd_ctx* ctx, const int32_t* prompt_dev, int32_t B, int32_t P,
+                      const l2pd_decode_cfg* cfg, const l2pd_filter* filter, int32_t* tokens_out_dev,
+                      int32_t* steps_out_dev, int32_t* decoded_len_out_dev, void* stream);
+
+/* Timing aid: kernel classes whose launches can be bracketed with HIP events on the launch stream. */
+enum {
+  L2PD_K_NONE = 0, L2PD_K_GEMM_QKV = 1, L2PD_K_GEMM_O = 2, L2PD_K_GEMM_GATEUP = 3,
+  L2PD_K_GEMM_DOWN = 4, L2PD_K_ATTN = 5, L2PD_K_LMHEAD = 6, L2PD_K_NORM = 7, L2PD_K_UPDATE = 8
+};
+/* Selects one kernel class (L2PD_K_NONE switches timing off) and clears the counters. */
+int32_t l2pd_profile_select(l2pd_ctx* ctx, int32_t kernel_class);
+/* Synchronises the recorded events and returns the number of timed launches of the selected class
+ * since the last select and the sum of their durations in milliseconds. */
+int32_t l2pd_profile_read(l2pd_ctx* ctx, int64_t* launches_out, double* total_ms_out);
+
+const char* l2pd_strerror(int32_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* L2PD_H */

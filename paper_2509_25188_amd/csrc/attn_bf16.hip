@@ -1,0 +1,220 @@
+// Bidirectional (non-causal) flash-style attention on bf16 MFMA for gfx950.
+//
+// Inputs are what the QKV GEMM epilogue leaves: rotated queries q [B*Tq, d], rotated keys
+// kstore [B, Tpad, d] and transposed values vtstore [B, H, Dh, Tpad].  A workgroup owns 32*NW
+// queries of one (sequence, head); each wavefront owns 32 of them.  Key/value tiles of 64 keys are
+// staged in LDS (XOR-swizzled rows, double buffered) and shared by the workgroup's wavefronts.
+//
+// The wave computes S^T = K Q^T (keys are MFMA rows, queries are columns), so that a lane holds
+// scores of ONE query: the row maximum is 31 register maxima plus one cross-lane exchange, and the
+// exponentiated scores are already laid out as the B operand of O^T = V^T P^T.  The key order
+// inside each 16-key MFMA step is the accumulator's (keys {4h..4h+3, 8+4h..8+4h+3} for lane half h);
+// V^T is read from LDS in that same order, which is legal because the contraction is a sum.
+#include "common.h"
+
+namespace l2pd {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+
+__device__ __forceinline__ unsigned int pack_bf16x2(float lo, float hi) {
+  unsigned int a = __float_as_uint(lo), b = __float_as_uint(hi);
+  a += 0x7fffu + ((a >> 16) & 1u);
+  b += 0x7fffu + ((b >> 16) & 1u);
+  return (a >> 16) | (b & 0xffff0000u);
+}
+
+template <int DH, int NW>
+__global__ void __launch_bounds__(NW * 64) k_attn_bf16(const bf16* __restrict__ q, const bf16* __restrict__ kstore,
+                                                       const bf16* __restrict__ vtstore, bf16* __restrict__ out,
+                                                       int B, int Tq, int Tk, int Tpad, int H, Gate g) {
+  if (gate_skip(g)) return;
+  constexpr int NT = NW * 64;
+  constexpr int KT = 64;                       // keys per LDS tile
+  constexpr int K_ROW = DH * 2;                // bytes per key row
+  constexpr int K_BYTES = KT * K_ROW;
+  constexpr int V_BYTES = DH * KT * 2;         // [DH rows][64 keys]
+  constexpr int STAGE = K_BYTES + V_BYTES;
+  constexpr int KCH = K_BYTES / 16 / NT, VCH = V_BYTES / 16 / NT;
+  static_assert(KCH * NT * 16 == K_BYTES && VCH * NT * 16 == V_BYTES, "tile/threads mismatch");
+  constexpr int KK = DH / 16;                  // MFMA steps over the feature dim
+  constexpr int FO = DH / 32;                  // output row fragments
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5, lj = lane & 31;
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int d = H * DH;
+  const int q0 = blockIdx.x * (32 * NW) + wave * 32;
+  const int qrow = min(q0 + lj, Tq - 1);
+
+  // Q as the B operand: lane (query lj, half hf) holds features kk*16 + hf*8 .. +7
+  bf16x8_t fq[KK];
+  {
+    const bf16* qp = q + ((size_t)b * Tq + qrow) * d + h * DH + hf * 8;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) fq[kk] = *reinterpret_cast<const bf16x8_t*>(qp + kk * 16);
+  }
+
+  const bf16* kbase = kstore + (size_t)b * Tpad * d + h * DH;
+  const bf16* vbase = vtstore + (size_t)(b * H + h) * DH * Tpad;
+  const bf16* srcK[KCH];
+  int dstK[KCH];
+#pragma unroll
+  for (int i = 0; i < KCH; ++i) {
+    int c = tid + i * NT;
+    int r = c / (DH / 8), cc = c % (DH / 8);
+    srcK[i] = kbase + (size_t)r * d + cc * 8;
+    dstK[i] = r * K_ROW + ((cc ^ (r & 7)) << 4);
+  }
+  const bf16* srcV[VCH];
+  int dstV[VCH];
+#pragma unroll
+  for (int i = 0; i < VCH; ++i) {
+    int c = tid + i * NT;
+    int r = c >> 3, cc = c & 7;
+    srcV[i] = vbase + (size_t)r * Tpad + cc * 8;
+    dstV[i] = K_BYTES + r * (KT * 2) + ((cc ^ (r & 7)) << 4);
+  }
+  u32x4 rk[KCH], rv[VCH];
+  auto gload = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < KCH; ++i) rk[i] = *reinterpret_cast<const u32x4*>(srcK[i] + (size_t)k0 * d);
+#pragma unroll
+    for (int i = 0; i < VCH; ++i) rv[i] = *reinterpret_cast<const u32x4*>(srcV[i] + k0);
+  };
+  auto sstore = [&](int stage) {
+    unsigned char* base = smem + stage * STAGE;
+#pragma unroll
+    for (int i = 0; i < KCH; ++i) *reinterpret_cast<u32x4*>(base + dstK[i]) = rk[i];
+#pragma unroll
+    for (int i = 0; i < VCH; ++i) *reinterpret_cast<u32x4*>(base + dstV[i]) = rv[i];
+  };
+
+  f32x16 o[FO];
+#pragma unroll
+  for (int f = 0; f < FO; ++f)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[f][r] = 0.f;
+  float m = -INFINITY, lsum = 0.f;
+  const float sc = rsqrtf((float)DH) * 1.4426950408889634f;   // softmax scale folded with log2(e)
+  const int key = lj & 7;
+
+  const int n_tiles = (Tk + KT - 1) / KT;
+  gload(0);
+  sstore(0);
+  __syncthreads();
+  for (int t = 0; t < n_tiles; ++t) {
+    const bool more = t + 1 < n_tiles;
+    if (more) gload((t + 1) * KT);
+    const unsigned char* base = smem + (t & 1) * STAGE;
+    const int k0 = t * KT;
+
+    // S^T for the two 32-key halves of the tile
+    f32x16 s[2];
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[sub][r] = 0.f;
+      const unsigned char* krow = base + (sub * 32 + lj) * K_ROW;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        bf16x8_t fk = *reinterpret_cast<const bf16x8_t*>(krow + (((kk * 2 + hf) ^ key) << 4));
+        s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk, fq[kk], s[sub], 0, 0, 0);
+      }
+    }
+    float tmax = -INFINITY;
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        int kidx = k0 + sub * 32 + (r >> 2) * 8 + hf * 4 + (r & 3);
+        float v = kidx < Tk ? s[sub][r] * sc : -INFINITY;
+        s[sub][r] = v;
+        tmax = fmaxf(tmax, v);
+      }
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+    const float mn = fmaxf(m, tmax);
+    const float alpha = exp2f(m - mn);       // m = -inf on the first tile gives 0
+    m = mn;
+    float ps = 0.f;
+    unsigned int pk[2][8];                   // bf16 pairs: [sub][4 per 16-key step * 2 steps]
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+      for (int r = 0; r < 16; r += 2) {
+        float p0 = exp2f(s[sub][r] - mn), p1 = exp2f(s[sub][r + 1] - mn);
+        ps += p0 + p1;
+        pk[sub][r >> 1] = pack_bf16x2(p0, p1);
+      }
+    lsum = lsum * alpha + ps;
+#pragma unroll
+    for (int f = 0; f < FO; ++f)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[f][r] *= alpha;
+
+    // O^T += V^T P^T, 16 keys per MFMA
+#pragma unroll
+    for (int m16 = 0; m16 < 4; ++m16) {
+      const int sub = m16 >> 1, mm = m16 & 1;
+      u32x4 pw = {pk[sub][mm * 4 + 0], pk[sub][mm * 4 + 1], pk[sub][mm * 4 + 2], pk[sub][mm * 4 + 3]};
+      bf16x8_t fp = __builtin_bit_cast(bf16x8_t, pw);
+#pragma unroll
+      for (int f = 0; f < FO; ++f) {
+        const unsigned char* vrow = base + K_BYTES + (f * 32 + lj) * (KT * 2) + hf * 8;
+        u32x2 v0 = *reinterpret_cast<const u32x2*>(vrow + (((m16 * 2) ^ key) << 4));
+        u32x2 v1 = *reinterpret_cast<const u32x2*>(vrow + (((m16 * 2 + 1) ^ key) << 4));
+        u32x4 vw = {v0.x, v0.y, v1.x, v1.y};
+        bf16x8_t fv = __builtin_bit_cast(bf16x8_t, vw);
+        o[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv, fp, o[f], 0, 0, 0);
+      }
+    }
+    if (more) sstore((t + 1) & 1);
+    __syncthreads();
+  }
+
+  const float l = lsum + __shfl_xor(lsum, 32, 64);
+  const float inv = 1.f / l;
+  if (q0 + lj < Tq) {
+    unsigned short* op = reinterpret_cast<unsigned short*>(out) + ((size_t)b * Tq + q0 + lj) * d + h * DH;
+#pragma unroll
+    for (int f = 0; f < FO; ++f)
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        u32x2 w;
+        w.x = pack_bf16x2(o[f][rq * 4 + 0] * inv, o[f][rq * 4 + 1] * inv);
+        w.y = pack_bf16x2(o[f][rq * 4 + 2] * inv, o[f][rq * 4 + 3] * inv);
+        *reinterpret_cast<u32x2*>(op + f * 32 + rq * 8 + hf * 4) = w;
+      }
+  }
+}
+
+template <int DH, int NW>
+static void launch(const bf16* q, const bf16* kstore, const bf16* vtstore, bf16* out, int B, int Tq, int Tk,
+                   int Tpad, int H, Gate g, hipStream_t s) {
+  auto kern = k_attn_bf16<DH, NW>;
+  constexpr int smem = 2 * (64 * DH * 2 + DH * 64 * 2);
+  static bool attr_done = false;
+  if (!attr_done) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    attr_done = true;
+  }
+  dim3 grid((Tq + 32 * NW - 1) / (32 * NW), H, B);
+  hipLaunchKernelGGL(kern, grid, dim3(NW * 64), smem, s, q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, g);
+}
+
+void launch_attn_bf16(const bf16* q, const bf16* kstore, const bf16* vtstore, bf16* out, int B, int Tq, int Tk,
+                      int Tpad, int H, int Dh, Gate g, hipStream_t s) {
+  const bool small = Tq <= 64;
+  if (Dh == 128) {
+    if (small) launch<128, 2>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, g, s);
+    else launch<128, 4>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, g, s);
+  } else {
+    if (small) launch<64, 2>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, g, s);
+    else launch<64, 4>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, g, s);
+  }
+}
+
+}  // namespace l2pd

@@ -1,0 +1,124 @@
+// Internal declarations shared by the HIP translation units of libl2pd.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_bf16.h>
+#include <stdint.h>
+
+#include "../../include/l2pd.h"
+
+namespace l2pd {
+
+typedef __hip_bfloat16 bf16;
+
+// Device control block (int32 words).  Written by k_prepare at the start of every step.
+enum { CTL_GB = 0, CTL_ALL_DONE = 1, CTL_ACTIVE = 2, CTL_WORDS = 8 };
+
+// Every kernel of a step is gated: once decoding has stopped (or, with the prefix cache, once the
+// block the host enqueued it for is finished) it returns at once, so steps that the host enqueued
+// ahead of the device's progress cost a launch and nothing else.
+struct Gate {
+  const int* ctl;   // nullptr: never skip
+  int expect_gb;    // >= 0: skip unless ctl[CTL_GB] == expect_gb
+};
+__device__ __forceinline__ bool gate_skip(const Gate& g) {
+  if (!g.ctl) return false;
+  if (g.ctl[CTL_ALL_DONE]) return true;
+  return g.expect_gb >= 0 && g.ctl[CTL_GB] != g.expect_gb;
+}
+
+// Maps a compact row index r (b * rows_per_seq + j) to a row of a [B, seq_stride] array:
+//   b * seq_stride + off_base + gb * off_per_gb + j,  gb read from the control block.
+struct RowMap {
+  int rows_per_seq, seq_stride, off_base, off_per_gb;
+};
+__device__ __forceinline__ int map_row(const RowMap& m, int r, const int* ctl) {
+  int gb = (m.off_per_gb && ctl) ? ctl[CTL_GB] : 0;
+  return (r / m.rows_per_seq) * m.seq_stride + m.off_base + gb * m.off_per_gb + (r % m.rows_per_seq);
+}
+
+// ---- small kernels (kernels_misc.hip) ----
+void launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t s);
+void launch_rope_table(float* cos_t, float* sin_t, int max_pos, int head_dim, float base, hipStream_t s);
+void launch_init_decode(int32_t* X, const int32_t* prompt, int B, int P, int G, int mask_id, int32_t* state,
+                        int* ctl, hipStream_t s);
+void launch_prepare(const int32_t* state, int B, int n_blocks, int* ctl, hipStream_t s);
+void launch_embed(float* h, const void* emb, int dtype, const int32_t* tokens, RowMap tokmap, int rows, int d,
+                  Gate g, hipStream_t s);
+// h (+= p0 + p1 when given; written back) -> y = rmsnorm(h) * gain, rows taken through `src`.
+void launch_rmsnorm(float* h, const float* p0, const float* p1, RowMap src, const void* gain, int dtype,
+                    void* y, int rows, int d, float eps, Gate g, hipStream_t s);
+struct UpdateArgs {
+  int32_t* X;            // [B, T]
+  int32_t* state;        // [B, 3]
+  int B, P, T, s, n_blocks, mask_id, eos_id, eotp;
+  const float* part_max; // [B*s, n_part]
+  const float* part_sum;
+  const int32_t* part_idx;
+  int n_part;
+  const float *w1, *b1, *w2, *b2;
+  int hidden;
+  float tau;
+  float* conf_out;       // optional taps [B, s]
+  int32_t* pred_out;
+  float* filt_out;
+  uint8_t* unmask_out;
+  int* ctl;
+};
+void launch_update(const UpdateArgs& a, Gate g, hipStream_t s);
+void launch_finalize(const int32_t* X, const int32_t* state, int B, int P, int G, int s_len, int32_t* tokens_out,
+                     int32_t* steps_out, int32_t* dlen_out, hipStream_t s);
+
+// ---- vocabulary reduction over materialised logits (fp32 path and the logits tap) ----
+struct BiasArgs {
+  int token_id, gen_pos_from, block_len;
+  float value;           // 0: off
+};
+// partials over column chunks of `chunk` logits: max, sum exp(x - max), argmax (lowest id on ties),
+// mask_id excluded.  logits [rows, V] are modified in place by the bias first.
+void launch_vocab_partials(float* logits, int rows, int V, int chunk, int mask_id, BiasArgs bias, float* part_max,
+                           float* part_sum, int32_t* part_idx, int n_part, Gate g, hipStream_t s);
+
+// ---- fp32 path (kernels_f32.hip) ----
+// C[M,N] (+)= A[M,K] * W[N,K]^T
+void launch_gemm_f32(const float* A, const float* W, float* C, int M, int N, int K, int accumulate, Gate g,
+                     hipStream_t s);
+// rotate q [rows, d] in place and copy/rotate k, v rows into the [B, Tmax, d] key/value stores at pos0 + t
+void launch_rope_store_f32(float* q, const float* k, const float* v, float* kstore, float* vstore, int B, int Tq,
+                           int pos0, int Tmax, int H, int Dh, const float* cos_t, const float* sin_t, Gate g,
+                           hipStream_t s);
+void launch_attn_f32(const float* q, const float* kstore, const float* vstore, float* out, int B, int Tq, int Tk,
+                     int Tmax, int H, int Dh, Gate g, hipStream_t s);
+void launch_swiglu_f32(const float* gate, const float* up, float* act, size_t n, Gate g, hipStream_t s);
+
+// ---- bf16 path ----
+struct QkvEpilogue {
+  bf16* q;               // [rows, d]
+  bf16* kstore;          // [B, Tpad, d]
+  bf16* vtstore;         // [B, H, Dh, Tpad]
+  const float *cos_t, *sin_t;  // [max_pos, Dh/2]
+  int Tq, pos0, Tpad, H, Dh, d;
+};
+void launch_gemm_qkv_bf16(const bf16* A, const bf16* wq, const bf16* wk, const bf16* wv, int M, int K,
+                          const QkvEpilogue& e, Gate g, hipStream_t s);
+// partial[z][M,N] = A[:, z-th K slice] * W[:, slice]^T, z < splits (1 or 2)
+void launch_gemm_partial_bf16(const bf16* A, const bf16* W, float* part0, float* part1, int M, int N, int K,
+                              int splits, Gate g, hipStream_t s);
+// act[M, F] = silu(A Wg^T) * (A Wu^T)
+void launch_gemm_swiglu_bf16(const bf16* A, const bf16* wg, const bf16* wu, bf16* act, int M, int F, int K, Gate g,
+                             hipStream_t s);
+struct LmHeadEpilogue {
+  float* logits;         // optional [M, V]
+  float* part_max;       // optional [M, n_part]
+  float* part_sum;
+  int32_t* part_idx;
+  int n_part;            // = V / 128 rounded up
+  int mask_id;
+  BiasArgs bias;         // applied when value != 0 (needs ctl for the active block)
+};
+int lmhead_n_part(int V);
+void launch_gemm_lmhead_bf16(const bf16* A, const bf16* W, int M, int V, int K, const LmHeadEpilogue& e, Gate g,
+                             hipStream_t s);
+void launch_attn_bf16(const bf16* q, const bf16* kstore, const bf16* vtstore, bf16* out, int B, int Tq, int Tk,
+                      int Tpad, int H, int Dh, Gate g, hipStream_t s);
+
+}  // namespace l2pd

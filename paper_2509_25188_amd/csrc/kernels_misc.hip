@@ -1,0 +1,340 @@
+// Small kernels of the decoding loop: embedding gather, RMSNorm (wavefront reduction), the
+// vocabulary reduction over materialised logits, the filter + unmask + EoTP update, loop control.
+#include "common.h"
+
+namespace l2pd {
+
+// ------------------------------------------------------------------------------------------------
+__global__ void k_fill_u32(uint32_t* p, size_t n, uint32_t v) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) p[i] = v;
+}
+void launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t s) {
+  if (!n) return;
+  size_t blocks = (n + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)blocks), dim3(256), 0, s, p, n, v);
+}
+
+// cos/sin of pos * base^(-2i/Dh), evaluated in double and stored as float.
+__global__ void k_rope_table(float* cos_t, float* sin_t, int max_pos, int half, int head_dim, float base) {
+  int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= max_pos * half) return;
+  int pos = idx / half, i = idx % half;
+  double inv = pow((double)base, -2.0 * (double)i / (double)head_dim);
+  double a = (double)pos * inv;
+  cos_t[idx] = (float)cos(a);
+  sin_t[idx] = (float)sin(a);
+}
+void launch_rope_table(float* cos_t, float* sin_t, int max_pos, int head_dim, float base, hipStream_t s) {
+  int half = head_dim / 2, n = max_pos * half;
+  hipLaunchKernelGGL(k_rope_table, dim3((n + 255) / 256), dim3(256), 0, s, cos_t, sin_t, max_pos, half, head_dim,
+                     base);
+}
+
+// X <- prompt || [MASK]^G ; state <- 0   (Alg. 2, initialisation of X)
+__global__ void k_init_decode(int32_t* X, const int32_t* prompt, int B, int P, int G, int mask_id, int32_t* state,
+                              int* ctl) {
+  int T = P + G;
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < B * T) {
+    int b = i / T, t = i % T;
+    X[i] = t < P ? prompt[b * P + t] : mask_id;
+  }
+  if (i < B * 3) state[i] = 0;
+  if (i < CTL_WORDS) ctl[i] = 0;
+}
+void launch_init_decode(int32_t* X, const int32_t* prompt, int B, int P, int G, int mask_id, int32_t* state,
+                        int* ctl, hipStream_t s) {
+  int n = B * (P + G);
+  if (n < 64) n = 64;
+  hipLaunchKernelGGL(k_init_decode, dim3((n + 255) / 256), dim3(256), 0, s, X, prompt, B, P, G, mask_id, state,
+                     ctl);
+}
+
+// Active block of the lock-step batch = smallest block index among sequences that are not done.
+__global__ void k_prepare(const int32_t* state, int B, int n_blocks, int* ctl) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    int gb = n_blocks, all_done = 1;
+    for (int b = 0; b < B; ++b) {
+      if (!state[b * 3 + 2]) {
+        all_done = 0;
+        int bi = state[b * 3 + 0];
+        gb = bi < gb ? bi : gb;
+      }
+    }
+    if (gb >= n_blocks) all_done = 1;
+    ctl[CTL_GB] = all_done ? (n_blocks > 0 ? n_blocks - 1 : 0) : gb;
+    ctl[CTL_ALL_DONE] = all_done;
+  }
+}
+void launch_prepare(const int32_t* state, int B, int n_blocks, int* ctl, hipStream_t s) {
+  hipLaunchKernelGGL(k_prepare, dim3(1), dim3(64), 0, s, state, B, n_blocks, ctl);
+}
+
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__device__ __forceinline__ float to_f(T v);
+template <>
+__device__ __forceinline__ float to_f<float>(float v) { return v; }
+template <>
+__device__ __forceinline__ float to_f<bf16>(bf16 v) { return __bfloat162float(v); }
+template <typename T>
+__device__ __forceinline__ T from_f(float v);
+template <>
+__device__ __forceinline__ float from_f<float>(float v) { return v; }
+template <>
+__device__ __forceinline__ bf16 from_f<bf16>(float v) { return __float2bfloat16(v); }
+
+template <typename T>
+__global__ void k_embed(float* h, const T* emb, const int32_t* tokens, RowMap tokmap, int rows, int d, Gate g) {
+  if (gate_skip(g)) return;
+  int r = blockIdx.x;
+  int tok = tokens[map_row(tokmap, r, g.ctl)];
+  const T* e = emb + (size_t)tok * d;
+  float* o = h + (size_t)r * d;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) o[i] = to_f<T>(e[i]);
+}
+void launch_embed(float* h, const void* emb, int dtype, const int32_t* tokens, RowMap tokmap, int rows, int d,
+                  Gate g, hipStream_t s) {
+  if (dtype == L2PD_FP32)
+    hipLaunchKernelGGL(k_embed<float>, dim3(rows), dim3(256), 0, s, h, (const float*)emb, tokens, tokmap, rows, d, g);
+  else
+    hipLaunchKernelGGL(k_embed<bf16>, dim3(rows), dim3(256), 0, s, h, (const bf16*)emb, tokens, tokmap, rows, d, g);
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// One wavefront per row: the row's sum of squares is a 64-lane butterfly, no LDS.
+// When partial buffers are given the residual update h += p0 + p1 (fixed order) is folded in.
+template <typename T>
+__global__ void k_rmsnorm(float* h, const float* p0, const float* p1, RowMap src, const T* gain, T* y, int rows,
+                          int d, float eps, Gate g) {
+  if (gate_skip(g)) return;
+  int lane = threadIdx.x & 63;
+  int r = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  size_t srow = (size_t)map_row(src, r, g.ctl);
+  float* x = h + srow * d;
+  const float* a0 = p0 ? p0 + srow * d : nullptr;
+  const float* a1 = p1 ? p1 + srow * d : nullptr;
+  float ss = 0.f;
+  for (int i = lane; i < d; i += 64) {
+    float v = x[i];
+    if (a0) {
+      v += a0[i];
+      if (a1) v += a1[i];
+      x[i] = v;
+    }
+    ss += v * v;
+  }
+  ss = wave_sum(ss);
+  float inv = rsqrtf(ss / (float)d + eps);
+  T* o = y + (size_t)r * d;
+  for (int i = lane; i < d; i += 64) o[i] = from_f<T>(x[i] * inv * to_f<T>(gain[i]));
+}
+void launch_rmsnorm(float* h, const float* p0, const float* p1, RowMap src, const void* gain, int dtype, void* y,
+                    int rows, int d, float eps, Gate g, hipStream_t s) {
+  dim3 grid((rows + 3) / 4), block(256);
+  if (dtype == L2PD_FP32)
+    hipLaunchKernelGGL(k_rmsnorm<float>, grid, block, 0, s, h, p0, p1, src, (const float*)gain, (float*)y, rows, d,
+                       eps, g);
+  else
+    hipLaunchKernelGGL(k_rmsnorm<bf16>, grid, block, 0, s, h, p0, p1, src, (const bf16*)gain, (bf16*)y, rows, d,
+                       eps, g);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Vocabulary reduction over materialised fp32 logits: per (row, column chunk) the running
+// (max, sum exp(x - max), argmax) triple of Eq. 3 / Eq. 4; the mask id is not a data token.
+__global__ void k_vocab_partials(float* logits, int rows, int V, int chunk, int mask_id, BiasArgs bias,
+                                 float* part_max, float* part_sum, int32_t* part_idx, int n_part, Gate g) {
+  if (gate_skip(g)) return;
+  __shared__ float s_m[256];
+  __shared__ int s_i[256];
+  __shared__ float s_s[256];
+  int p = blockIdx.x, r = blockIdx.y, tid = threadIdx.x;
+  float* row = logits + (size_t)r * V;
+  int c0 = p * chunk, c1 = min(V, c0 + chunk);
+  if (bias.value != 0.f && bias.token_id >= c0 && bias.token_id < c1 && tid == 0) {
+    int gb = g.ctl ? g.ctl[CTL_GB] : 0;
+    int genpos = gb * bias.block_len + (r % bias.block_len);
+    if (genpos >= bias.gen_pos_from) row[bias.token_id] += bias.value;
+  }
+  __syncthreads();
+  float m = -INFINITY;
+  int mi = 0x7fffffff;
+  for (int c = c0 + tid; c < c1; c += 256) {
+    float v = c == mask_id ? -INFINITY : row[c];
+    if (v > m || (v == m && c < mi)) { m = v; mi = c; }
+  }
+  s_m[tid] = m; s_i[tid] = mi;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (tid < o) {
+      float m2 = s_m[tid + o]; int i2 = s_i[tid + o];
+      if (m2 > s_m[tid] || (m2 == s_m[tid] && i2 < s_i[tid])) { s_m[tid] = m2; s_i[tid] = i2; }
+    }
+    __syncthreads();
+  }
+  float M = s_m[0];
+  float sum = 0.f;
+  for (int c = c0 + tid; c < c1; c += 256) {
+    float v = c == mask_id ? -INFINITY : row[c];
+    sum += (M == -INFINITY) ? 0.f : expf(v - M);
+  }
+  s_s[tid] = sum;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (tid < o) s_s[tid] += s_s[tid + o];
+    __syncthreads();
+  }
+  if (tid == 0) {
+    size_t o = (size_t)r * n_part + p;
+    part_max[o] = M; part_sum[o] = s_s[0]; part_idx[o] = s_i[0];
+  }
+}
+void launch_vocab_partials(float* logits, int rows, int V, int chunk, int mask_id, BiasArgs bias, float* part_max,
+                           float* part_sum, int32_t* part_idx, int n_part, Gate g, hipStream_t s) {
+  hipLaunchKernelGGL(k_vocab_partials, dim3(n_part, rows), dim3(256), 0, s, logits, rows, V, chunk, mask_id, bias,
+                     part_max, part_sum, part_idx, n_part, g);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Per sequence: combine the vocabulary partials into conf / pre (Eq. 3, Eq. 4), evaluate the filter
+// p = sigmoid(W2 relu(W1 c + b1) + b2) on the block's confidences (committed positions enter as 1.0),
+// unmask where p > tau plus the most confident masked position, advance the block, apply EoTP.
+__global__ void __launch_bounds__(256) k_update(UpdateArgs a, Gate g) {
+  if (gate_skip(g)) return;
+  __shared__ float s_conf[256];
+  __shared__ int s_pred[256];
+  __shared__ float s_cin[256];
+  __shared__ float s_hid[1024];
+  __shared__ unsigned char s_masked[256];
+  __shared__ unsigned char s_sel[256];
+  __shared__ int s_flag[4];
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int s = a.s;
+  const int gb = a.ctl[CTL_GB];
+  const int lo = a.P + gb * s;
+  int32_t* X = a.X + (size_t)b * a.T;
+  int32_t* st = a.state + b * 3;
+
+  for (int j = wave; j < s; j += 4) {
+    size_t base = (size_t)(b * s + j) * a.n_part;
+    float m = -INFINITY, sum = 0.f;
+    int idx = 0x7fffffff;
+    for (int p = lane; p < a.n_part; p += 64) {
+      float pm = a.part_max[base + p], ps = a.part_sum[base + p];
+      int pi = a.part_idx[base + p];
+      if (pm > m) {
+        sum = sum * (m == -INFINITY ? 0.f : expf(m - pm)) + ps;
+        m = pm; idx = pi;
+      } else if (pm > -INFINITY) {
+        sum += ps * expf(pm - m);
+        if (pm == m && pi < idx) idx = pi;
+      }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      float m2 = __shfl_xor(m, o, 64), s2 = __shfl_xor(sum, o, 64);
+      int i2 = __shfl_xor(idx, o, 64);
+      float M = fmaxf(m, m2);
+      float f1 = (m == -INFINITY) ? 0.f : expf(m - M), f2 = (m2 == -INFINITY) ? 0.f : expf(m2 - M);
+      sum = sum * f1 + s2 * f2;
+      if (m2 > m || (m2 == m && i2 < idx)) idx = i2;
+      m = M;
+    }
+    if (lane == 0) { s_conf[j] = 1.f / sum; s_pred[j] = idx; }
+  }
+  if (tid < 4) s_flag[tid] = 0;
+  __syncthreads();
+  if (tid < s) {
+    bool mk = X[lo + tid] == a.mask_id;
+    s_masked[tid] = mk;
+    s_cin[tid] = mk ? s_conf[tid] : 1.0f;
+    if (a.conf_out) a.conf_out[b * s + tid] = s_conf[tid];
+    if (a.pred_out) a.pred_out[b * s + tid] = s_pred[tid];
+    if (mk) atomicAdd(&s_flag[0], 1);   // integer count of masked positions
+  }
+  __syncthreads();
+  for (int t = tid; t < a.hidden; t += 256) {
+    float acc = a.b1[t];
+    const float* w = a.w1 + (size_t)t * s;
+    for (int j = 0; j < s; ++j) acc += w[j] * s_cin[j];
+    s_hid[t] = fmaxf(acc, 0.f);
+  }
+  __syncthreads();
+  if (tid < s) {
+    float z = a.b2[tid];
+    const float* w = a.w2 + (size_t)tid * a.hidden;
+    for (int t = 0; t < a.hidden; ++t) z += w[t] * s_hid[t];
+    float p = 1.f / (1.f + expf(-z));
+    if (a.filt_out) a.filt_out[b * s + tid] = p;
+    s_sel[tid] = s_masked[tid] && (p > a.tau);
+  }
+  __syncthreads();
+  const int n_masked = s_flag[0];
+  const bool mine = !st[2] && st[0] == gb;
+  if (tid == 0 && n_masked > 0) {
+    float best = -INFINITY;
+    int bj = -1;
+    for (int j = 0; j < s; ++j)
+      if (s_masked[j] && (bj < 0 || s_conf[j] > best)) { best = s_conf[j]; bj = j; }
+    s_sel[bj] = 1;
+  }
+  __syncthreads();
+  if (tid < s) {
+    bool sel = mine && s_sel[tid];
+    if (a.unmask_out) a.unmask_out[b * s + tid] = sel ? 1 : 0;
+    if (sel) {
+      X[lo + tid] = s_pred[tid];
+      atomicAdd(&s_flag[1], 1);
+    }
+  }
+  __syncthreads();
+  if (!mine) return;
+  const bool complete = s_flag[1] == n_masked;   // also true when nothing was masked
+  if (complete && a.eotp) {
+    for (int t = a.P + tid; t < lo + s; t += 256)
+      if (X[t] == a.eos_id) s_flag[2] = 1;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    if (n_masked > 0) st[1] += 1;
+    if (complete) {
+      st[0] = gb + 1;
+      if (s_flag[2] || gb + 1 >= a.n_blocks) st[2] = 1;
+    }
+  }
+}
+void launch_update(const UpdateArgs& a, Gate g, hipStream_t s) {
+  hipLaunchKernelGGL(k_update, dim3(a.B), dim3(256), 0, s, a, g);
+}
+
+// response_i = X[P : P+G], steps, decoded length
+__global__ void k_finalize(const int32_t* X, const int32_t* state, int B, int P, int G, int s_len,
+                           int32_t* tokens_out, int32_t* steps_out, int32_t* dlen_out) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < B * G) {
+    int b = i / G, t = i % G;
+    tokens_out[i] = X[(size_t)b * (P + G) + P + t];
+  }
+  if (i < B) {
+    if (steps_out) steps_out[i] = state[i * 3 + 1];
+    if (dlen_out) dlen_out[i] = state[i * 3 + 0] * s_len;
+  }
+}
+void launch_finalize(const int32_t* X, const int32_t* state, int B, int P, int G, int s_len, int32_t* tokens_out,
+                     int32_t* steps_out, int32_t* dlen_out, hipStream_t s) {
+  int n = B * G;
+  hipLaunchKernelGGL(k_finalize, dim3((n + 255) / 256), dim3(256), 0, s, X, state, B, P, G, s_len, tokens_out,
+                     steps_out, dlen_out);
+}
+
+}  // namespace l2pd

@@ -1,0 +1,583 @@
+// C ABI of libl2pd: argument checks, workspace layout, and the launch sequences of
+// M(X) (forward), one denoising step (Alg. 2 loop body) and the whole decode (Alg. 2 / Alg. 3).
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <vector>
+
+#include "common.h"
+
+using namespace l2pd;
+
+namespace {
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct Carver {
+  size_t off = 0;
+  size_t take(size_t bytes) {
+    size_t o = off;
+    off = align_up(off + bytes, 256);
+    return o;
+  }
+};
+
+struct Layout {
+  // offsets into the workspace
+  size_t cos_t, sin_t, ctl, state, X, h, xn, q, attn, act, part0, part1, kstore, vstore, tmp_k, tmp_v, gate_up,
+      xn_head, logits, part_max, part_sum, part_idx, conf, pred, total;
+  size_t kv_layer_stride_k, kv_layer_stride_v;
+  int Tpad, n_part, lm_chunk;
+};
+
+struct ProfileEv {
+  hipEvent_t a, b;
+};
+
+}  // namespace
+
+struct l2pd_ctx {
+  l2pd_model_desc m;
+  std::vector<const void*> attn_g, wq, wk, wv, wo, ffn_g, wg, wu, wd;
+  const void *tok_emb, *lm_head, *final_g;
+  int max_batch, max_seq, cache;
+  unsigned char* ws;
+  size_t ws_bytes;
+  Layout L;
+  bool device_ready = false;
+  // host side of the generate loop
+  int* pinned = nullptr;                 // polled copies of the control block
+  hipEvent_t poll_ev[2] = {nullptr, nullptr};
+  // timing aid
+  int prof_class = 0;
+  std::vector<ProfileEv> prof;
+  std::vector<ProfileEv> prof_pool;
+  int last_hip_error = 0;
+  int pend_splits = 0;   // bf16: split-K partials of the last down projection still to be folded into h
+
+  template <typename T>
+  T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
+};
+
+namespace {
+
+bool desc_ok(const l2pd_model_desc* d) {
+  if (!d) return false;
+  if (d->n_layers < 1 || d->d_model < 1 || d->n_heads < 1 || d->head_dim < 2 || d->d_ffn < 1 || d->vocab < 2)
+    return false;
+  if (d->n_heads * d->head_dim != d->d_model) return false;
+  if (d->head_dim % 2) return false;
+  if (d->mask_id < 0 || d->mask_id >= d->vocab || d->eos_id < 0 || d->eos_id >= d->vocab) return false;
+  if (d->mask_id == d->eos_id) return false;
+  if (!(d->rope_base > 0.f) || !(d->rms_eps >= 0.f)) return false;
+  if (d->dtype != L2PD_FP32 && d->dtype != L2PD_BF16) return false;
+  return true;
+}
+
+int desc_supported(const l2pd_model_desc* d) {
+  if (d->dtype == L2PD_BF16) {
+    if (d->d_model % 64 || d->d_ffn % 64) return L2PD_ENOTIMPL;
+    if (d->head_dim != 64 && d->head_dim != 128) return L2PD_ENOTIMPL;
+  } else {
+    if (d->head_dim > 256) return L2PD_ENOTIMPL;
+  }
+  return L2PD_OK;
+}
+
+Layout make_layout(const l2pd_model_desc& m, int max_batch, int max_seq, int cache) {
+  Layout L = {};
+  Carver c;
+  const size_t es = m.dtype == L2PD_FP32 ? 4 : 2;
+  const size_t rows = (size_t)max_batch * max_seq;
+  const size_t d = m.d_model, F = m.d_ffn, V = m.vocab;
+  L.Tpad = (int)align_up(max_seq, 64);
+  L.lm_chunk = 1024;
+  L.n_part = m.dtype == L2PD_FP32 ? (int)((V + L.lm_chunk - 1) / L.lm_chunk) : lmhead_n_part((int)V);
+  const size_t head_rows = (size_t)max_batch * 256;   // block_len <= 256
+  L.cos_t = c.take((size_t)L.Tpad * (m.head_dim / 2) * 4);
+  L.sin_t = c.take((size_t)L.Tpad * (m.head_dim / 2) * 4);
+  L.ctl = c.take(CTL_WORDS * 4);
+  L.state = c.take((size_t)max_batch * 3 * 4);
+  L.X = c.take(rows * 4);
+  L.h = c.take(rows * d * 4);
+  L.xn = c.take(rows * d * es);
+  L.q = c.take(rows * d * es);
+  L.attn = c.take(rows * d * es);
+  L.act = c.take(rows * F * es);
+  const size_t kv_one = (size_t)max_batch * L.Tpad * d * es;
+  const size_t n_kv = cache ? m.n_layers : 1;
+  L.kv_layer_stride_k = kv_one;
+  L.kv_layer_stride_v = kv_one;
+  L.kstore = c.take(kv_one * n_kv);
+  L.vstore = c.take(kv_one * n_kv);
+  if (m.dtype == L2PD_FP32) {
+    L.tmp_k = c.take(rows * d * 4);
+    L.tmp_v = c.take(rows * d * 4);
+    L.gate_up = c.take(rows * F * 4 * 2);
+    L.logits = c.take(head_rows * V * 4);
+  } else {
+    L.part0 = c.take(rows * d * 4);
+    L.part1 = c.take(rows * d * 4);
+  }
+  L.xn_head = c.take(rows * d * es);   // l2pd_forward may ask for every row
+  L.part_max = c.take(head_rows * L.n_part * 4);
+  L.part_sum = c.take(head_rows * L.n_part * 4);
+  L.part_idx = c.take(head_rows * L.n_part * 4);
+  L.conf = c.take(head_rows * 4);
+  L.pred = c.take(head_rows * 4);
+  L.total = c.off;
+  return L;
+}
+
+#define HIP_TRY(ctx, expr)                       \
+  do {                                           \
+    hipError_t e_ = (expr);                      \
+    if (e_ != hipSuccess) {                      \
+      (ctx)->last_hip_error = (int)e_;           \
+      return L2PD_EHIP;                          \
+    }                                            \
+  } while (0)
+
+int ensure_device(l2pd_ctx* c, hipStream_t s) {
+  if (c->device_ready) return L2PD_OK;
+  // Zero the workspace once: padded key/value slots must hold finite numbers.
+  launch_fill_u32(reinterpret_cast<uint32_t*>(c->ws), c->L.total / 4, 0u, s);
+  launch_rope_table(c->at<float>(c->L.cos_t), c->at<float>(c->L.sin_t), c->L.Tpad, c->m.head_dim, c->m.rope_base, s);
+  HIP_TRY(c, hipGetLastError());
+  c->device_ready = true;
+  return L2PD_OK;
+}
+
+// ---- timing aid ----
+struct Timed {
+  l2pd_ctx* c;
+  hipStream_t s;
+  bool on;
+  ProfileEv ev;
+  Timed(l2pd_ctx* c_, int cls, hipStream_t s_) : c(c_), s(s_), on(c_->prof_class == cls && cls != 0) {
+    if (!on) return;
+    if (!c->prof_pool.empty()) {
+      ev = c->prof_pool.back();
+      c->prof_pool.pop_back();
+    } else if (hipEventCreate(&ev.a) != hipSuccess || hipEventCreate(&ev.b) != hipSuccess) {
+      on = false;
+      return;
+    }
+    (void)hipEventRecord(ev.a, s);
+  }
+  ~Timed() {
+    if (!on) return;
+    (void)hipEventRecord(ev.b, s);
+    c->prof.push_back(ev);
+  }
+};
+
+// One transformer pass over `B` sequences with `Tq` rows each at absolute positions pos0 .. pos0+Tq-1,
+// attending to keys 0 .. Tk-1 of the key/value stores (which this pass fills at pos0 .. pos0+Tq-1).
+struct Pass {
+  int B, Tq, pos0, Tk;
+  int Tfull;            // row length of the token array
+  const int32_t* tokens;
+  bool per_layer_kv;    // prefix cache: one K/V store per layer
+  bool kv_only_last;    // refresh pass: the last layer only has to leave its K/V
+};
+
+void run_layers(l2pd_ctx* c, const Pass& p, Gate g, hipStream_t s) {
+  const l2pd_model_desc& m = c->m;
+  const Layout& L = c->L;
+  const int rows = p.B * p.Tq, d = m.d_model, F = m.d_ffn, H = m.n_heads, Dh = m.head_dim;
+  const RowMap ident = {rows, 0, 0, 0};
+  float* h = c->at<float>(L.h);
+  launch_embed(h, c->tok_emb, m.dtype, p.tokens, RowMap{p.Tq, p.Tfull, p.pos0, 0}, rows, d, g, s);
+  const float* cos_t = c->at<float>(L.cos_t);
+  const float* sin_t = c->at<float>(L.sin_t);
+  bool pending = false;   // bf16: split-K partials of the previous projection not yet folded into h
+  int pend_splits = 0;
+  for (int l = 0; l < m.n_layers; ++l) {
+    const size_t kvo_k = p.per_layer_kv ? L.kv_layer_stride_k * l : 0;
+    const size_t kvo_v = p.per_layer_kv ? L.kv_layer_stride_v * l : 0;
+    if (m.dtype == L2PD_FP32) {
+      float* xn = c->at<float>(L.xn);
+      float* q = c->at<float>(L.q);
+      float* ks = reinterpret_cast<float*>(c->ws + L.kstore + kvo_k);
+      float* vs = reinterpret_cast<float*>(c->ws + L.vstore + kvo_v);
+      { Timed t(c, L2PD_K_NORM, s);
+        launch_rmsnorm(h, nullptr, nullptr, ident, c->attn_g[l], m.dtype, xn, rows, d, m.rms_eps, g, s); }
+      { Timed t(c, L2PD_K_GEMM_QKV, s);
+        launch_gemm_f32(xn, (const float*)c->wq[l], q, rows, d, d, 0, g, s);
+        launch_gemm_f32(xn, (const float*)c->wk[l], c->at<float>(L.tmp_k), rows, d, d, 0, g, s);
+        launch_gemm_f32(xn, (const float*)c->wv[l], c->at<float>(L.tmp_v), rows, d, d, 0, g, s);
+        launch_rope_store_f32(q, c->at<float>(L.tmp_k), c->at<float>(L.tmp_v), ks, vs, p.B, p.Tq, p.pos0, L.Tpad, H,
+                              Dh, cos_t, sin_t, g, s); }
+      if (p.kv_only_last && l + 1 == m.n_layers) break;
+      { Timed t(c, L2PD_K_ATTN, s);
+        launch_attn_f32(q, ks, vs, c->at<float>(L.attn), p.B, p.Tq, p.Tk, L.Tpad, H, Dh, g, s); }
+      { Timed t(c, L2PD_K_GEMM_O, s);
+        launch_gemm_f32(c->at<float>(L.attn), (const float*)c->wo[l], h, rows, d, d, 1, g, s); }
+      { Timed t(c, L2PD_K_NORM, s);
+        launch_rmsnorm(h, nullptr, nullptr, ident, c->ffn_g[l], m.dtype, xn, rows, d, m.rms_eps, g, s); }
+      float* gt = c->at<float>(L.gate_up);
+      float* up = gt + (size_t)rows * F;
+      { Timed t(c, L2PD_K_GEMM_GATEUP, s);
+        launch_gemm_f32(xn, (const float*)c->wg[l], gt, rows, F, d, 0, g, s);
+        launch_gemm_f32(xn, (const float*)c->wu[l], up, rows, F, d, 0, g, s);
+        launch_swiglu_f32(gt, up, c->at<float>(L.act), (size_t)rows * F, g, s); }
+      { Timed t(c, L2PD_K_GEMM_DOWN, s);
+        launch_gemm_f32(c->at<float>(L.act), (const float*)c->wd[l], h, rows, d, F, 1, g, s); }
+    } else {
+      bf16* xn = c->at<bf16>(L.xn);
+      bf16* q = c->at<bf16>(L.q);
+      bf16* ks = reinterpret_cast<bf16*>(c->ws + L.kstore + kvo_k);
+      bf16* vts = reinterpret_cast<bf16*>(c->ws + L.vstore + kvo_v);
+      float* p0 = c->at<float>(L.part0);
+      float* p1 = c->at<float>(L.part1);
+      { Timed t(c, L2PD_K_NORM, s);
+        launch_rmsnorm(h, pending ? p0 : nullptr, (pending && pend_splits > 1) ? p1 : nullptr, ident, c->attn_g[l],
+                       m.dtype, xn, rows, d, m.rms_eps, g, s); }
+      pending = false;
+      QkvEpilogue e = {q, ks, vts, cos_t, sin_t, p.Tq, p.pos0, L.Tpad, H, Dh, d};
+      { Timed t(c, L2PD_K_GEMM_QKV, s);
+        launch_gemm_qkv_bf16(xn, (const bf16*)c->wq[l], (const bf16*)c->wk[l], (const bf16*)c->wv[l], rows, d, e, g,
+                             s); }
+      if (p.kv_only_last && l + 1 == m.n_layers) break;
+      bf16* ao = c->at<bf16>(L.attn);
+      { Timed t(c, L2PD_K_ATTN, s);
+        launch_attn_bf16(q, ks, vts, ao, p.B, p.Tq, p.Tk, L.Tpad, H, Dh, g, s); }
+      // Few row tiles leave half of the CUs idle on the [d, d] and [d, F] projections: split K in two.
+      const int tiles = ((rows + 127) / 128) * (d / 128);
+      int so = (tiles < 256 && (d / 64) % 2 == 0) ? 2 : 1;
+      int sd = (tiles < 256 && (F / 64) % 2 == 0) ? 2 : 1;
+      { Timed t(c, L2PD_K_GEMM_O, s);
+        launch_gemm_partial_bf16(ao, (const bf16*)c->wo[l], p0, p1, rows, d, d, so, g, s); }
+      { Timed t(c, L2PD_K_NORM, s);
+        launch_rmsnorm(h, p0, so > 1 ? p1 : nullptr, ident, c->ffn_g[l], m.dtype, xn, rows, d, m.rms_eps, g, s); }
+      bf16* act = c->at<bf16>(L.act);
+      { Timed t(c, L2PD_K_GEMM_GATEUP, s);
+        launch_gemm_swiglu_bf16(xn, (const bf16*)c->wg[l], (const bf16*)c->wu[l], act, rows, F, d, g, s); }
+      { Timed t(c, L2PD_K_GEMM_DOWN, s);
+        launch_gemm_partial_bf16(act, (const bf16*)c->wd[l], p0, p1, rows, d, F, sd, g, s); }
+      pending = true;
+      pend_splits = sd;
+    }
+  }
+  // bf16: the last down projection's partials are folded in by the final norm (see run_head)
+  c->pend_splits = pending ? pend_splits : 0;
+}
+
+// Final RMSNorm of the selected rows + LM head.  Produces the vocabulary partials (and optionally
+// the fp32 logits) of `n_rows_per_seq` rows per sequence, taken from h through `src`.
+void run_head(l2pd_ctx* c, int B, int n_rows_per_seq, RowMap src, float* logits_out, bool want_parts,
+              BiasArgs bias, Gate g, hipStream_t s) {
+  const l2pd_model_desc& m = c->m;
+  const Layout& L = c->L;
+  const int d = m.d_model, V = m.vocab, hr = B * n_rows_per_seq;
+  float* h = c->at<float>(L.h);
+  if (m.dtype == L2PD_FP32) {
+    float* xh = c->at<float>(L.xn_head);
+    { Timed t(c, L2PD_K_NORM, s);
+      launch_rmsnorm(h, nullptr, nullptr, src, c->final_g, m.dtype, xh, hr, d, m.rms_eps, g, s); }
+    float* lg = logits_out ? logits_out : c->at<float>(L.logits);
+    Timed t(c, L2PD_K_LMHEAD, s);
+    launch_gemm_f32(xh, (const float*)c->lm_head, lg, hr, V, d, 0, g, s);
+    if (want_parts)
+      launch_vocab_partials(lg, hr, V, L.lm_chunk, m.mask_id, bias, c->at<float>(L.part_max),
+                            c->at<float>(L.part_sum), c->at<int32_t>(L.part_idx), L.n_part, g, s);
+  } else {
+    // fold the last down projection's split-K partials into every row of h first (fixed order)
+    bf16* xh = c->at<bf16>(L.xn_head);
+    const int sd = c->pend_splits;
+    { Timed t(c, L2PD_K_NORM, s);
+      launch_rmsnorm(h, sd > 0 ? c->at<float>(L.part0) : nullptr, sd > 1 ? c->at<float>(L.part1) : nullptr, src,
+                     c->final_g, m.dtype, xh, hr, d, m.rms_eps, g, s); }
+    LmHeadEpilogue e = {};
+    e.logits = logits_out;
+    if (want_parts) {
+      e.part_max = c->at<float>(L.part_max);
+      e.part_sum = c->at<float>(L.part_sum);
+      e.part_idx = c->at<int32_t>(L.part_idx);
+    }
+    e.n_part = L.n_part;
+    e.mask_id = m.mask_id;
+    e.bias = bias;
+    Timed t(c, L2PD_K_LMHEAD, s);
+    launch_gemm_lmhead_bf16(xh, (const bf16*)c->lm_head, hr, V, d, e, g, s);
+  }
+}
+
+int check_decode_args(const l2pd_ctx* c, int B, int P, const l2pd_decode_cfg* cfg, const l2pd_filter* f) {
+  if (!c || !cfg || !f) return L2PD_EINVAL;
+  if (B < 1 || B > c->max_batch || P < 1) return L2PD_EINVAL;
+  if (cfg->gen_len < 1 || cfg->block_len < 1 || cfg->block_len > 256) return L2PD_EINVAL;
+  if (cfg->gen_len % cfg->block_len) return L2PD_EINVAL;
+  if ((long long)P + cfg->gen_len > c->max_seq) return L2PD_EINVAL;
+  if (f->in_dim != cfg->block_len || f->hidden < 1 || f->hidden > 1024) return L2PD_EINVAL;
+  if (!f->w1_dev || !f->b1_dev || !f->w2_dev || !f->b2_dev) return L2PD_EINVAL;
+  if (isnan(cfg->threshold)) return L2PD_EINVAL;
+  if (cfg->use_prefix_cache && !c->cache) return L2PD_EINVAL;
+  if (cfg->bias.value != 0.f && (cfg->bias.token_id < 0 || cfg->bias.token_id >= c->m.vocab)) return L2PD_EINVAL;
+  if (isnan(cfg->bias.value)) return L2PD_EINVAL;
+  return L2PD_OK;
+}
+
+struct StepTaps {
+  float* logits;
+  float* conf;
+  int32_t* pred;
+  float* filt;
+  uint8_t* unmask;
+};
+
+// Rebuild the prefix cache for block gb: K/V of a forward over X[0 : P + gb*s] alone.
+void run_refresh(l2pd_ctx* c, const int32_t* X, int B, int P, const l2pd_decode_cfg* cfg, int gb, Gate g,
+                 hipStream_t s) {
+  const int cpos = P + gb * cfg->block_len;
+  Pass p = {B, cpos, 0, cpos, P + cfg->gen_len, X, true, true};
+  run_layers(c, p, g, s);
+}
+
+// One denoising step for the lock-step batch.  host_gb >= 0 is required with the prefix cache.
+void run_step(l2pd_ctx* c, int32_t* X, int B, int P, const l2pd_decode_cfg* cfg, const l2pd_filter* f,
+              int32_t* state, int host_gb, const StepTaps& taps, hipStream_t s) {
+  const Layout& L = c->L;
+  const int sl = cfg->block_len, T = P + cfg->gen_len, nb = cfg->gen_len / sl;
+  int* ctl = c->at<int>(L.ctl);
+  launch_prepare(state, B, nb, ctl, s);
+  Gate g = {ctl, cfg->use_prefix_cache ? host_gb : -1};
+  BiasArgs bias = {cfg->bias.token_id, cfg->bias.gen_pos_from, sl, cfg->bias.value};
+  if (cfg->use_prefix_cache) {
+    const int cpos = P + host_gb * sl;
+    Pass p = {B, sl, cpos, cpos + sl, T, X, true, false};
+    run_layers(c, p, g, s);
+    run_head(c, B, sl, RowMap{B * sl, 0, 0, 0}, taps.logits, true, bias, g, s);
+  } else {
+    Pass p = {B, T, 0, T, T, X, false, false};
+    run_layers(c, p, g, s);
+    run_head(c, B, sl, RowMap{sl, T, P, sl}, taps.logits, true, bias, g, s);
+  }
+  UpdateArgs u = {};
+  u.X = X; u.state = state; u.B = B; u.P = P; u.T = T; u.s = sl; u.n_blocks = nb;
+  u.mask_id = c->m.mask_id; u.eos_id = c->m.eos_id; u.eotp = cfg->eotp;
+  u.part_max = c->at<float>(L.part_max); u.part_sum = c->at<float>(L.part_sum);
+  u.part_idx = c->at<int32_t>(L.part_idx); u.n_part = L.n_part;
+  u.w1 = f->w1_dev; u.b1 = f->b1_dev; u.w2 = f->w2_dev; u.b2 = f->b2_dev; u.hidden = f->hidden;
+  u.tau = cfg->threshold;
+  u.conf_out = taps.conf; u.pred_out = taps.pred; u.filt_out = taps.filt; u.unmask_out = taps.unmask;
+  u.ctl = ctl;
+  Timed t(c, L2PD_K_UPDATE, s);
+  launch_update(u, g, s);
+}
+
+}  // namespace
+
+// =================================================================================================
+extern "C" {
+
+const char* l2pd_strerror(int32_t st) {
+  switch (st) {
+    case L2PD_OK: return "ok";
+    case L2PD_EINVAL: return "invalid argument";
+    case L2PD_ENOMEM: return "workspace too small";
+    case L2PD_EHIP: return "HIP runtime error";
+    case L2PD_ENOTIMPL: return "shape not supported by the kernels";
+    default: return "unknown status";
+  }
+}
+
+size_t l2pd_workspace_bytes(const l2pd_model_desc* desc, int32_t max_batch, int32_t max_seq,
+                            int32_t use_prefix_cache) {
+  if (!desc_ok(desc) || desc_supported(desc) != L2PD_OK || max_batch < 1 || max_seq < 2) return 0;
+  return make_layout(*desc, max_batch, max_seq, use_prefix_cache).total;
+}
+
+int32_t l2pd_create(const l2pd_model_desc* desc, const l2pd_weights* w, int32_t max_batch, int32_t max_seq,
+                    int32_t use_prefix_cache, void* workspace_dev, size_t workspace_bytes, l2pd_ctx** out) {
+  if (!out) return L2PD_EINVAL;
+  *out = nullptr;
+  if (!desc_ok(desc) || !w || !workspace_dev || max_batch < 1 || max_seq < 2) return L2PD_EINVAL;
+  int sup = desc_supported(desc);
+  if (sup != L2PD_OK) return sup;
+  if (!w->tok_emb_dev || !w->lm_head_dev || !w->final_norm_g_dev || !w->attn_norm_g || !w->wq || !w->wk || !w->wv ||
+      !w->wo || !w->ffn_norm_g || !w->w_gate || !w->w_up || !w->w_down)
+    return L2PD_EINVAL;
+  for (int l = 0; l < desc->n_layers; ++l)
+    if (!w->attn_norm_g[l] || !w->wq[l] || !w->wk[l] || !w->wv[l] || !w->wo[l] || !w->ffn_norm_g[l] ||
+        !w->w_gate[l] || !w->w_up[l] || !w->w_down[l])
+      return L2PD_EINVAL;
+  if ((uintptr_t)workspace_dev % 256) return L2PD_EINVAL;
+  Layout L = make_layout(*desc, max_batch, max_seq, use_prefix_cache);
+  if (workspace_bytes < L.total) return L2PD_ENOMEM;
+  l2pd_ctx* c = new (std::nothrow) l2pd_ctx();
+  if (!c) return L2PD_ENOMEM;
+  c->m = *desc;
+  c->tok_emb = w->tok_emb_dev; c->lm_head = w->lm_head_dev; c->final_g = w->final_norm_g_dev;
+  const int n = desc->n_layers;
+  c->attn_g.assign(w->attn_norm_g, w->attn_norm_g + n);
+  c->wq.assign(w->wq, w->wq + n); c->wk.assign(w->wk, w->wk + n); c->wv.assign(w->wv, w->wv + n);
+  c->wo.assign(w->wo, w->wo + n); c->ffn_g.assign(w->ffn_norm_g, w->ffn_norm_g + n);
+  c->wg.assign(w->w_gate, w->w_gate + n); c->wu.assign(w->w_up, w->w_up + n);
+  c->wd.assign(w->w_down, w->w_down + n);
+  c->max_batch = max_batch; c->max_seq = max_seq; c->cache = use_prefix_cache ? 1 : 0;
+  c->ws = static_cast<unsigned char*>(workspace_dev);
+  c->ws_bytes = workspace_bytes;
+  c->L = L;
+  *out = c;
+  return L2PD_OK;
+}
+
+void l2pd_destroy(l2pd_ctx* c) {
+  if (!c) return;
+  for (auto& e : c->prof) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
+  for (auto& e : c->prof_pool) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
+  if (c->pinned) (void)hipHostFree(c->pinned);
+  for (auto& e : c->poll_ev) if (e) (void)hipEventDestroy(e);
+  delete c;
+}
+
+int32_t l2pd_forward(l2pd_ctx* c, const int32_t* tokens_dev, int32_t B, int32_t T, int32_t row_begin,
+                     int32_t row_count, float* logits_out_dev, void* stream) {
+  if (!c || !tokens_dev || !logits_out_dev) return L2PD_EINVAL;
+  if (B < 1 || B > c->max_batch || T < 1 || T > c->max_seq) return L2PD_EINVAL;
+  if (row_begin < 0 || row_count < 1 || (long long)row_begin + row_count > T) return L2PD_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int st = ensure_device(c, s);
+  if (st) return st;
+  Gate g = {nullptr, -1};
+  Pass p = {B, T, 0, T, T, tokens_dev, false, false};
+  run_layers(c, p, g, s);
+  // the LM head runs in slabs of rows so that the fp32 path's scratch bound (256 rows per sequence) holds
+  for (int r0 = 0; r0 < row_count; r0 += 256) {
+    int rc = row_count - r0 < 256 ? row_count - r0 : 256;
+    if (B == 1 || row_count <= 256) {
+      run_head(c, B, rc, RowMap{rc, T, row_begin + r0, 0},
+               logits_out_dev + (size_t)r0 * c->m.vocab, false, BiasArgs{0, 0, 1, 0.f}, g, s);
+    } else {
+      for (int b = 0; b < B; ++b)
+        run_head(c, 1, rc, RowMap{rc, T, b * T + row_begin + r0, 0},
+                 logits_out_dev + ((size_t)b * row_count + r0) * c->m.vocab, false, BiasArgs{0, 0, 1, 0.f}, g, s);
+    }
+  }
+  HIP_TRY(c, hipGetLastError());
+  return L2PD_OK;
+}
+
+int32_t l2pd_denoise_step(l2pd_ctx* c, int32_t* tokens_dev, int32_t B, int32_t prompt_len,
+                          const l2pd_decode_cfg* cfg, const l2pd_filter* f, int32_t* state_dev, float* logits_dev,
+                          float* conf_dev, int32_t* pred_dev, float* filt_dev, uint8_t* unmask_dev, void* stream) {
+  int st = check_decode_args(c, B, prompt_len, cfg, f);
+  if (st) return st;
+  if (!tokens_dev || !state_dev) return L2PD_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  st = ensure_device(c, s);
+  if (st) return st;
+  int host_gb = -1;
+  if (cfg->use_prefix_cache) {
+    std::vector<int32_t> hs((size_t)B * 3);
+    HIP_TRY(c, hipMemcpyAsync(hs.data(), state_dev, hs.size() * 4, hipMemcpyDeviceToHost, s));
+    HIP_TRY(c, hipStreamSynchronize(s));
+    const int nb = cfg->gen_len / cfg->block_len;
+    host_gb = nb;
+    for (int b = 0; b < B; ++b)
+      if (!hs[b * 3 + 2] && hs[b * 3] < host_gb) host_gb = hs[b * 3];
+    if (host_gb >= nb) return L2PD_OK;   // every sequence is done: nothing to do
+    if (host_gb < 0) return L2PD_EINVAL;
+    run_refresh(c, tokens_dev, B, prompt_len, cfg, host_gb, Gate{nullptr, -1}, s);
+  }
+  StepTaps taps = {logits_dev, conf_dev, pred_dev, filt_dev, unmask_dev};
+  run_step(c, tokens_dev, B, prompt_len, cfg, f, state_dev, host_gb, taps, s);
+  HIP_TRY(c, hipGetLastError());
+  return L2PD_OK;
+}
+
+int32_t l2pd_generate(l2pd_ctx* c, const int32_t* prompt_dev, int32_t B, int32_t P, const l2pd_decode_cfg* cfg,
+                      const l2pd_filter* f, int32_t* tokens_out_dev, int32_t* steps_out_dev,
+                      int32_t* decoded_len_out_dev, void* stream) {
+  int st = check_decode_args(c, B, P, cfg, f);
+  if (st) return st;
+  if (!prompt_dev || !tokens_out_dev) return L2PD_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  st = ensure_device(c, s);
+  if (st) return st;
+  if (!c->pinned) {
+    HIP_TRY(c, hipHostMalloc(reinterpret_cast<void**>(&c->pinned), 2 * CTL_WORDS * sizeof(int), hipHostMallocDefault));
+    HIP_TRY(c, hipEventCreateWithFlags(&c->poll_ev[0], hipEventDisableTiming));
+    HIP_TRY(c, hipEventCreateWithFlags(&c->poll_ev[1], hipEventDisableTiming));
+  }
+  const Layout& L = c->L;
+  int32_t* X = c->at<int32_t>(L.X);
+  int32_t* state = c->at<int32_t>(L.state);
+  int* ctl = c->at<int>(L.ctl);
+  const int sl = cfg->block_len, G = cfg->gen_len, nb = G / sl;
+  launch_init_decode(X, prompt_dev, B, P, G, c->m.mask_id, state, ctl, s);
+  const StepTaps no_taps = {nullptr, nullptr, nullptr, nullptr, nullptr};
+  const int CHUNK = 4;   // steps enqueued between two looks at the control block
+
+  // Enqueue `CHUNK` steps, then a copy of the control block to pinned memory; look at the copy of
+  // the chunk before, so the device always has a chunk queued while the host waits.
+  auto run_until = [&](int host_gb, int max_steps) -> int {   // returns 1 when everything is done
+    int issued = 0, slot = 0;
+    bool have_prev = false;
+    while (issued < max_steps) {
+      for (int i = 0; i < CHUNK && issued < max_steps; ++i, ++issued)
+        run_step(c, X, B, P, cfg, f, state, host_gb, no_taps, s);
+      launch_prepare(state, B, nb, ctl, s);
+      if (hipMemcpyAsync(c->pinned + slot * CTL_WORDS, ctl, CTL_WORDS * sizeof(int), hipMemcpyDeviceToHost, s) !=
+              hipSuccess ||
+          hipEventRecord(c->poll_ev[slot], s) != hipSuccess)
+        return -1;
+      if (have_prev) {
+        int prev = slot ^ 1;
+        if (hipEventSynchronize(c->poll_ev[prev]) != hipSuccess) return -1;
+        const int* pc = c->pinned + prev * CTL_WORDS;
+        if (pc[CTL_ALL_DONE]) return 1;
+        if (host_gb >= 0 && pc[CTL_GB] != host_gb) return 0;
+      }
+      have_prev = true;
+      slot ^= 1;
+    }
+    // all steps this block (or decode) can need are enqueued: read the final state
+    int last = slot ^ 1;
+    if (hipEventSynchronize(c->poll_ev[last]) != hipSuccess) return -1;
+    return c->pinned[last * CTL_WORDS + CTL_ALL_DONE] ? 1 : 0;
+  };
+
+  if (cfg->use_prefix_cache) {
+    for (int gb = 0; gb < nb; ++gb) {
+      launch_prepare(state, B, nb, ctl, s);
+      run_refresh(c, X, B, P, cfg, gb, Gate{ctl, -1}, s);
+      int r = run_until(gb, sl);   // a block needs at most block_len steps
+      if (r < 0) { c->last_hip_error = (int)hipGetLastError(); return L2PD_EHIP; }
+      if (r == 1) break;
+    }
+  } else {
+    int r = run_until(-1, G);      // at most gen_len steps in total
+    if (r < 0) { c->last_hip_error = (int)hipGetLastError(); return L2PD_EHIP; }
+  }
+  launch_finalize(X, state, B, P, G, sl, tokens_out_dev, steps_out_dev, decoded_len_out_dev, s);
+  HIP_TRY(c, hipGetLastError());
+  return L2PD_OK;
+}
+
+int32_t l2pd_profile_select(l2pd_ctx* c, int32_t cls) {
+  if (!c || cls < 0 || cls > L2PD_K_UPDATE) return L2PD_EINVAL;
+  for (auto& e : c->prof) c->prof_pool.push_back(e);
+  c->prof.clear();
+  c->prof_class = cls;
+  return L2PD_OK;
+}
+
+int32_t l2pd_profile_read(l2pd_ctx* c, int64_t* launches_out, double* total_ms_out) {
+  if (!c || !launches_out || !total_ms_out) return L2PD_EINVAL;
+  double total = 0.0;
+  for (auto& e : c->prof) {
+    HIP_TRY(c, hipEventSynchronize(e.b));
+    float ms = 0.f;
+    HIP_TRY(c, hipEventElapsedTime(&ms, e.a, e.b));
+    total += ms;
+  }
+  *launches_out = (int64_t)c->prof.size();
+  *total_ms_out = total;
+  return L2PD_OK;
+}
+
+}  // extern "C"

@@ -215,9 +215,15 @@ def make_tensor(m: ModelShape, seed: int, name: str, shape, kind: str, device="c
     return normal(seed, name, shape, init_std, dt, device)
 
 
-def make_weights(m: ModelShape, seed: int, device="cpu", init_std: float = 0.02) -> Dict[str, torch.Tensor]:
-    """All model tensors: matrices N(0, init_std^2), RMSNorm gains 1."""
-    return {name: make_tensor(m, seed, name, shape, kind, device, init_std)
+def make_weights(m: ModelShape, seed: int, device="cpu", init_std: float = 0.02,
+                 lm_head_scale: float = 1.0) -> Dict[str, torch.Tensor]:
+    """All model tensors: matrices N(0, init_std^2), RMSNorm gains 1.
+
+    lm_head_scale > 1 gives the "peaked" test variant: logits spread out, so confidences cover
+    (0, 1) instead of sitting near 1/vocab as they do for a plain random-init model.
+    """
+    return {name: make_tensor(m, seed, name, shape, kind, device,
+                              init_std * (lm_head_scale if name == "lm_head" else 1.0))
             for name, shape, kind in weight_specs(m)}
 
 

@@ -1,0 +1,102 @@
+"""The C-ABI library loads, exports everything include/l2pd.h declares, and rejects bad arguments
+on the host before anything is launched (no GPU needed: no compute call is made here)."""
+import ctypes as C
+import math
+import os
+import re
+
+import pytest
+
+from paper_2509_25188_amd import binding as Bd
+from paper_2509_25188_amd import synth
+
+HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "l2pd.h")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(l2pd_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = Bd.lib()
+    names = declared_functions()
+    assert set(names) == set(Bd.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_strerror():
+    lib = Bd.lib()
+    assert lib.l2pd_strerror(0) == b"ok"
+    for code in (-1, -2, -3, -4, -77):
+        assert len(lib.l2pd_strerror(code)) > 0
+
+
+def fake_weights(L):
+    arr = (C.c_void_p * L)(*([0x1000] * L))
+    p = C.cast(arr, C.POINTER(C.c_void_p))
+    return Bd.Weights(0x1000, 0x1000, 0x1000, p, p, p, p, p, p, p, p, p), arr
+
+
+def test_workspace_and_create_argument_checks():
+    lib = Bd.lib()
+    m = synth.WORKLOADS["tiny"].model
+    d = Bd.model_desc(m)
+    n = lib.l2pd_workspace_bytes(C.byref(d), 1, 96, 0)
+    assert n > 0
+    assert lib.l2pd_workspace_bytes(C.byref(d), 1, 96, 1) > n          # per-layer K/V stores
+    assert lib.l2pd_workspace_bytes(C.byref(d), 0, 96, 0) == 0
+    bad = Bd.model_desc(m)
+    bad.n_heads = 3                                                     # heads * head_dim != d_model
+    assert lib.l2pd_workspace_bytes(C.byref(bad), 1, 96, 0) == 0
+    w, keep = fake_weights(m.n_layers)
+    ctx = C.c_void_p()
+    assert lib.l2pd_create(C.byref(bad), C.byref(w), 1, 96, 0, 0x10000, n, C.byref(ctx)) == Bd.L2PD_EINVAL
+    assert lib.l2pd_create(C.byref(d), C.byref(w), 1, 96, 0, None, n, C.byref(ctx)) == Bd.L2PD_EINVAL
+    assert lib.l2pd_create(C.byref(d), C.byref(w), 1, 96, 0, 0x10000, n - 1, C.byref(ctx)) == Bd.L2PD_ENOMEM
+    assert lib.l2pd_create(C.byref(d), C.byref(w), 1, 96, 0, 0x10001, n, C.byref(ctx)) == Bd.L2PD_EINVAL
+    for field, val in (("mask_id", m.vocab), ("eos_id", -1), ("dtype", 7), ("head_dim", 31)):
+        b2 = Bd.model_desc(m)
+        setattr(b2, field, val)
+        assert lib.l2pd_create(C.byref(b2), C.byref(w), 1, 96, 0, 0x10000, n, C.byref(ctx)) == Bd.L2PD_EINVAL
+    bf = Bd.model_desc(synth.WORKLOADS["mid"].model)
+    bf.head_dim, bf.n_heads = 32, 32                                    # bf16 kernels need head_dim 64 or 128
+    assert lib.l2pd_create(C.byref(bf), C.byref(w), 1, 96, 0, 0x10000, 1 << 40, C.byref(ctx)) == Bd.L2PD_ENOTIMPL
+
+
+def test_decode_argument_checks_return_before_any_launch():
+    lib = Bd.lib()
+    m = synth.WORKLOADS["tiny"].model
+    d = Bd.model_desc(m)
+    n = lib.l2pd_workspace_bytes(C.byref(d), 2, 96, 0)
+    w, keep = fake_weights(m.n_layers)
+    ctx = C.c_void_p()
+    assert lib.l2pd_create(C.byref(d), C.byref(w), 2, 96, 0, 0x10000, n, C.byref(ctx)) == Bd.L2PD_OK
+    try:
+        flt = Bd.Filter(32, 64, 0x1000, 0x1000, 0x1000, 0x1000)
+
+        def gen(cfg, f=flt, B=1, P=32, prompt=0x1000, out=0x1000):
+            return lib.l2pd_generate(ctx, prompt, B, P, C.byref(cfg), C.byref(f), out, None, None, None)
+
+        ok = Bd.Engine.cfg_struct(64, 32, 0.5)
+        assert gen(Bd.Engine.cfg_struct(64, 24, 0.5)) == Bd.L2PD_EINVAL            # gen_len % block_len
+        assert gen(Bd.Engine.cfg_struct(64, 32, math.nan)) == Bd.L2PD_EINVAL       # NaN threshold
+        assert gen(Bd.Engine.cfg_struct(128, 32, 0.5)) == Bd.L2PD_EINVAL           # P + gen_len > max_seq
+        assert gen(ok, B=3) == Bd.L2PD_EINVAL                                      # B > max_batch
+        assert gen(ok, f=Bd.Filter(16, 64, 0x1000, 0x1000, 0x1000, 0x1000)) == Bd.L2PD_EINVAL  # in_dim != block
+        assert gen(ok, f=Bd.Filter(32, 64, None, 0x1000, 0x1000, 0x1000)) == Bd.L2PD_EINVAL
+        assert gen(Bd.Engine.cfg_struct(64, 32, 0.5, prefix_cache=True)) == Bd.L2PD_EINVAL  # ctx has no cache
+        assert gen(Bd.Engine.cfg_struct(64, 32, 0.5, bias=(m.vocab, 0, 1.0))) == Bd.L2PD_EINVAL
+        assert gen(ok, prompt=None) == Bd.L2PD_EINVAL
+        assert gen(ok, out=None) == Bd.L2PD_EINVAL
+        assert lib.l2pd_forward(ctx, 0x1000, 1, 97, 0, 1, 0x1000, None) == Bd.L2PD_EINVAL   # T > max_seq
+        assert lib.l2pd_forward(ctx, 0x1000, 1, 64, 60, 5, 0x1000, None) == Bd.L2PD_EINVAL  # rows past T
+        assert lib.l2pd_forward(ctx, None, 1, 64, 0, 1, 0x1000, None) == Bd.L2PD_EINVAL
+        assert lib.l2pd_denoise_step(ctx, 0x1000, 1, 32, C.byref(ok), C.byref(flt), None, None, None, None, None,
+                                     None, None) == Bd.L2PD_EINVAL                          # no state
+        assert lib.l2pd_profile_select(ctx, 99) == Bd.L2PD_EINVAL
+        assert lib.l2pd_profile_select(ctx, Bd.K_GEMM_GATEUP) == Bd.L2PD_OK
+    finally:
+        lib.l2pd_destroy(ctx)

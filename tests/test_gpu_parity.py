@@ -1,0 +1,239 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element on the
+same seeded inputs.  All tests here need a real MI355X."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2509_25188_amd import binding as Bd
+from paper_2509_25188_amd import synth
+from tests import parity as Pz
+
+pytestmark = pytest.mark.gpu
+SEED = 1234
+
+
+def small_bf16(name, L, d, H, Dh, F, V, B, P, G, s, hidden=32, tau=0.7, **kw):
+    m = synth.ModelShape(L, d, H, Dh, F, V, V - 1, V - 2, dtype="bf16")
+    return synth.Workload(name, m, B, P, G, s, hidden, tau, prompt_hi=V - 2, **kw)
+
+
+def build(w: synth.Workload, seed=SEED, lm_head_scale=1.0, max_batch=None):
+    weights = synth.make_weights(w.model, seed, "cpu", lm_head_scale=lm_head_scale)
+    eng = Bd.Engine(w.model, Pz.to_dev(weights), max_batch or w.batch, w.prompt_len + w.gen_len, w.prefix_cache)
+    ora = Pz.oracle_model(w.model, weights)
+    flt = synth.make_filter(seed, w.block_len, w.filter_hidden, "cpu")
+    prompt = synth.make_prompt(seed, w.batch, w.prompt_len, w.prompt_hi, "cpu")
+    return eng, ora, flt, prompt
+
+
+def test_generator_is_device_independent():
+    for dt in (torch.float32, torch.bfloat16):
+        a = synth.normal(3, "t", (513, 257), 0.02, dt, "cpu")
+        b = synth.normal(3, "t", (513, 257), 0.02, dt, "cuda")
+        assert torch.equal(a, b.cpu())
+    p = synth.make_prompt(3, 4, 99, 1000, "cuda")
+    assert torch.equal(p.cpu(), synth.make_prompt(3, 4, 99, 1000, "cpu"))
+
+
+# ------------------------------------------------------------------------------------------ forward
+def test_forward_tiny_fp32_all_rows():
+    w = synth.WORKLOADS["tiny"]
+    eng, ora, flt, prompt = build(w)
+    X = torch.cat([prompt, torch.full((1, w.gen_len), w.model.mask_id, dtype=torch.int32)], 1)
+    got = eng.forward(X.cuda()).cpu().numpy()[0]
+    ref = ora.forward(X[0].numpy())
+    assert Pz.rel_err(got, ref) < 1e-4
+    sub = eng.forward(X.cuda(), 40, 7).cpu().numpy()[0]
+    np.testing.assert_allclose(sub, got[40:47], rtol=0, atol=0)
+
+
+def test_forward_fp32_ragged_batch():
+    # T = 77 is not a multiple of any tile; two different sequences in one batch
+    m = synth.ModelShape(2, 96, 3, 32, 200, 301, 300, 299, dtype="fp32")
+    w = synth.Workload("ragged32", m, 2, 13, 64, 32, 16, 0.5, prompt_hi=299)
+    eng, ora, flt, prompt = build(w)
+    X = torch.cat([prompt, torch.full((2, 64), 300, dtype=torch.int32)], 1)
+    X[1, 20:30] = torch.arange(10, dtype=torch.int32)
+    got = eng.forward(X.cuda()).cpu().numpy()
+    for b in range(2):
+        assert Pz.rel_err(got[b], ora.forward(X[b].numpy())) < 1e-4
+
+
+@pytest.mark.parametrize("Dh,H,T", [(64, 4, 200), (128, 2, 333), (128, 2, 64)])
+def test_forward_bf16_small(Dh, H, T):
+    # several row tiles, ragged tails in rows and keys, both head sizes
+    w = small_bf16(f"bf{Dh}", 2, H * Dh, H, Dh, 448, 1000, 2, T - 32, 32, 32)
+    eng, ora, flt, prompt = build(w)
+    X = torch.cat([prompt, torch.full((2, 32), w.model.mask_id, dtype=torch.int32)], 1)
+    got = eng.forward(X.cuda()).cpu().numpy()
+    for b in range(2):
+        ref = ora.forward(X[b].numpy())
+        e = Pz.rel_err(got[b], ref)
+        assert e < 2e-2, e
+
+
+# ------------------------------------------------------------------------------------------ decode, fp32
+def test_tiny_trajectory_and_teacher_forced_steps():
+    w = synth.WORKLOADS["tiny"]
+    eng, ora, flt, prompt = build(w)
+    trace = []
+    resp, steps, dlen = Pz.oracle_generate(ora, prompt[0].numpy(), w, Pz.np_filter(flt), trace)
+    fdev = {k: v.cuda() for k, v in flt.items()}
+    cfg = Pz.cfg_for(w)
+    rep = Pz.StepReport()
+    same = Pz.teacher_forced(eng, [trace], w.prompt_len, cfg, fdev, w.model, w.threshold, rep)
+    print("tiny teacher-forced:", rep)
+    assert rep.max_logit_err < 1e-4
+    tok, st, dl = eng.generate(prompt.cuda(), fdev, cfg)
+    torch.cuda.synchronize()
+    if same:
+        np.testing.assert_array_equal(tok.cpu().numpy()[0], resp)
+        assert int(st[0]) == steps and int(dl[0]) == dlen
+    assert not np.any(tok.cpu().numpy() == w.model.mask_id)
+
+
+def test_tiny_peaked_trajectory_exact():
+    # LM head scaled so that confidences spread over (0, 1): decisions have real margins
+    w = synth.WORKLOADS["tiny"]
+    eng, ora, flt, prompt = build(w, lm_head_scale=60.0)
+    trace = []
+    resp, steps, dlen = Pz.oracle_generate(ora, prompt[0].numpy(), w, Pz.np_filter(flt), trace)
+    confs = np.concatenate([t["conf"] for t in trace])
+    assert confs.max() > 0.5 and confs.min() < 0.2
+    fdev = {k: v.cuda() for k, v in flt.items()}
+    tok, st, dl = eng.generate(prompt.cuda(), fdev, Pz.cfg_for(w))
+    np.testing.assert_array_equal(tok.cpu().numpy()[0], resp)
+    assert int(st[0]) == steps and int(dl[0]) == dlen
+
+
+@pytest.mark.parametrize("tau,expect", [(1.0, 64), (-0.1, 2)])
+def test_tiny_threshold_special_cases(tau, expect):
+    # tau >= 1: one token per step, gen_len steps (32 decodings per block of 32); tau < 0: one step per block
+    w = synth.WORKLOADS["tiny"]
+    eng, ora, flt, prompt = build(w)
+    fdev = {k: v.cuda() for k, v in flt.items()}
+    tok, st, dl = eng.generate(prompt.cuda(), fdev, Pz.cfg_for(w, tau))
+    assert int(st[0]) == expect and int(dl[0]) == w.gen_len
+    assert not np.any(tok.cpu().numpy() == w.model.mask_id)
+
+
+def test_batch_rows_equal_their_own_single_runs_fp32():
+    m = synth.WORKLOADS["tiny"].model
+    w = synth.Workload("tiny_b3", m, 3, 20, 64, 32, 64, 0.5, prompt_hi=1022)
+    eng, ora, flt, prompt = build(w, lm_head_scale=60.0)
+    fdev = {k: v.cuda() for k, v in flt.items()}
+    cfg = Pz.cfg_for(w)
+    tok, st, dl = eng.generate(prompt.cuda(), fdev, cfg)
+    tok, st = tok.cpu().numpy(), st.cpu().numpy()
+    assert len(set(st.tolist())) > 1        # the sequences really take different numbers of steps
+    for b in range(3):
+        resp, steps, dlen = Pz.oracle_generate(ora, prompt[b].numpy(), w, Pz.np_filter(flt))
+        np.testing.assert_array_equal(tok[b], resp)
+        assert st[b] == steps
+        t1, s1, _ = eng.generate(prompt[b:b + 1].cuda(), fdev, cfg)
+        np.testing.assert_array_equal(t1.cpu().numpy()[0], tok[b])
+        assert int(s1[0]) == st[b]
+
+
+def test_eotp_stops_at_first_block_with_eos_fp32():
+    m = synth.WORKLOADS["tiny"].model
+    w = synth.Workload("tiny_eotp", m, 2, 16, 128, 16, 32, 1.0, eotp=True, bias_from=53, bias_value=40.0,
+                       prompt_hi=1022)
+    eng, ora, flt, prompt = build(w)
+    fdev = {k: v.cuda() for k, v in flt.items()}
+    tok, st, dl = eng.generate(prompt.cuda(), fdev, Pz.cfg_for(w))
+    tok = tok.cpu().numpy()
+    nb = 53 // 16 + 1
+    for b in range(2):
+        assert int(st[b]) == nb * 16 and int(dl[b]) == nb * 16          # tau >= 1: one token per step
+        assert np.all(tok[b, 53:nb * 16] == m.eos_id) and np.all(tok[b, nb * 16:] == m.mask_id)
+        resp, steps, dlen = Pz.oracle_generate(ora, prompt[b].numpy(), w, Pz.np_filter(flt))
+        assert (steps, dlen) == (nb * 16, nb * 16)
+        np.testing.assert_array_equal(tok[b], resp)
+    off = dataclasses.replace(w, eotp=False)
+    tok2, st2, dl2 = eng.generate(prompt.cuda(), fdev, Pz.cfg_for(off))
+    assert st2.tolist() == [128, 128] and dl2.tolist() == [128, 128]
+    np.testing.assert_array_equal(tok2.cpu().numpy()[:, :nb * 16], tok[:, :nb * 16])
+
+
+def test_prefix_cache_fp32_matches_oracle():
+    m = synth.WORKLOADS["tiny"].model
+    w = synth.Workload("tiny_pc", m, 2, 24, 96, 32, 48, 0.5, prefix_cache=True, prompt_hi=1022)
+    eng, ora, flt, prompt = build(w, lm_head_scale=60.0)
+    fdev = {k: v.cuda() for k, v in flt.items()}
+    cfg = Pz.cfg_for(w)
+    traces = []
+    outs = []
+    for b in range(2):
+        tr = []
+        outs.append(Pz.oracle_generate(ora, prompt[b].numpy(), w, Pz.np_filter(flt), tr))
+        traces.append(tr)
+    rep = Pz.StepReport()
+    Pz.teacher_forced(eng, traces, w.prompt_len, cfg, fdev, w.model, w.threshold, rep)
+    print("prefix-cache fp32 teacher-forced:", rep)
+    assert rep.max_logit_err < 1e-4
+    tok, st, dl = eng.generate(prompt.cuda(), fdev, cfg)
+    for b in range(2):
+        np.testing.assert_array_equal(tok.cpu().numpy()[b], outs[b][0])
+        assert int(st[b]) == outs[b][1]
+
+
+# ------------------------------------------------------------------------------------------ decode, bf16
+def test_bf16_small_teacher_forced_and_generate():
+    w = small_bf16("bf_dec", 2, 256, 4, 64, 512, 2000, 2, 40, 64, 32, tau=0.7)
+    eng, ora, flt, prompt = build(w, lm_head_scale=40.0)
+    fdev = {k: v.cuda() for k, v in flt.items()}
+    cfg = Pz.cfg_for(w)
+    traces, outs = [], []
+    for b in range(2):
+        tr = []
+        outs.append(Pz.oracle_generate(ora, prompt[b].numpy(), w, Pz.np_filter(flt), tr))
+        traces.append(tr)
+    rep = Pz.StepReport()
+    same = Pz.teacher_forced(eng, traces, w.prompt_len, cfg, fdev, w.model, w.threshold, rep)
+    print("bf16 small teacher-forced:", rep)
+    assert rep.max_logit_err < 2e-2
+    tok, st, dl = eng.generate(prompt.cuda(), fdev, cfg)
+    assert not np.any(tok.cpu().numpy() == w.model.mask_id)
+    if same:
+        for b in range(2):
+            np.testing.assert_array_equal(tok.cpu().numpy()[b], outs[b][0])
+            assert int(st[b]) == outs[b][1]
+
+
+def test_bf16_prefix_cache_and_eotp():
+    w = small_bf16("bf_pc", 2, 256, 2, 128, 320, 1500, 3, 33, 192, 64, hidden=32, tau=0.8, eotp=True,
+                   prefix_cache=True, bias_from=70, bias_value=30.0)
+    eng, ora, flt, prompt = build(w, lm_head_scale=40.0)
+    fdev = {k: v.cuda() for k, v in flt.items()}
+    cfg = Pz.cfg_for(w)
+    traces, outs = [], []
+    for b in range(3):
+        tr = []
+        outs.append(Pz.oracle_generate(ora, prompt[b].numpy(), w, Pz.np_filter(flt), tr))
+        traces.append(tr)
+        assert outs[b][2] == 128          # EOS bias from position 70: stop after block 1 of 3
+    rep = Pz.StepReport()
+    same = Pz.teacher_forced(eng, traces, w.prompt_len, cfg, fdev, w.model, w.threshold, rep)
+    print("bf16 prefix-cache teacher-forced:", rep)
+    assert rep.max_logit_err < 2e-2
+    tok, st, dl = eng.generate(prompt.cuda(), fdev, cfg)
+    assert dl.tolist() == [128, 128, 128]
+    assert np.all(tok.cpu().numpy()[:, 128:] == w.model.mask_id)
+    if same:
+        for b in range(3):
+            np.testing.assert_array_equal(tok.cpu().numpy()[b], outs[b][0])
+            assert int(st[b]) == outs[b][1]
+
+
+def test_generate_is_deterministic_bf16():
+    w = small_bf16("bf_det", 2, 256, 4, 64, 448, 2000, 4, 40, 64, 32, tau=0.7)
+    eng, ora, flt, prompt = build(w)
+    fdev = {k: v.cuda() for k, v in flt.items()}
+    cfg = Pz.cfg_for(w)
+    a = eng.generate(prompt.cuda(), fdev, cfg)
+    b = eng.generate(prompt.cuda(), fdev, cfg)
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
