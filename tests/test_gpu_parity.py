@@ -97,7 +97,7 @@ def test_tiny_trajectory_and_teacher_forced_steps():
 def test_tiny_peaked_trajectory_exact():
     # LM head scaled so that confidences spread over (0, 1): decisions have real margins
     w = synth.WORKLOADS["tiny"]
-    eng, ora, flt, prompt = build(w, lm_head_scale=60.0)
+    eng, ora, flt, prompt = build(w, lm_head_scale=25.0)
     trace = []
     resp, steps, dlen = Pz.oracle_generate(ora, prompt[0].numpy(), w, Pz.np_filter(flt), trace)
     confs = np.concatenate([t["conf"] for t in trace])
@@ -122,7 +122,7 @@ def test_tiny_threshold_special_cases(tau, expect):
 def test_batch_rows_equal_their_own_single_runs_fp32():
     m = synth.WORKLOADS["tiny"].model
     w = synth.Workload("tiny_b3", m, 3, 20, 64, 32, 64, 0.5, prompt_hi=1022)
-    eng, ora, flt, prompt = build(w, lm_head_scale=60.0)
+    eng, ora, flt, prompt = build(w, lm_head_scale=25.0)
     fdev = {k: v.cuda() for k, v in flt.items()}
     cfg = Pz.cfg_for(w)
     tok, st, dl = eng.generate(prompt.cuda(), fdev, cfg)
@@ -161,7 +161,7 @@ def test_eotp_stops_at_first_block_with_eos_fp32():
 def test_prefix_cache_fp32_matches_oracle():
     m = synth.WORKLOADS["tiny"].model
     w = synth.Workload("tiny_pc", m, 2, 24, 96, 32, 48, 0.5, prefix_cache=True, prompt_hi=1022)
-    eng, ora, flt, prompt = build(w, lm_head_scale=60.0)
+    eng, ora, flt, prompt = build(w, lm_head_scale=25.0)
     fdev = {k: v.cuda() for k, v in flt.items()}
     cfg = Pz.cfg_for(w)
     traces = []
@@ -183,7 +183,7 @@ def test_prefix_cache_fp32_matches_oracle():
 # ------------------------------------------------------------------------------------------ decode, bf16
 def test_bf16_small_teacher_forced_and_generate():
     w = small_bf16("bf_dec", 2, 256, 4, 64, 512, 2000, 2, 40, 64, 32, tau=0.7)
-    eng, ora, flt, prompt = build(w, lm_head_scale=40.0)
+    eng, ora, flt, prompt = build(w, lm_head_scale=25.0)
     fdev = {k: v.cuda() for k, v in flt.items()}
     cfg = Pz.cfg_for(w)
     traces, outs = [], []
@@ -206,7 +206,7 @@ def test_bf16_small_teacher_forced_and_generate():
 def test_bf16_prefix_cache_and_eotp():
     w = small_bf16("bf_pc", 2, 256, 2, 128, 320, 1500, 3, 33, 192, 64, hidden=32, tau=0.8, eotp=True,
                    prefix_cache=True, bias_from=70, bias_value=30.0)
-    eng, ora, flt, prompt = build(w, lm_head_scale=40.0)
+    eng, ora, flt, prompt = build(w, lm_head_scale=25.0)
     fdev = {k: v.cuda() for k, v in flt.items()}
     cfg = Pz.cfg_for(w)
     traces, outs = [], []
