@@ -1,0 +1,211 @@
+#!/usr/bin/env python3
+"""Throughput of the Learn2PD denoising loop on one MI355X.
+
+A "step" is one pass of the whole hot path over the batch: the full bidirectional forward of the
+8B-shaped model over prompt + generation window, the fused vocabulary softmax-max / argmax of the
+active block, the filter, and the on-device unmask / block-advance / EoTP update.  The timed region
+runs exactly K such steps along the real decoding trajectory (the state is re-initialised on device
+whenever a generation completes), with weights, prompt and state already resident in HBM.
+
+Prints ONE JSON line.  `value` = generated tokens per second (tokens committed per step on this
+trajectory x steps per second); `roofline` is for the dominant kernel (the gate/up SwiGLU GEMM),
+timed live with HIP events on the launch stream; `cpu_baseline` is the CPU oracle timed on this
+host on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
+PEAK_HBM_GBS = 8000.0
+
+
+def step_flops(w):
+    """Algorithmic flops of one denoising step (full recompute): linear layers on every row,
+    bidirectional attention, LM head on the active block's rows only."""
+    m = w.model
+    rows = w.batch * (w.prompt_len + w.gen_len)
+    T = w.prompt_len + w.gen_len
+    lin = 2.0 * rows * m.n_layers * (4 * m.d_model * m.d_model + 3 * m.d_model * m.d_ffn)
+    attn = 4.0 * w.batch * T * T * m.d_model * m.n_layers
+    head = 2.0 * w.batch * w.block_len * m.d_model * m.vocab
+    return lin, attn, head
+
+
+def cpu_baseline(w, tokens_per_step, seed, n_layers_sample=2):
+    """Times the oracle as it stands on a bounded sample: `n_layers_sample` of the layers plus
+    embedding + LM head + decode rule at full width and full sequence length, one sequence."""
+    import numpy as np
+    import torch
+    from oracle import l2pd_oracle as O
+    from paper_2509_25188_amd import synth
+    from tests import parity as Pz
+
+    m = w.model
+    ws = synth.with_layers(w, n_layers_sample)
+    t0 = time.time()
+    weights = synth.make_weights(ws.model, seed, "cpu")
+    ora = Pz.oracle_model(ws.model, weights)
+    flt = Pz.np_filter(synth.make_filter(seed, w.block_len, w.filter_hidden))
+    prompt = synth.make_prompt(seed, 1, w.prompt_len, w.prompt_hi)[0].numpy()
+    gen_s = time.time() - t0
+    X = np.concatenate([prompt.astype(np.int64), np.full(w.gen_len, m.mask_id, dtype=np.int64)])
+    T = len(X)
+    pos = np.arange(T)
+    t0 = time.time()
+    h = ora.embed(X)
+    t_embed = time.time() - t0
+    t_layers = 0.0
+    for l in range(n_layers_sample):
+        t0 = time.time()
+        q, k, v = ora.qkv(l, h, pos)
+        h = ora.finish_layer(l, h, O.attention(q, k, v))
+        t_layers += time.time() - t0
+    t0 = time.time()
+    logits = ora.head(h[w.prompt_len:w.prompt_len + w.block_len])
+    d = O.decide(X[w.prompt_len:w.prompt_len + w.block_len], logits, m.mask_id, flt, w.threshold)
+    t_head = time.time() - t0
+    per_step = t_embed + t_layers / n_layers_sample * m.n_layers + t_head
+    per_step *= w.batch           # the oracle decodes one sequence at a time
+    steps_per_s = 1.0 / per_step
+    return {
+        "value": steps_per_s * tokens_per_step, "unit": "tokens/s", "cores": torch.get_num_threads(),
+        "kind": "oracle", "steps_per_s": steps_per_s,
+        "sample": (f"one denoising step of one sequence: embedding + {n_layers_sample} of {m.n_layers} layers "
+                   f"+ LM head + decode rule at full width, T={T}, fp32 NumPy; layer time scaled to "
+                   f"{m.n_layers} layers and to batch {w.batch} (measured {t_layers + t_embed + t_head:.1f} s of "
+                   f"oracle work, {gen_s:.0f} s generating its weights)"),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=96)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="8b_g256")
+    ap.add_argument("--layers", type=int, default=0, help="reduced depth (debugging only; invalid as a result)")
+    ap.add_argument("--seed", type=int, default=1234)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2509_25188_amd import binding as Bd
+    from paper_2509_25188_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    w = synth.WORKLOADS[args.workload]
+    if args.layers:
+        w = synth.with_layers(w, args.layers)
+    m = w.model
+    dev = "cuda"
+    t0 = time.time()
+    eng = Bd.engine_for(w, args.seed, dev)
+    flt = synth.make_filter(args.seed, w.block_len, w.filter_hidden, dev)
+    prompt = synth.make_prompt(args.seed, w.batch, w.prompt_len, w.prompt_hi, dev)
+    bias = (m.eos_id, w.bias_from, w.bias_value) if w.bias_value else None
+    cfg = Bd.Engine.cfg_struct(w.gen_len, w.block_len, w.threshold, w.eotp, w.prefix_cache, bias)
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+
+    # The real trajectory once (also a warm-up): total steps and tokens of one generation.
+    t0 = time.time()
+    tok, st, dl = eng.generate(prompt, flt, cfg)
+    torch.cuda.synchronize()
+    gen_wall = time.time() - t0
+    t0 = time.time()
+    tok, st, dl = eng.generate(prompt, flt, cfg)
+    torch.cuda.synchronize()
+    gen_wall = time.time() - t0
+    steps_per_seq = st.cpu().tolist()
+    traj_steps = max(steps_per_seq)                 # lock-step batch: forwards of one generation
+    tokens_total = int(dl.sum().item())
+    tokens_per_step = tokens_total / traj_steps
+
+    # K steps along that trajectory through l2pd_denoise_step; state reset on device at wrap-around.
+    T = w.prompt_len + w.gen_len
+    X0 = torch.cat([prompt, torch.full((w.batch, w.gen_len), m.mask_id, dtype=torch.int32, device=dev)], 1)
+    X = X0.clone()
+    state0 = torch.zeros((w.batch, 3), dtype=torch.int32, device=dev)
+    state = state0.clone()
+    f = eng.filter_struct(flt)
+    import ctypes as C
+    lib = Bd.lib()
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def run(n, k0):
+        for k in range(k0, k0 + n):
+            if k % traj_steps == 0:
+                X.copy_(X0)
+                state.copy_(state0)
+            rc = lib.l2pd_denoise_step(eng._ctx, X.data_ptr(), w.batch, w.prompt_len, C.byref(cfg), C.byref(f),
+                                       state.data_ptr(), None, None, None, None, None, stream)
+            if rc:
+                raise RuntimeError(f"l2pd_denoise_step: {rc}")
+        return k0 + n
+
+    if w.prefix_cache:
+        raise SystemExit("bench.py times full-recompute workloads; the prefix-cache workload is a parity case")
+    k = run(args.warmup, 0)
+    torch.cuda.synchronize()
+    eng.profile_select(Bd.K_GEMM_GATEUP)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(args.steps, k)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    n_launch, kern_ms = eng.profile_read()
+    eng.profile_select(Bd.K_NONE)
+
+    ms_per_step = elapsed * 1e3 / args.steps
+    steps_per_s = args.steps / elapsed
+    lin, attn, head = step_flops(w)
+    total_flops = lin + attn + head
+    rows = w.batch * T
+    gu_flops = 2.0 * rows * m.d_model * 2 * m.d_ffn
+    avg_kern_ms = kern_ms / max(n_launch, 1)
+    achieved = gu_flops / (avg_kern_ms * 1e-3) / 1e12 if n_launch else None
+    result = {
+        "metric": "generated tokens/sec (and denoising steps/sec), 8B-shaped dLLM, bs=1, 1 MI355X",
+        "value": tokens_per_step * steps_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if m.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.batch, "prompt_len": w.prompt_len, "gen_len": w.gen_len,
+                   "block_len": w.block_len, "threshold": w.threshold, "eotp": bool(w.eotp),
+                   "layers": m.n_layers, "d_model": m.d_model, "d_ffn": m.d_ffn, "vocab": m.vocab,
+                   "full_recompute_rows": rows},
+        "steps_per_s": steps_per_s,
+        "trajectory": {"steps_per_generation": traj_steps, "tokens_per_generation": tokens_total,
+                       "tokens_per_step": tokens_per_step, "generate_wall_s": gen_wall,
+                       "generate_tokens_per_s": tokens_total / gen_wall},
+        "step_tflop": total_flops / 1e12,
+        "step_mfma_frac": total_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "step_weight_stream_gbs": (sum(v.numel() * v.element_size() for k_, v in eng.weights.items()
+                                       if k_ != "tok_emb") / 1e9) / (ms_per_step * 1e-3),
+        "roofline": {"bound": "mfma", "kernel": "k_gemm_bf16<SwiGLU gate/up>", "achieved": achieved,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": (achieved / PEAK_BF16_TFLOPS) if achieved else None, "traffic": None,
+                     "launches": n_launch, "avg_launch_ms": avg_kern_ms, "flop_per_launch": gu_flops},
+        "setup_s": setup_s,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, tokens_per_step, args.seed)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,9 +1,14 @@
 // bf16 MFMA GEMM for gfx950:  C[M, N] = A[M, K] * W[N, K]^T, fp32 accumulation.
 //
 // Both operands are K-contiguous, which is the layout v_mfma_f32_32x32x16_bf16 wants: a lane feeds
-// eight consecutive K elements of one row.  Tiles go global -> LDS with 16-byte accesses; the LDS
-// rows (128 B = one bank sweep) are XOR-swizzled at 16-byte granularity so that the 32 rows a
-// wavefront reads together spread over all banks.  The fused epilogues are the ones the decoding
+// eight consecutive K elements of one row.  Tiles go global -> LDS directly (global_load_lds_dwordx4:
+// no VGPR staging, no ds_write) through an NS-stage ring, so that loads run NS-1 K-steps ahead of
+// the MFMAs; the wait for a stage is a manual s_waitcnt vmcnt(n) that leaves the younger stages in
+// flight.  One such load writes 1 KB = 8 LDS rows, lane i at byte 16*i, so the XOR swizzle of the
+// 128-byte rows is applied on the global side: lane i fetches chunk (i & 7) ^ key(r) of its row.
+// The LDS of gfx950 sweeps 64 banks x 4 B = 256 B, i.e. two tile rows, so the key is (r >> 1) & 7:
+// 16 consecutive rows then cover every bank exactly once per 16-byte read (measured: 1.5x the read
+// rate of key r & 7, 5x that of unswizzled rows).  The fused epilogues are the ones the decoding
 // step needs: rotary embedding + K / V^T store (QKV), SiLU(gate) * up (FFN), fp32 split-K partials
 // that the next RMSNorm folds into the residual stream (O and down projections), and the LM head's
 // per-tile (max, sum exp, argmax) reduction so that logits are never written.
@@ -19,7 +24,6 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
-constexpr int BK = 64;  // K elements per LDS tile row: 128 bytes
 enum { EPI_PARTIAL = 0, EPI_QKV = 1, EPI_SWIGLU = 2, EPI_LMHEAD = 3 };
 
 struct GemmArgs {
@@ -49,18 +53,52 @@ __device__ __forceinline__ unsigned short f2bf(float f) {   // round to nearest 
   return (unsigned short)(u >> 16);
 }
 
-template <int BM, int BN, int WM, int WN, int EPI>
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {   // s_waitcnt vmcnt(N) only (expcnt / lgkmcnt untouched)
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+// Workgroup barrier without the memory-model fence of __syncthreads(), which would wait for every
+// outstanding global load (vmcnt(0)) and so drain the prefetch ring.  LDS visibility is ordered by
+// the explicit waits around it; the empty asm statements keep the compiler from moving LDS
+// accesses across the barrier.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+// 16 bytes per lane, global -> LDS without passing through VGPRs.  The LDS destination of the whole
+// wavefront is M0 + 16 * lane.  Written as inline asm on purpose: the compiler's wait-count pass
+// falls back to lgkmcnt(0) before every LDS read while a direct-to-LDS load it knows of is in
+// flight, which would serialise the fragment prefetch; completion is tracked by hand with
+// wait_vmcnt<>().  (Untracked extra loads can only make the compiler's own vmcnt waits stricter,
+// because vmcnt retires in order.)
+__device__ __forceinline__ void dma16(const void* gptr, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :
+               : "v"(gptr), "s"(lds_addr)
+               : "memory", "m0");
+}
+
+template <int BM, int BN, int BK, int WM, int WN, int NS, int EPI>
 __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
   constexpr int NT = WM * WN * 64;
+  constexpr int NW = WM * WN;
   constexpr int FM = BM / WM / 32, FN = BN / WN / 32;
   constexpr bool PAIR = (EPI == EPI_QKV || EPI == EPI_SWIGLU);
   static_assert(!PAIR || (FN % 2 == 0), "pair epilogues need an even number of column fragments");
-  constexpr int CH_A = BM * 8 / NT, CH_B = BN * 8 / NT;   // 16-byte chunks per thread per tile
-  static_assert(CH_A * NT == BM * 8 && CH_B * NT == BN * 8, "tile/threads mismatch");
+  static_assert(BK == 32 || BK == 64, "LDS tile rows hold 32 or 64 K elements");
+  constexpr int CPR = BK / 8;               // 16-byte chunks per LDS row
+  constexpr int RPD = 64 / CPR;             // rows filled by one direct-to-LDS wave load (1 KB)
+  constexpr int KEY_SHIFT = BK == 64 ? 1 : 2;   // rows per 256-byte bank sweep = 1 << KEY_SHIFT
+  constexpr int LPS = (BM + BN) / RPD / NW; // direct-to-LDS loads per thread per stage
+  static_assert(LPS * NW * RPD == BM + BN, "tile/threads mismatch");
+  static_assert(NS >= 3 && (NS - 2) * LPS < 64, "ring depth: at least 3 stages, vmcnt is 6 bits");
 
   if (gate_skip(a.gate)) return;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  // [stage][A: BM rows | B: BN rows][64 bf16]
+  // [stage][A: BM rows | B: BN rows][BK bf16]
   constexpr int STAGE_BYTES = (BM + BN) * BK * 2;
 
   // ---- tile assignment: consecutive ids on one XCD share a weight panel ----
@@ -87,46 +125,55 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
   const int k_begin = z * k_len;
   const int nk = k_len / BK;
 
-  // ---- per-thread source pointers for the global -> LDS copies (fixed over the K loop) ----
-  const bf16* srcA[CH_A];
-  int dstA[CH_A];
+  // ---- per-thread source pointers of the direct-to-LDS loads (fixed over the K loop) ----
+  // Load q of a stage (q = wave + i*NW) fills combined tile rows RPD*q .. RPD*q+RPD-1 (A rows first, then B).
+  const bf16* src[LPS];
 #pragma unroll
-  for (int i = 0; i < CH_A; ++i) {
-    int q = tid + i * NT;
-    int r = q >> 3, c = q & 7;
-    int gr = min(m0 + r, a.M - 1);
-    srcA[i] = a.A + (size_t)gr * a.K + k_begin + c * 8;
-    dstA[i] = r * (BK * 2) + ((c ^ (r & 7)) << 4);
-  }
-  const bf16* srcB[CH_B];
-  int dstB[CH_B];
-#pragma unroll
-  for (int i = 0; i < CH_B; ++i) {
-    int q = tid + i * NT;
-    int r = q >> 3, c = q & 7;
-    const bf16* base;
-    size_t grow;
-    if constexpr (!PAIR) {
-      base = a.B0;
-      grow = (size_t)min(n0 + r, a.N - 1);
+  for (int i = 0; i < LPS; ++i) {
+    const int q = wave + i * NW;
+    const int rr = q * RPD + lane / CPR;         // row in the combined [A; B] tile
+    const int c = (lane % CPR) ^ ((rr >> KEY_SHIFT) & (CPR - 1));   // global chunk that belongs at this lane's slot
+    if (rr < BM) {
+      int gr = min(m0 + rr, a.M - 1);
+      src[i] = a.A + (size_t)gr * a.K + k_begin + c * 8;
     } else {
-      int rw = r / (32 * FN), f = (r >> 5) % FN, j = r & 31;
-      int G = tile_n * (BN / 64) + rw * (FN / 2) + (f >> 1), side = f & 1;
-      if constexpr (EPI == EPI_SWIGLU) {
-        base = side ? a.B1 : a.B0;
-        grow = (size_t)min(G * 32 + j, a.F - 1);
+      const int r = rr - BM;
+      const bf16* base;
+      size_t grow;
+      if constexpr (!PAIR) {
+        base = a.B0;
+        grow = (size_t)min(n0 + r, a.N - 1);
       } else {
-        const int half = a.qkv.Dh / 2, gph = half / 32;
-        int hg = G / gph, gi = G % gph;
-        int mat = hg / a.qkv.H, head = hg % a.qkv.H;
-        mat = min(mat, 2);
-        base = mat == 0 ? a.B0 : (mat == 1 ? a.B1 : a.B2);
-        grow = (size_t)(head * a.qkv.Dh + side * half + gi * 32 + j);
+        int rw = r / (32 * FN), f = (r >> 5) % FN, j = r & 31;
+        int G = tile_n * (BN / 64) + rw * (FN / 2) + (f >> 1), side = f & 1;
+        if constexpr (EPI == EPI_SWIGLU) {
+          base = side ? a.B1 : a.B0;
+          grow = (size_t)min(G * 32 + j, a.F - 1);
+        } else {
+          const int half = a.qkv.Dh / 2, gph = half / 32;
+          int hg = G / gph, gi = G % gph;
+          int mat = hg / a.qkv.H, head = hg % a.qkv.H;
+          mat = min(mat, 2);
+          base = mat == 0 ? a.B0 : (mat == 1 ? a.B1 : a.B2);
+          grow = (size_t)(head * a.qkv.Dh + side * half + gi * 32 + j);
+        }
       }
+      src[i] = base + grow * a.K + k_begin + c * 8;
     }
-    srcB[i] = base + grow * a.K + k_begin + c * 8;
-    dstB[i] = BM * (BK * 2) + r * (BK * 2) + ((c ^ (r & 7)) << 4);
   }
+  // LDS byte address of this wave's first slot in stage 0 (wave-uniform, goes to M0)
+  const unsigned lds0 = __builtin_amdgcn_readfirstlane(
+      (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)(smem + wave * 1024));
+  constexpr int KS = BK / 16;   // MFMA K-steps per stage
+  // Loads of one stage are issued in KS parts (load i belongs to part i % KS), one part per K-step,
+  // so that they trickle into the texture-address queue behind MFMAs instead of arriving as a burst
+  // from every wave right after the barrier (a burst stalls instruction issue until the queue drains).
+  auto issue_part = [&](int kt, int part) {
+    const unsigned dst = lds0 + (kt % NS) * STAGE_BYTES;
+#pragma unroll
+    for (int i = 0; i < LPS; ++i)
+      if (i % KS == part) dma16(src[i] + kt * BK, dst + i * NW * 1024);
+  };
 
   f32x16 acc[FM][FN];
 #pragma unroll
@@ -136,53 +183,89 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  u32x4 ra[CH_A], rb[CH_B];
-  auto gload = [&](int kt) {
-#pragma unroll
-    for (int i = 0; i < CH_A; ++i) ra[i] = *reinterpret_cast<const u32x4*>(srcA[i] + kt * BK);
-#pragma unroll
-    for (int i = 0; i < CH_B; ++i) rb[i] = *reinterpret_cast<const u32x4*>(srcB[i] + kt * BK);
-  };
-  auto sstore = [&](int stage) {
-    unsigned char* base = smem + stage * STAGE_BYTES;
-#pragma unroll
-    for (int i = 0; i < CH_A; ++i) *reinterpret_cast<u32x4*>(base + dstA[i]) = ra[i];
-#pragma unroll
-    for (int i = 0; i < CH_B; ++i) *reinterpret_cast<u32x4*>(base + dstB[i]) = rb[i];
-  };
-
   // fragment row byte offsets inside a stage (row * 128) and the row's swizzle key
   int offA[FM], offB[FN];
 #pragma unroll
   for (int i = 0; i < FM; ++i) offA[i] = (wm * (BM / WM) + i * 32 + lj) * (BK * 2);
 #pragma unroll
   for (int j = 0; j < FN; ++j) offB[j] = BM * (BK * 2) + (wn * (BN / WN) + j * 32 + lj) * (BK * 2);
-  const int key = lj & 7;   // all fragment rows are lj mod 8 (fragment bases are multiples of 32)
+  const int key = (lj >> KEY_SHIFT) & (CPR - 1);   // row's swizzle key (fragment bases are multiples of 32)
 
-  gload(0);
-  sstore(0);
-  __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    const bool more = kt + 1 < nk;
-    if (more) gload(kt + 1);
-    const unsigned char* base = smem + (kt & 1) * STAGE_BYTES;
+  // Software pipeline.  Fragments are double-buffered in registers: the ds_reads of K-step kk+1 are
+  // issued before the MFMAs of step kk, and the first fragments of the next stage are read during
+  // the last step of the current one.  The ring advances (wait for stage kt+1, barrier, refill the
+  // buffer of stage kt-1 with stage kt+NS-1) right before that last step, so a wave that waits at
+  // the barrier leaves a full step of MFMAs queued behind it.
+  bf16x8_t fa[2][FM], fb[2][FN];
+  auto read_frags = [&](int buf, const unsigned char* base, int kk) {
+    const int sw = ((kk * 2 + hf) ^ key) << 4;
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      const int sw = ((kk * 2 + hf) ^ key) << 4;
-      bf16x8_t fa[FM], fb[FN];
+    for (int i = 0; i < FM; ++i) fa[buf][i] = *reinterpret_cast<const bf16x8_t*>(base + offA[i] + sw);
 #pragma unroll
-      for (int i = 0; i < FM; ++i) fa[i] = *reinterpret_cast<const bf16x8_t*>(base + offA[i] + sw);
+    for (int j = 0; j < FN; ++j) fb[buf][j] = *reinterpret_cast<const bf16x8_t*>(base + offB[j] + sw);
+  };
+  // One K-step: the FM*FN MFMAs on fragment set `cur`, with the FM+FN ds_reads that fetch set
+  // `cur ^ 1` (K-step kk_next of the stage at `nbase`) slotted in between them, one read after each
+  // of the first MFMAs, so that every read is issued while an MFMA occupies the matrix pipe.
+  auto step = [&](int cur, const unsigned char* nbase, int kk_next, int dma_kt, int dma_part) {
+    const int sw = ((kk_next * 2 + hf) ^ key) << 4;
+    const int nxt = cur ^ 1;
 #pragma unroll
-      for (int j = 0; j < FN; ++j) fb[j] = *reinterpret_cast<const bf16x8_t*>(base + offB[j] + sw);
+    for (int idx = 0; idx < FM * FN; ++idx) {
+      const int i = idx / FN, j = idx % FN;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0);
 #pragma unroll
-      for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+      for (int r = 0; r < FM + FN; ++r) {
+        if ((r < FM * FN ? r : FM * FN - 1) != idx) continue;   // read r goes after MFMA min(r, last)
+        if (r < FM) fa[nxt][r] = *reinterpret_cast<const bf16x8_t*>(nbase + offA[r] + sw);
+        else fb[nxt][r - FM] = *reinterpret_cast<const bf16x8_t*>(nbase + offB[r - FM] + sw);
+      }
+      if (idx == 0 && dma_kt >= 0) issue_part(dma_kt, dma_part);   // asm volatile: stays in program order
     }
-    if (more) sstore((kt + 1) & 1);
-    __syncthreads();
+#pragma unroll
+    for (int idx = 0; idx < FM * FN; ++idx) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA, then the LDS reads of its slot
+#pragma unroll
+      for (int r = 0; r < FM + FN; ++r)
+        if ((r < FM * FN ? r : FM * FN - 1) == idx) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+#pragma unroll
+  for (int st = 0; st < NS - 1; ++st)
+    if (st < nk) {
+#pragma unroll
+      for (int part = 0; part < KS; ++part) issue_part(st, part);
+    }
+  if (nk >= NS - 1) wait_vmcnt<(NS - 2) * LPS>();
+  else wait_vmcnt<0>();
+  lds_barrier();
+  // Drain scalar loads here, so that only in-order LDS reads are pending when the loop is entered
+  // and the compiler can wait for "all but the newest reads" instead of lgkmcnt(0) at its head.
+  __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
+  read_frags(0, smem, 0);
+  __builtin_amdgcn_sched_barrier(0);
+  for (int kt = 0; kt < nk; ++kt) {
+    const unsigned char* base = smem + (kt % NS) * STAGE_BYTES;
+    // parts 1 .. KS-1 of stage kt+NS-2 (its part 0 went out with the last K-step of iteration kt-1)
+    const int dma_a = (kt >= 1 && kt + NS - 2 < nk) ? kt + NS - 2 : -1;
+#pragma unroll
+    for (int kk = 0; kk < KS - 1; ++kk) step(kk & 1, base, kk + 1, dma_a, kk + 1);
+    if (kt + 1 < nk) {
+      // stage kt+1 has landed once at most the loads of the NS-3 younger stages are outstanding
+      if (kt + NS - 2 < nk) wait_vmcnt<(NS - 3) * LPS>();
+      else wait_vmcnt<0>();
+      lds_barrier();   // stage kt+1 visible to all; every wave is past its reads of stage kt-1
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // The reads of the next stage's first fragments are unconditional (after the last stage they
+    // fetch stale but valid LDS that nobody uses): a branch around them would make the compiler's
+    // LDS wait counts conservative at the join.  The buffer of stage kt-1 is free from here on:
+    // start refilling it with stage kt+NS-1.
+    step((KS - 1) & 1, smem + ((kt + 1) % NS) * STAGE_BYTES, 0, (kt + NS - 1 < nk) ? kt + NS - 1 : -1, 0);
   }
+  lds_barrier();
 
   // ------------------------------------------------------------------------------------------
   // C layout of the 32x32 MFMA: register r of a lane is row (r/4)*8 + hf*4 + r%4, column lj.
@@ -354,10 +437,10 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
-template <int BM, int BN, int WM, int WN, int EPI>
+template <int BM, int BN, int BK, int WM, int WN, int NS, int EPI>
 static void launch(GemmArgs& a, hipStream_t s) {
-  auto kern = k_gemm_bf16<BM, BN, WM, WN, EPI>;
-  constexpr int smem = 2 * (BM + BN) * BK * 2;
+  auto kern = k_gemm_bf16<BM, BN, BK, WM, WN, NS, EPI>;
+  constexpr int smem = NS * (BM + BN) * BK * 2;
   static bool attr_done = false;
   if (!attr_done) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
@@ -370,12 +453,33 @@ static void launch(GemmArgs& a, hipStream_t s) {
   hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), smem, s, a);
 }
 
+// Tile choice.  One CU moves about 64 B/clk from L2 into LDS, which a 128x128 tile needs in full to
+// keep its MFMAs fed (64 flop per loaded byte); 256-wide tiles halve that traffic and win whenever
+// there are enough of them to occupy the 256 CUs.  cost = rounds over the CUs x work per tile /
+// measured relative per-CU rate of the configuration.
+static double tile_cost(int M, int N, int bm, int bn, double rate) {
+  const double tiles = (double)((M + bm - 1) / bm) * ((N + bn - 1) / bn);
+  const double rounds = (double)(((long long)tiles + 255) / 256);
+  return rounds * bm * bn / rate;
+}
+static int pick_tile(int M, int N) {   // 0: 128x128, 1: 256x128, 2: 256x256
+  const double c0 = tile_cost(M, N, 128, 128, 0.80), c1 = tile_cost(M, N, 256, 128, 0.95),
+               c2 = tile_cost(M, N, 256, 256, 1.25);
+  if (M <= 128) return 0;
+  if (c2 <= c1 && c2 <= c0) return 2;
+  return c1 <= c0 ? 1 : 0;
+}
+
 void launch_gemm_qkv_bf16(const bf16* A, const bf16* wq, const bf16* wk, const bf16* wv, int M, int K,
                           const QkvEpilogue& e, Gate g, hipStream_t s) {
   GemmArgs a = {};
   a.A = A; a.B0 = wq; a.B1 = wk; a.B2 = wv;
   a.M = M; a.N = 3 * e.d; a.K = K; a.splits = 1; a.gate = g; a.qkv = e;
-  launch<128, 128, 2, 2, EPI_QKV>(a, s);
+  switch (pick_tile(M, a.N)) {
+    case 2: launch<256, 256, 32, 4, 2, 4, EPI_QKV>(a, s); break;
+    case 1: launch<256, 128, 32, 4, 2, 6, EPI_QKV>(a, s); break;
+    default: launch<128, 128, 64, 2, 2, 4, EPI_QKV>(a, s);
+  }
 }
 
 void launch_gemm_partial_bf16(const bf16* A, const bf16* W, float* part0, float* part1, int M, int N, int K,
@@ -383,7 +487,8 @@ void launch_gemm_partial_bf16(const bf16* A, const bf16* W, float* part0, float*
   GemmArgs a = {};
   a.A = A; a.B0 = W; a.M = M; a.N = N; a.K = K; a.splits = splits; a.gate = g;
   a.part0 = part0; a.part1 = part1;
-  launch<128, 128, 2, 2, EPI_PARTIAL>(a, s);
+  if (splits == 1 && pick_tile(M, N) == 2) launch<256, 256, 32, 4, 2, 4, EPI_PARTIAL>(a, s);
+  else launch<128, 128, 64, 2, 2, 4, EPI_PARTIAL>(a, s);
 }
 
 void launch_gemm_swiglu_bf16(const bf16* A, const bf16* wg, const bf16* wu, bf16* act, int M, int F, int K, Gate g,
@@ -391,7 +496,11 @@ void launch_gemm_swiglu_bf16(const bf16* A, const bf16* wg, const bf16* wu, bf16
   GemmArgs a = {};
   a.A = A; a.B0 = wg; a.B1 = wu; a.M = M; a.N = 2 * F; a.K = K; a.splits = 1; a.gate = g;
   a.act = act; a.F = F;
-  launch<128, 128, 2, 2, EPI_SWIGLU>(a, s);
+  switch (pick_tile(M, a.N)) {
+    case 2: launch<256, 256, 32, 4, 2, 4, EPI_SWIGLU>(a, s); break;
+    case 1: launch<256, 128, 32, 4, 2, 6, EPI_SWIGLU>(a, s); break;
+    default: launch<128, 128, 64, 2, 2, 4, EPI_SWIGLU>(a, s);
+  }
 }
 
 int lmhead_n_part(int V) { return (V + 127) / 128; }
@@ -401,9 +510,9 @@ void launch_gemm_lmhead_bf16(const bf16* A, const bf16* W, int M, int V, int K, 
   GemmArgs a = {};
   a.A = A; a.B0 = W; a.M = M; a.N = V; a.K = K; a.splits = 1; a.gate = g; a.lm = e;
   if (M <= 32)
-    launch<32, 128, 1, 4, EPI_LMHEAD>(a, s);
+    launch<32, 128, 64, 1, 4, 4, EPI_LMHEAD>(a, s);
   else
-    launch<128, 128, 2, 2, EPI_LMHEAD>(a, s);
+    launch<128, 128, 64, 2, 2, 4, EPI_LMHEAD>(a, s);
 }
 
 }  // namespace l2pd

@@ -138,15 +138,84 @@ __global__ void k_rmsnorm(float* h, const float* p0, const float* p1, RowMap src
   T* o = y + (size_t)r * d;
   for (int i = lane; i < d; i += 64) o[i] = from_f<T>(x[i] * inv * to_f<T>(gain[i]));
 }
+// Same, with the row held in registers: VPL float4 per lane, all loads of a row in flight at once,
+// one pass over memory.  Used when d is a multiple of 4 and d <= 1024 * VPL.
+template <typename T, int VPL>
+__global__ void __launch_bounds__(256) k_rmsnorm_vec(float* h, const float* p0, const float* p1, RowMap src,
+                                                    const T* gain, T* y, int rows, int d, float eps, Gate g) {
+  if (gate_skip(g)) return;
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  const size_t srow = (size_t)map_row(src, r, g.ctl);
+  const int d4 = d >> 2;
+  float4* x = reinterpret_cast<float4*>(h + srow * d);
+  const float4* a0 = p0 ? reinterpret_cast<const float4*>(p0 + srow * d) : nullptr;
+  const float4* a1 = p1 ? reinterpret_cast<const float4*>(p1 + srow * d) : nullptr;
+  float4 v[VPL];
+#pragma unroll
+  for (int k = 0; k < VPL; ++k) {
+    const int i = lane + 64 * k;
+    v[k] = i < d4 ? x[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  if (a0) {
+#pragma unroll
+    for (int k = 0; k < VPL; ++k) {
+      const int i = lane + 64 * k;
+      if (i < d4) {
+        float4 t = a0[i];
+        v[k].x += t.x; v[k].y += t.y; v[k].z += t.z; v[k].w += t.w;
+        if (a1) {
+          float4 u = a1[i];
+          v[k].x += u.x; v[k].y += u.y; v[k].z += u.z; v[k].w += u.w;
+        }
+        x[i] = v[k];
+      }
+    }
+  }
+  float ss = 0.f;
+#pragma unroll
+  for (int k = 0; k < VPL; ++k) ss += v[k].x * v[k].x + v[k].y * v[k].y + v[k].z * v[k].z + v[k].w * v[k].w;
+  ss = wave_sum(ss);
+  const float inv = rsqrtf(ss / (float)d + eps);
+  T* o = y + (size_t)r * d;
+#pragma unroll
+  for (int k = 0; k < VPL; ++k) {
+    const int i = lane + 64 * k;
+    if (i < d4) {
+      const T* gp = gain + 4 * i;
+      if constexpr (sizeof(T) == 4) {
+        float4 gg = *reinterpret_cast<const float4*>(gp);
+        *reinterpret_cast<float4*>(o + 4 * i) =
+            make_float4(v[k].x * inv * gg.x, v[k].y * inv * gg.y, v[k].z * inv * gg.z, v[k].w * inv * gg.w);
+      } else {
+        T o4[4] = {from_f<T>(v[k].x * inv * to_f<T>(gp[0])), from_f<T>(v[k].y * inv * to_f<T>(gp[1])),
+                   from_f<T>(v[k].z * inv * to_f<T>(gp[2])), from_f<T>(v[k].w * inv * to_f<T>(gp[3]))};
+        *reinterpret_cast<uint2*>(o + 4 * i) = *reinterpret_cast<const uint2*>(o4);
+      }
+    }
+  }
+}
+
+template <typename T>
+static void launch_rmsnorm_t(float* h, const float* p0, const float* p1, RowMap src, const T* gain, T* y, int rows,
+                             int d, float eps, Gate g, hipStream_t s) {
+  dim3 grid((rows + 3) / 4), block(256);
+  if (d % 4 == 0 && d <= 1024)
+    hipLaunchKernelGGL((k_rmsnorm_vec<T, 4>), grid, block, 0, s, h, p0, p1, src, gain, y, rows, d, eps, g);
+  else if (d % 4 == 0 && d <= 4096)
+    hipLaunchKernelGGL((k_rmsnorm_vec<T, 16>), grid, block, 0, s, h, p0, p1, src, gain, y, rows, d, eps, g);
+  else if (d % 4 == 0 && d <= 8192)
+    hipLaunchKernelGGL((k_rmsnorm_vec<T, 32>), grid, block, 0, s, h, p0, p1, src, gain, y, rows, d, eps, g);
+  else
+    hipLaunchKernelGGL(k_rmsnorm<T>, grid, block, 0, s, h, p0, p1, src, gain, y, rows, d, eps, g);
+}
 void launch_rmsnorm(float* h, const float* p0, const float* p1, RowMap src, const void* gain, int dtype, void* y,
                     int rows, int d, float eps, Gate g, hipStream_t s) {
-  dim3 grid((rows + 3) / 4), block(256);
   if (dtype == L2PD_FP32)
-    hipLaunchKernelGGL(k_rmsnorm<float>, grid, block, 0, s, h, p0, p1, src, (const float*)gain, (float*)y, rows, d,
-                       eps, g);
+    launch_rmsnorm_t<float>(h, p0, p1, src, (const float*)gain, (float*)y, rows, d, eps, g, s);
   else
-    hipLaunchKernelGGL(k_rmsnorm<bf16>, grid, block, 0, s, h, p0, p1, src, (const bf16*)gain, (bf16*)y, rows, d,
-                       eps, g);
+    launch_rmsnorm_t<bf16>(h, p0, p1, src, (const bf16*)gain, (bf16*)y, rows, d, eps, g, s);
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -32,7 +32,7 @@ import torch
 
 _M32 = 0xFFFFFFFF
 _MULT = 0x45D9F3B  # < 2**27, so products of 32-bit values stay below 2**59
-_CHUNK = 1 << 22
+_CHUNK = 1 << 24
 
 
 @dataclasses.dataclass(frozen=True)
