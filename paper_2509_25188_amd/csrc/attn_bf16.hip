@@ -60,6 +60,9 @@ __global__ void __launch_bounds__(NW * 64) k_attn_bf16(const bf16* __restrict__ 
 
   const bf16* kbase = kstore + (size_t)b * Tpad * d + h * DH;
   const bf16* vbase = vtstore + (size_t)(b * H + h) * DH * Tpad;
+  // LDS swizzle: the 64 banks sweep 256 bytes.  A K row is 256 B (DH = 128: key = row & 15 over its
+  // 16 chunks) or 128 B (DH = 64: two rows per sweep, key = (row >> 1) & 7); a V^T row is 128 B.
+  auto kkey = [](int r) { return DH == 128 ? (r & 15) : ((r >> 1) & 7); };
   const bf16* srcK[KCH];
   int dstK[KCH];
 #pragma unroll
@@ -67,7 +70,7 @@ __global__ void __launch_bounds__(NW * 64) k_attn_bf16(const bf16* __restrict__ 
     int c = tid + i * NT;
     int r = c / (DH / 8), cc = c % (DH / 8);
     srcK[i] = kbase + (size_t)r * d + cc * 8;
-    dstK[i] = r * K_ROW + ((cc ^ (r & 7)) << 4);
+    dstK[i] = r * K_ROW + ((cc ^ kkey(r)) << 4);
   }
   const bf16* srcV[VCH];
   int dstV[VCH];
@@ -76,7 +79,7 @@ __global__ void __launch_bounds__(NW * 64) k_attn_bf16(const bf16* __restrict__ 
     int c = tid + i * NT;
     int r = c >> 3, cc = c & 7;
     srcV[i] = vbase + (size_t)r * Tpad + cc * 8;
-    dstV[i] = K_BYTES + r * (KT * 2) + ((cc ^ (r & 7)) << 4);
+    dstV[i] = K_BYTES + r * (KT * 2) + ((cc ^ ((r >> 1) & 7)) << 4);
   }
   u32x4 rk[KCH], rv[VCH];
   auto gload = [&](int k0) {
@@ -100,7 +103,7 @@ __global__ void __launch_bounds__(NW * 64) k_attn_bf16(const bf16* __restrict__ 
     for (int r = 0; r < 16; ++r) o[f][r] = 0.f;
   float m = -INFINITY, lsum = 0.f;
   const float sc = rsqrtf((float)DH) * 1.4426950408889634f;   // softmax scale folded with log2(e)
-  const int key = lj & 7;
+  const int keyK = kkey(lj), keyV = (lj >> 1) & 7;   // fragment rows are lj modulo 32
 
   const int n_tiles = (Tk + KT - 1) / KT;
   gload(0);
@@ -121,7 +124,7 @@ __global__ void __launch_bounds__(NW * 64) k_attn_bf16(const bf16* __restrict__ 
       const unsigned char* krow = base + (sub * 32 + lj) * K_ROW;
 #pragma unroll
       for (int kk = 0; kk < KK; ++kk) {
-        bf16x8_t fk = *reinterpret_cast<const bf16x8_t*>(krow + (((kk * 2 + hf) ^ key) << 4));
+        bf16x8_t fk = *reinterpret_cast<const bf16x8_t*>(krow + (((kk * 2 + hf) ^ keyK) << 4));
         s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk, fq[kk], s[sub], 0, 0, 0);
       }
     }
@@ -164,8 +167,8 @@ __global__ void __launch_bounds__(NW * 64) k_attn_bf16(const bf16* __restrict__ 
 #pragma unroll
       for (int f = 0; f < FO; ++f) {
         const unsigned char* vrow = base + K_BYTES + (f * 32 + lj) * (KT * 2) + hf * 8;
-        u32x2 v0 = *reinterpret_cast<const u32x2*>(vrow + (((m16 * 2) ^ key) << 4));
-        u32x2 v1 = *reinterpret_cast<const u32x2*>(vrow + (((m16 * 2 + 1) ^ key) << 4));
+        u32x2 v0 = *reinterpret_cast<const u32x2*>(vrow + (((m16 * 2) ^ keyV) << 4));
+        u32x2 v1 = *reinterpret_cast<const u32x2*>(vrow + (((m16 * 2 + 1) ^ keyV) << 4));
         u32x4 vw = {v0.x, v0.y, v1.x, v1.y};
         bf16x8_t fv = __builtin_bit_cast(bf16x8_t, vw);
         o[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv, fp, o[f], 0, 0, 0);
@@ -207,7 +210,7 @@ static void launch(const bf16* q, const bf16* kstore, const bf16* vtstore, bf16*
 
 void launch_attn_bf16(const bf16* q, const bf16* kstore, const bf16* vtstore, bf16* out, int B, int Tq, int Tk,
                       int Tpad, int H, int Dh, Gate g, hipStream_t s) {
-  const bool small = Tq <= 64;
+  const bool small = Tq <= 64;   // short query blocks (prefix-cache steps): 64 queries per workgroup
   if (Dh == 128) {
     if (small) launch<128, 2>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, g, s);
     else launch<128, 4>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, g, s);

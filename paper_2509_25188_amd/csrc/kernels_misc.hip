@@ -201,6 +201,7 @@ template <typename T>
 static void launch_rmsnorm_t(float* h, const float* p0, const float* p1, RowMap src, const T* gain, T* y, int rows,
                              int d, float eps, Gate g, hipStream_t s) {
   dim3 grid((rows + 3) / 4), block(256);
+  if (rows <= 4096) { grid = dim3(rows); block = dim3(64); }   // few rows: one wavefront per workgroup fills more CUs
   if (d % 4 == 0 && d <= 1024)
     hipLaunchKernelGGL((k_rmsnorm_vec<T, 4>), grid, block, 0, s, h, p0, p1, src, gain, y, rows, d, eps, g);
   else if (d % 4 == 0 && d <= 4096)
