@@ -37,7 +37,13 @@ a random-init model, for which the paper prints no worked example:
 PARITY UNPINNED for `generate` beyond its invariants and special cases.
 
 Precision: `dtype` is numpy float32 (default) or float64.  Weights given as
-uint16 arrays are bf16 bit patterns and are widened exactly.
+uint16 arrays are bf16 bit patterns and are widened exactly.  For bf16 models
+("bf16 weights, fp32 accumulate") the model can also be evaluated with every
+matrix-product INPUT rounded to bf16 (`gemm_input="bf16"`: normalised
+activations, rotated q and k, v, softmax probabilities, attention output,
+SwiGLU output), accumulation, residual stream, norms and softmax staying in
+`dtype`.  That is the arithmetic a bf16 matrix unit performs; comparing against
+both modes separates implementation error from the error of the number format.
 """
 from __future__ import annotations
 
@@ -51,6 +57,14 @@ def widen(w, dtype):
     if w.dtype == np.uint16:
         return (w.astype(np.uint32) << 16).view(np.float32).astype(dtype, copy=False)
     return w.astype(dtype, copy=False)
+
+
+def round_bf16(x):
+    """Round to the nearest bf16 value (ties to even), result kept in x's dtype."""
+    a = np.ascontiguousarray(x, dtype=np.float32)
+    u = a.view(np.uint32)
+    r = ((u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) & np.uint32(0xFFFF0000)).view(np.float32)
+    return r.astype(np.asarray(x).dtype, copy=False)
 
 
 def rmsnorm(x, g, eps):
@@ -81,15 +95,18 @@ def softmax(z, axis=-1):
     return e / np.sum(e, axis=axis, keepdims=True)
 
 
-def attention(q, k, v):
+def attention(q, k, v, rin=None):
     """Bidirectional attention.  q: [Tq, H, Dh]; k, v: [Tk, H, Dh] -> [Tq, H, Dh].
 
     Every query sees every key: there is no causal mask (the dLLM refines the
-    whole sequence at once, Sec. 1).
+    whole sequence at once, Sec. 1).  `rin`, if given, rounds the probabilities
+    before they enter the product with v.
     """
     dh = q.shape[-1]
     s = np.einsum("qhd,khd->hqk", q, k) / q.dtype.type(np.sqrt(dh))
     p = softmax(s, axis=-1)
+    if rin is not None:
+        p = rin(p)
     return np.einsum("hqk,khd->qhd", p, v)
 
 
@@ -106,10 +123,13 @@ class Model:
     """The mask predictor.  `shape` needs n_layers, d_model, n_heads, head_dim, rope_base, rms_eps;
     `weights` maps tensor names to arrays ([out, in] row-major matrices)."""
 
-    def __init__(self, shape, weights, dtype=np.float32):
+    def __init__(self, shape, weights, dtype=np.float32, gemm_input="fp32"):
         self.s = shape
         self.w = weights
         self.dtype = np.dtype(dtype)
+        assert gemm_input in ("fp32", "bf16")
+        self.rin = round_bf16 if gemm_input == "bf16" else (lambda x: x)
+        self.p_rin = round_bf16 if gemm_input == "bf16" else None
 
     def W(self, name):
         return widen(self.w[name], self.dtype)
@@ -122,23 +142,23 @@ class Model:
     def qkv(self, l, h, pos):
         """Layer l's rotated queries/keys and values for hidden rows h at positions pos."""
         s, p = self.s, f"layers.{l}."
-        a = rmsnorm(h, self.W(p + "attn_norm_g"), s.rms_eps)
+        a = self.rin(rmsnorm(h, self.W(p + "attn_norm_g"), s.rms_eps))
         t = a.shape[0]
         q = (a @ self.W(p + "wq").T).reshape(t, s.n_heads, s.head_dim)
         k = (a @ self.W(p + "wk").T).reshape(t, s.n_heads, s.head_dim)
         v = (a @ self.W(p + "wv").T).reshape(t, s.n_heads, s.head_dim)
-        return rope(q, pos, s.rope_base), rope(k, pos, s.rope_base), v
+        return self.rin(rope(q, pos, s.rope_base)), self.rin(rope(k, pos, s.rope_base)), self.rin(v)
 
     def finish_layer(self, l, h, o):
         """Attention output projection + residual, then the SwiGLU FFN + residual."""
         p = f"layers.{l}."
-        h = h + o.reshape(h.shape[0], -1) @ self.W(p + "wo").T
-        f = rmsnorm(h, self.W(p + "ffn_norm_g"), self.s.rms_eps)
-        act = silu(f @ self.W(p + "w_gate").T) * (f @ self.W(p + "w_up").T)
+        h = h + self.rin(o.reshape(h.shape[0], -1)) @ self.W(p + "wo").T
+        f = self.rin(rmsnorm(h, self.W(p + "ffn_norm_g"), self.s.rms_eps))
+        act = self.rin(silu(f @ self.W(p + "w_gate").T) * (f @ self.W(p + "w_up").T))
         return h + act @ self.W(p + "w_down").T
 
     def head(self, h_rows):
-        return rmsnorm(h_rows, self.W("final_norm_g"), self.s.rms_eps) @ self.W("lm_head").T
+        return self.rin(rmsnorm(h_rows, self.W("final_norm_g"), self.s.rms_eps)) @ self.W("lm_head").T
 
     def forward(self, tokens, row_begin=0, row_count=None):
         """logits[row_count, V] of one sequence `tokens` [T]; full bidirectional forward."""
@@ -149,7 +169,7 @@ class Model:
         h = self.embed(tokens)
         for l in range(self.s.n_layers):
             q, k, v = self.qkv(l, h, pos)
-            h = self.finish_layer(l, h, attention(q, k, v))
+            h = self.finish_layer(l, h, attention(q, k, v, self.p_rin))
         return self.head(h[row_begin:row_begin + row_count])
 
     # ---- prefix KV cache (Sec. 4.3) ----
@@ -163,7 +183,7 @@ class Model:
             q, k, v = self.qkv(l, h, pos)
             cache.append((k, v))
             if l + 1 < self.s.n_layers:
-                h = self.finish_layer(l, h, attention(q, k, v))
+                h = self.finish_layer(l, h, attention(q, k, v, self.p_rin))
         return cache
 
     def forward_block_cached(self, cache, block_tokens, c):
@@ -175,7 +195,7 @@ class Model:
         for l in range(self.s.n_layers):
             q, k, v = self.qkv(l, h, pos)
             kc, vc = cache[l]
-            o = attention(q, np.concatenate([kc, k], axis=0), np.concatenate([vc, v], axis=0))
+            o = attention(q, np.concatenate([kc, k], axis=0), np.concatenate([vc, v], axis=0), self.p_rin)
             h = self.finish_layer(l, h, o)
         return self.head(h)
 

@@ -22,11 +22,11 @@ from paper_2509_25188_amd import binding as Bd
 from paper_2509_25188_amd import synth
 
 
-def oracle_model(shape: synth.ModelShape, weights, dtype=np.float32) -> O.Model:
+def oracle_model(shape: synth.ModelShape, weights, dtype=np.float32, gemm_input="fp32") -> O.Model:
     s = types.SimpleNamespace(**{k: getattr(shape, k) for k in
                                  ("n_layers", "d_model", "n_heads", "head_dim", "d_ffn", "vocab", "mask_id",
                                   "eos_id", "rope_base", "rms_eps")})
-    return O.Model(s, {k: synth.to_numpy(v) for k, v in weights.items()}, dtype)
+    return O.Model(s, {k: synth.to_numpy(v) for k, v in weights.items()}, dtype, gemm_input)
 
 
 def to_dev(weights, device="cuda"):
@@ -159,3 +159,27 @@ def cfg_for(w: synth.Workload, tau=None):
     bias = (w.model.eos_id, w.bias_from, w.bias_value) if w.bias_value else None
     return Bd.Engine.cfg_struct(w.gen_len, w.block_len, w.threshold if tau is None else tau, w.eotp,
                                 w.prefix_cache, bias)
+
+
+def random_state(w: synth.Workload, seed: int, block: int, n_committed: int, b: int = 0):
+    """A teacher-forced state: prompt of sequence b, blocks before `block` committed with random
+    tokens, `n_committed` random positions of the active block committed, the rest masked."""
+    rng = np.random.default_rng(seed)
+    prompt = synth.make_prompt(1234, max(w.batch, b + 1), w.prompt_len, w.prompt_hi)[b].numpy()
+    X = np.concatenate([prompt.astype(np.int64), np.full(w.gen_len, w.model.mask_id, dtype=np.int64)])
+    lo = w.prompt_len + block * w.block_len
+    X[w.prompt_len:lo] = rng.integers(0, w.prompt_hi, lo - w.prompt_len)
+    idx = rng.choice(w.block_len, n_committed, replace=False)
+    X[lo + idx] = rng.integers(0, w.prompt_hi, n_committed)
+    return X
+
+
+def oracle_step_record(model, X, w: synth.Workload, flt_np, block: int):
+    """The oracle's record of one step taken from state X (X is not modified)."""
+    bias = (w.model.eos_id, w.bias_from, w.bias_value) if w.bias_value else None
+    Xc = np.array(X, copy=True)
+    cache = model.prefix_kv(Xc[:w.prompt_len + block * w.block_len]) if w.prefix_cache else None
+    rec = O.denoise_step(model, Xc, w.prompt_len, block, w.block_len, w.model.mask_id, flt_np, w.threshold, bias,
+                         cache)
+    rec.update(X_before=np.array(X, copy=True), block=block)
+    return rec

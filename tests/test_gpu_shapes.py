@@ -1,0 +1,135 @@
+"""GPU parity at the real widths of the workloads (8B-shaped layers, full vocabulary), at reduced
+depth so that the CPU oracle finishes in seconds, on teacher-forced states; plus properties that hold
+at any size on the full-depth launch configuration."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2509_25188_amd import binding as Bd
+from paper_2509_25188_amd import synth
+from tests import parity as Pz
+
+pytestmark = pytest.mark.gpu
+SEED = 1234
+
+
+def setup(w: synth.Workload, max_batch=1):
+    weights = synth.make_weights(w.model, SEED, "cpu")
+    ora = Pz.oracle_model(w.model, weights)
+    eng = Bd.Engine(w.model, Pz.to_dev(weights), max_batch, w.prompt_len + w.gen_len, w.prefix_cache)
+    del weights
+    flt = synth.make_filter(SEED, w.block_len, w.filter_hidden)
+    return eng, ora, flt
+
+
+def forced_steps(w, eng, ora, flt, states, rep):
+    fdev = {k: v.cuda() for k, v in flt.items()}
+    cfg = Pz.cfg_for(w)
+    for block, n_committed, seed in states:
+        X = Pz.random_state(w, seed, block, n_committed)
+        rec = Pz.oracle_step_record(ora, X, w, Pz.np_filter(flt), block)
+        Xd = torch.tensor(X, dtype=torch.int32, device="cuda").view(1, -1)
+        state = torch.tensor([[block, 7, 0]], dtype=torch.int32, device="cuda")
+        taps = eng.denoise_step(Xd, w.prompt_len, state, fdev, cfg, want_logits=True)
+        torch.cuda.synchronize()
+        Pz.check_step(rec, taps, 0, w.model, w.threshold, Pz.tol_for(w.model), rep)
+
+
+def test_8b_width_two_layers_full_recompute():
+    # the benchmarked shape: 512 rows, d 4096, F 12288, vocabulary 126464, block 32
+    w = synth.with_layers(synth.WORKLOADS["8b_g256"], 2)
+    eng, ora, flt = setup(w)
+    rep = Pz.StepReport()
+    forced_steps(w, eng, ora, flt, [(0, 0, 1), (3, 11, 2), (7, 31, 3)], rep)
+    print("8b width, 2 layers:", rep)
+    assert rep.max_logit_err < 2e-2
+
+
+def test_8b_width_eotp_workload_bias_and_long_window():
+    # T = 1280 (ragged against 256-row tiles), EOS logit bias from generation position 300
+    w = synth.with_layers(synth.WORKLOADS["8b_g1024_eotp"], 1)
+    eng, ora, flt = setup(w)
+    rep = Pz.StepReport()
+    forced_steps(w, eng, ora, flt, [(9, 5, 4), (2, 0, 5)], rep)   # block 9 holds position 300
+    print("8b width, eotp workload:", rep)
+    assert rep.max_logit_err < 2e-2
+    # block 9 = generation positions 288..319: the bias makes EOS the greedy token from 300 on
+    X = Pz.random_state(w, 4, 9, 5)
+    rec = Pz.oracle_step_record(ora, X, w, Pz.np_filter(flt), 9)
+    assert np.all(rec["pre"][12:] == w.model.eos_id) and not np.any(rec["pre"][:12] == w.model.eos_id)
+    assert np.all(rec["conf"][12:] > 0.99)
+
+
+def test_8b_width_prefix_cache_block64():
+    w = synth.with_layers(synth.WORKLOADS["8b_b32_prefix"], 2)
+    w = dataclasses.replace(w, batch=1)
+    eng, ora, flt = setup(w)
+    rep = Pz.StepReport()
+    forced_steps(w, eng, ora, flt, [(0, 0, 6), (5, 40, 7)], rep)
+    print("8b width, prefix cache, block 64:", rep)
+    assert rep.max_logit_err < 2e-2
+
+
+def test_mid_workload_full_depth_batch8():
+    w = synth.WORKLOADS["mid"]
+    eng, ora, flt = setup(w, max_batch=w.batch)
+    rep = Pz.StepReport()
+    forced_steps(w, eng, ora, flt, [(0, 0, 8), (4, 20, 9), (7, 30, 10)], rep)
+    print("mid, 8 layers:", rep)
+    assert rep.max_logit_err < 2e-2
+    # whole decode of the batch of 8: invariants, and every row equals its own single run
+    fdev = {k: v.cuda() for k, v in flt.items()}
+    cfg = Pz.cfg_for(w)
+    prompt = synth.make_prompt(SEED, w.batch, w.prompt_len, w.prompt_hi, "cuda")
+    tok, st, dl = eng.generate(prompt, fdev, cfg)
+    tok = tok.cpu().numpy()
+    assert not np.any(tok == w.model.mask_id)
+    assert np.all(dl.cpu().numpy() == w.gen_len)
+    steps = st.cpu().numpy()
+    assert np.all(steps >= w.gen_len // w.block_len) and np.all(steps <= w.gen_len)
+    for b in (0, 5):
+        t1, s1, _ = eng.generate(prompt[b:b + 1].contiguous(), fdev, cfg)
+        same = np.array_equal(t1.cpu().numpy()[0], tok[b])
+        print(f"mid: batch row {b} vs its own run: identical={same} steps {int(s1[0])} vs {steps[b]}")
+        # different batch sizes pick different GEMM tiles (same K order per element), so rows agree
+        assert same and int(s1[0]) == steps[b]
+
+
+def test_8b_full_depth_step_against_both_oracle_precisions():
+    """The benchmarked configuration itself (32 layers, 512 rows), one teacher-forced step.
+
+    A random-init network of this depth amplifies rounding noise: the oracle evaluated with
+    bf16-rounded matrix-product inputs and the oracle with fp32 activations already differ from each
+    other by about 2e-2 of the largest logit (7e-3 at one layer, 1.4e-2 at eight layers, measured).
+    The HIP path must lie within that same distance of both (a kernel error would show as a distance
+    well above the distance between the two oracles), and its decisions must follow the margin rules
+    against the bf16-input oracle, whose arithmetic it implements."""
+    w = synth.WORKLOADS["8b_g256"]
+    weights = synth.make_weights(w.model, SEED, "cpu")
+    ora16 = Pz.oracle_model(w.model, weights, gemm_input="bf16")
+    ora32 = Pz.oracle_model(w.model, weights)
+    eng = Bd.Engine(w.model, Pz.to_dev(weights), 1, w.prompt_len + w.gen_len)
+    del weights
+    flt = synth.make_filter(SEED, w.block_len, w.filter_hidden)
+    fdev = {k: v.cuda() for k, v in flt.items()}
+    block = 3
+    X = Pz.random_state(w, 2, block, 11)
+    rec16 = Pz.oracle_step_record(ora16, X, w, Pz.np_filter(flt), block)
+    Xd = torch.tensor(X, dtype=torch.int32, device="cuda").view(1, -1)
+    state = torch.tensor([[block, 7, 0]], dtype=torch.int32, device="cuda")
+    taps = eng.denoise_step(Xd, w.prompt_len, state, fdev, Pz.cfg_for(w), want_logits=True)
+    torch.cuda.synchronize()
+    lo = w.prompt_len + block * w.block_len
+    ref32 = ora32.forward(X, lo, w.block_len)
+    got = taps["logits"][0].cpu().numpy()
+    e16, e32 = Pz.rel_err(got, rec16["logits"]), Pz.rel_err(got, ref32)
+    e_fmt = Pz.rel_err(rec16["logits"], ref32)
+    print(f"8b full depth: logit distance HIP/bf16-input oracle {e16:.3e}, HIP/fp32-activation oracle {e32:.3e}, "
+          f"between the two oracles {e_fmt:.3e}")
+    assert e16 < 1.5 * e_fmt + 5e-3 and e32 < 1.5 * e_fmt + 5e-3
+    assert e16 < 4e-2 and e32 < 5e-2
+    rep = Pz.StepReport()
+    Pz.check_step(rec16, taps, 0, w.model, w.threshold, 4e-2, rep)
+    print("8b full depth decisions vs bf16-input oracle:", rep)

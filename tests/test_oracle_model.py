@@ -267,3 +267,25 @@ def bf_forward_cached(s, w, prefix, block):
         hp = [finish(l, hp[t], attend(qp[t][0], pk, pv)) for t in range(len(hp))]
         hb = [finish(l, hb[t], attend(qb[t][0], pk + bk, pv + bv)) for t in range(len(hb))]
     return [bf_matvec(W["lm_head"], bf_norm(hr, W["final_norm_g"], s.rms_eps)) for hr in hb]
+
+
+def test_round_bf16_matches_the_library_conversion_and_ties_to_even():
+    import torch
+    r = np.random.default_rng(3)
+    x = np.concatenate([r.normal(size=5000) * 10.0 ** r.integers(-6, 6, 5000), [0.0, -0.0, 1.0, 65504.0]]).astype(np.float32)
+    ref = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    np.testing.assert_array_equal(O.round_bf16(x), ref)
+    # 1 + 2^-8 is halfway between bf16 neighbours 1 and 1 + 2^-7: ties go to the even mantissa
+    assert O.round_bf16(np.array([1.0 + 2.0 ** -8], dtype=np.float32))[0] == 1.0
+    assert O.round_bf16(np.array([1.0 + 3 * 2.0 ** -8], dtype=np.float32))[0] == np.float32(1.0 + 2.0 ** -6)
+    assert O.round_bf16(np.array([0.5, 2.0], dtype=np.float64)).dtype == np.float64
+
+
+def test_bf16_gemm_inputs_stay_close_to_full_precision():
+    s = tiny_shape()
+    w = {k: v.astype(np.float32) for k, v in tiny_weights(s, 8).items()}
+    tokens = np.array([1, 4, 10, 10, 8, 2])
+    a = O.Model(s, w, np.float32).forward(tokens)
+    b = O.Model(s, w, np.float32, gemm_input="bf16").forward(tokens)
+    e = np.max(np.abs(a - b)) / np.max(np.abs(a))
+    assert 1e-5 < e < 3e-2          # rounding is present, and of the size of bf16's 2^-9 steps
