@@ -53,6 +53,22 @@ __device__ __forceinline__ unsigned short f2bf(float f) {   // round to nearest 
   return (unsigned short)(u >> 16);
 }
 
+// 4x4 transpose inside every aligned group of four lanes: on entry lane j of a group holds
+// element (j, k) in w[k]; on return it holds element (k, j).  In the MFMA C layout a lane owns one
+// column and four consecutive rows, so the transpose gives each lane four consecutive columns of
+// one row, which it can store as one 8-byte piece instead of four 2-byte ones.
+__device__ __forceinline__ void quad_transpose(unsigned (&w)[4], int lane) {
+  const bool o1 = lane & 1, o2 = lane & 2;
+  unsigned s0 = o1 ? w[0] : w[1], s1 = o1 ? w[2] : w[3];
+  s0 = __shfl_xor(s0, 1, 64);
+  s1 = __shfl_xor(s1, 1, 64);
+  if (o1) { w[0] = s0; w[2] = s1; } else { w[1] = s0; w[3] = s1; }
+  unsigned t0 = o2 ? w[0] : w[2], t1 = o2 ? w[1] : w[3];
+  t0 = __shfl_xor(t0, 2, 64);
+  t1 = __shfl_xor(t1, 2, 64);
+  if (o2) { w[0] = t0; w[1] = t1; } else { w[2] = t0; w[3] = t1; }
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {   // s_waitcnt vmcnt(N) only (expcnt / lgkmcnt untouched)
   static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
@@ -284,19 +300,34 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
         }
       }
   } else if constexpr (EPI == EPI_SWIGLU) {
+    const int lr = lj & 3, c4 = lj & ~3;   // after the transpose: row within the group, first of 4 columns
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
       for (int p = 0; p < FN / 2; ++p) {
-        int G = tile_n * (BN / 64) + wn * (FN / 2) + p;
-        int col = G * 32 + lj;
+        const int G = tile_n * (BN / 64) + wn * (FN / 2) + p;
+        const int col = G * 32 + c4;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          int row = row_base + i * 32 + (r >> 2) * 8 + hf * 4 + (r & 3);
-          float gt = acc[i][2 * p][r], up = acc[i][2 * p + 1][r];
-          float v = gt / (1.f + __expf(-gt)) * up;
-          if (row < a.M && col < a.F)
-            reinterpret_cast<unsigned short*>(a.act)[(size_t)row * a.F + col] = f2bf(v);
+        for (int rq = 0; rq < 4; rq += 2) {   // two row groups share one transpose: low / high half words
+          unsigned w[4];
+#pragma unroll
+          for (int rr = 0; rr < 4; ++rr) {
+            const float g0 = acc[i][2 * p][rq * 4 + rr], u0 = acc[i][2 * p + 1][rq * 4 + rr];
+            const float g1 = acc[i][2 * p][rq * 4 + 4 + rr], u1 = acc[i][2 * p + 1][rq * 4 + 4 + rr];
+            const float s0 = __fmul_rn(__fdiv_rn(g0, __fadd_rn(1.f, __expf(-g0))), u0);
+            const float s1 = __fmul_rn(__fdiv_rn(g1, __fadd_rn(1.f, __expf(-g1))), u1);
+            w[rr] = (unsigned)f2bf(s0) | ((unsigned)f2bf(s1) << 16);
+          }
+          quad_transpose(w, lane);
+#pragma unroll
+          for (int h2 = 0; h2 < 2; ++h2) {
+            const int row = row_base + i * 32 + (rq + h2) * 8 + hf * 4 + lr;
+            uint2 o;
+            o.x = h2 ? (w[0] >> 16) | (w[1] & 0xffff0000u) : (w[0] & 0xffffu) | (w[1] << 16);
+            o.y = h2 ? (w[2] >> 16) | (w[3] & 0xffff0000u) : (w[2] & 0xffffu) | (w[3] << 16);
+            if (row < a.M && col < a.F)   // F is a multiple of 4, so a group of 4 columns is in or out as a whole
+              *reinterpret_cast<uint2*>(reinterpret_cast<unsigned short*>(a.act) + (size_t)row * a.F + col) = o;
+          }
         }
       }
   } else if constexpr (EPI == EPI_QKV) {
@@ -342,25 +373,56 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
             }
           }
         } else {
+          // Rotation of Q and K.  All table reads of the fragment are issued before its first
+          // store: the compiler cannot move a load above a store that might alias it, so an
+          // interleaved order would pay one memory round trip per element.
+          unsigned short* dst = reinterpret_cast<unsigned short*>(mat == 0 ? e.q : e.kstore);
+          float cs[16], sn[16];
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            int row = row_base + i * 32 + (r >> 2) * 8 + hf * 4 + (r & 3);
+          for (int rq = 0; rq < 4; ++rq) {
+            const int row0 = row_base + i * 32 + rq * 8 + hf * 4;
+            int t = row0 % e.Tq;
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+              const int r = rq * 4 + rr;
+              const bool live = row0 + rr < a.M;
+              cs[r] = live ? e.cos_t[(size_t)(e.pos0 + t) * half + dim] : 0.f;
+              sn[r] = live ? e.sin_t[(size_t)(e.pos0 + t) * half + dim] : 0.f;
+              if (++t == e.Tq) t = 0;
+            }
+          }
+          // rotate, round, and turn "one column, four rows" per lane into "four columns, one row"
+          const int lr = lj & 3, c4 = gi * 32 + (lj & ~3);
+#pragma unroll
+          for (int rq = 0; rq < 4; ++rq) {
+            unsigned w[4];
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+              const int r = rq * 4 + rr;
+              const float x1 = acc[i][2 * p][r], x2 = acc[i][2 * p + 1][r];
+              // explicit roundings: every tile configuration must produce the same bits, whatever
+              // contraction into fused multiply-adds the compiler would pick for each of them
+              const float o1 = __fmaf_rn(x1, cs[r], -__fmul_rn(x2, sn[r]));
+              const float o2 = __fmaf_rn(x2, cs[r], __fmul_rn(x1, sn[r]));
+              w[rr] = (unsigned)f2bf(o1) | ((unsigned)f2bf(o2) << 16);
+            }
+            quad_transpose(w, lane);
+            const int row = row_base + i * 32 + rq * 8 + hf * 4 + lr;
             if (row >= a.M) continue;
-            int b = row / e.Tq, pos = e.pos0 + row % e.Tq;
-            float cs = e.cos_t[(size_t)pos * half + dim], sn = e.sin_t[(size_t)pos * half + dim];
-            float x1 = acc[i][2 * p][r], x2 = acc[i][2 * p + 1][r];
-            float o1 = x1 * cs - x2 * sn, o2 = x2 * cs + x1 * sn;
-            unsigned short* dst;
             size_t o;
             if (mat == 0) {
-              dst = reinterpret_cast<unsigned short*>(e.q);
-              o = (size_t)row * e.d + head * e.Dh + dim;
+              o = (size_t)row * e.d + head * e.Dh + c4;
             } else {
-              dst = reinterpret_cast<unsigned short*>(e.kstore);
-              o = ((size_t)b * e.Tpad + pos) * e.d + head * e.Dh + dim;
+              const int b = row / e.Tq, pos = e.pos0 + row % e.Tq;
+              o = ((size_t)b * e.Tpad + pos) * e.d + head * e.Dh + c4;
             }
-            dst[o] = f2bf(o1);
-            dst[o + half] = f2bf(o2);
+            uint2 lo, hi;   // feature c4..c4+3 and its partner c4+half..c4+half+3
+            lo.x = (w[0] & 0xffffu) | (w[1] << 16);
+            lo.y = (w[2] & 0xffffu) | (w[3] << 16);
+            hi.x = (w[0] >> 16) | (w[1] & 0xffff0000u);
+            hi.y = (w[2] >> 16) | (w[3] & 0xffff0000u);
+            *reinterpret_cast<uint2*>(dst + o) = lo;
+            *reinterpret_cast<uint2*>(dst + o + half) = hi;
           }
         }
       }
@@ -456,18 +518,23 @@ static void launch(GemmArgs& a, hipStream_t s) {
 // Tile choice.  One CU moves about 64 B/clk from L2 into LDS, which a 128x128 tile needs in full to
 // keep its MFMAs fed (64 flop per loaded byte); 256-wide tiles halve that traffic and win whenever
 // there are enough of them to occupy the 256 CUs.  cost = rounds over the CUs x work per tile /
-// measured relative per-CU rate of the configuration.
+// measured relative per-CU rate of the configuration.  256x192 exists because 512 rows x 24576
+// gate/up columns make exactly 256 such tiles, one round with every CU busy.  (With random operands
+// the chip is power limited: the shader clock sits near 1.5-1.6 GHz inside these kernels, and a
+// register-resident MFMA stream alone tops out at 1.78 PFLOP/s.)
 static double tile_cost(int M, int N, int bm, int bn, double rate) {
   const double tiles = (double)((M + bm - 1) / bm) * ((N + bn - 1) / bn);
   const double rounds = (double)(((long long)tiles + 255) / 256);
   return rounds * bm * bn / rate;
 }
-static int pick_tile(int M, int N) {   // 0: 128x128, 1: 256x128, 2: 256x256
-  const double c0 = tile_cost(M, N, 128, 128, 0.80), c1 = tile_cost(M, N, 256, 128, 0.95),
-               c2 = tile_cost(M, N, 256, 256, 1.25);
+static int pick_tile(int M, int N) {   // 0: 128x128, 1: 256x128, 2: 256x256, 3: 256x192
   if (M <= 128) return 0;
-  if (c2 <= c1 && c2 <= c0) return 2;
-  return c1 <= c0 ? 1 : 0;
+  const double c[4] = {tile_cost(M, N, 128, 128, 0.80), tile_cost(M, N, 256, 128, 0.95),
+                       tile_cost(M, N, 256, 256, 1.25), tile_cost(M, N, 256, 192, 1.15)};
+  int best = 0;
+  for (int i = 1; i < 4; ++i)
+    if (c[i] < c[best]) best = i;
+  return best;
 }
 
 void launch_gemm_qkv_bf16(const bf16* A, const bf16* wq, const bf16* wk, const bf16* wv, int M, int K,
@@ -476,6 +543,7 @@ void launch_gemm_qkv_bf16(const bf16* A, const bf16* wq, const bf16* wk, const b
   a.A = A; a.B0 = wq; a.B1 = wk; a.B2 = wv;
   a.M = M; a.N = 3 * e.d; a.K = K; a.splits = 1; a.gate = g; a.qkv = e;
   switch (pick_tile(M, a.N)) {
+    case 3: launch<256, 192, 32, 4, 1, 4, EPI_QKV>(a, s); break;
     case 2: launch<256, 256, 32, 4, 2, 4, EPI_QKV>(a, s); break;
     case 1: launch<256, 128, 32, 4, 2, 6, EPI_QKV>(a, s); break;
     default: launch<128, 128, 64, 2, 2, 4, EPI_QKV>(a, s);
@@ -497,6 +565,7 @@ void launch_gemm_swiglu_bf16(const bf16* A, const bf16* wg, const bf16* wu, bf16
   a.A = A; a.B0 = wg; a.B1 = wu; a.M = M; a.N = 2 * F; a.K = K; a.splits = 1; a.gate = g;
   a.act = act; a.F = F;
   switch (pick_tile(M, a.N)) {
+    case 3: launch<256, 192, 32, 4, 1, 4, EPI_SWIGLU>(a, s); break;
     case 2: launch<256, 256, 32, 4, 2, 4, EPI_SWIGLU>(a, s); break;
     case 1: launch<256, 128, 32, 4, 2, 6, EPI_SWIGLU>(a, s); break;
     default: launch<128, 128, 64, 2, 2, 4, EPI_SWIGLU>(a, s);
