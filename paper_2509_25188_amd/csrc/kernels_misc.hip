@@ -197,12 +197,77 @@ __global__ void __launch_bounds__(256) k_rmsnorm_vec(float* h, const float* p0, 
   }
 }
 
+// Wide rows (d >= 2048): one row per 256-thread workgroup, the row's sum of squares combined across
+// the four wavefronts through LDS.  With a few hundred rows this puts four times as many
+// wavefronts, each with a quarter of the loads, on the chip as the one-wavefront-per-row kernel.
+// The choice between the two depends on d only, never on the number of rows, so that a row's
+// result does not depend on the batch it is part of.
+template <typename T, int VPL>
+__global__ void __launch_bounds__(256) k_rmsnorm_row(float* h, const float* p0, const float* p1, RowMap src,
+                                                    const T* gain, T* y, int rows, int d, float eps, Gate g) {
+  if (gate_skip(g)) return;
+  __shared__ float s_part[4];
+  const int tid = threadIdx.x;
+  const int r = blockIdx.x;
+  const size_t srow = (size_t)map_row(src, r, g.ctl);
+  const int d4 = d >> 2;
+  float4* x = reinterpret_cast<float4*>(h + srow * d);
+  const float4* a0 = p0 ? reinterpret_cast<const float4*>(p0 + srow * d) : nullptr;
+  const float4* a1 = p1 ? reinterpret_cast<const float4*>(p1 + srow * d) : nullptr;
+  float4 v[VPL], t0[VPL], t1[VPL];
+#pragma unroll
+  for (int k = 0; k < VPL; ++k) {
+    const int i = tid + 256 * k;
+    const bool in = i < d4;
+    v[k] = in ? x[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+    t0[k] = (in && a0) ? a0[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+    t1[k] = (in && a1) ? a1[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  float ss = 0.f;
+#pragma unroll
+  for (int k = 0; k < VPL; ++k) {
+    const int i = tid + 256 * k;
+    if (a0) {
+      v[k].x += t0[k].x; v[k].y += t0[k].y; v[k].z += t0[k].z; v[k].w += t0[k].w;
+      if (a1) { v[k].x += t1[k].x; v[k].y += t1[k].y; v[k].z += t1[k].z; v[k].w += t1[k].w; }
+      if (i < d4) x[i] = v[k];
+    }
+    ss += v[k].x * v[k].x + v[k].y * v[k].y + v[k].z * v[k].z + v[k].w * v[k].w;
+  }
+  ss = wave_sum(ss);
+  if ((tid & 63) == 0) s_part[tid >> 6] = ss;
+  __syncthreads();
+  ss = (s_part[0] + s_part[1]) + (s_part[2] + s_part[3]);
+  const float inv = rsqrtf(ss / (float)d + eps);
+  T* o = y + (size_t)r * d;
+#pragma unroll
+  for (int k = 0; k < VPL; ++k) {
+    const int i = tid + 256 * k;
+    if (i < d4) {
+      const T* gp = gain + 4 * i;
+      if constexpr (sizeof(T) == 4) {
+        float4 gg = *reinterpret_cast<const float4*>(gp);
+        *reinterpret_cast<float4*>(o + 4 * i) =
+            make_float4(v[k].x * inv * gg.x, v[k].y * inv * gg.y, v[k].z * inv * gg.z, v[k].w * inv * gg.w);
+      } else {
+        T o4[4] = {from_f<T>(v[k].x * inv * to_f<T>(gp[0])), from_f<T>(v[k].y * inv * to_f<T>(gp[1])),
+                   from_f<T>(v[k].z * inv * to_f<T>(gp[2])), from_f<T>(v[k].w * inv * to_f<T>(gp[3]))};
+        *reinterpret_cast<uint2*>(o + 4 * i) = *reinterpret_cast<const uint2*>(o4);
+      }
+    }
+  }
+}
+
 template <typename T>
 static void launch_rmsnorm_t(float* h, const float* p0, const float* p1, RowMap src, const T* gain, T* y, int rows,
                              int d, float eps, Gate g, hipStream_t s) {
   dim3 grid((rows + 3) / 4), block(256);
   if (rows <= 4096) { grid = dim3(rows); block = dim3(64); }   // few rows: one wavefront per workgroup fills more CUs
-  if (d % 4 == 0 && d <= 1024)
+  if (d % 4 == 0 && d >= 2048 && d <= 4096)
+    hipLaunchKernelGGL((k_rmsnorm_row<T, 4>), dim3(rows), dim3(256), 0, s, h, p0, p1, src, gain, y, rows, d, eps, g);
+  else if (d % 4 == 0 && d > 4096 && d <= 8192)
+    hipLaunchKernelGGL((k_rmsnorm_row<T, 8>), dim3(rows), dim3(256), 0, s, h, p0, p1, src, gain, y, rows, d, eps, g);
+  else if (d % 4 == 0 && d <= 1024)
     hipLaunchKernelGGL((k_rmsnorm_vec<T, 4>), grid, block, 0, s, h, p0, p1, src, gain, y, rows, d, eps, g);
   else if (d % 4 == 0 && d <= 4096)
     hipLaunchKernelGGL((k_rmsnorm_vec<T, 16>), grid, block, 0, s, h, p0, p1, src, gain, y, rows, d, eps, g);
