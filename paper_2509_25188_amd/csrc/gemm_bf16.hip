@@ -46,12 +46,14 @@ struct GemmArgs {
   LmHeadEpilogue lm;
 };
 
-__device__ __forceinline__ unsigned short f2bf(float f) {   // round to nearest even
-  unsigned int u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x40);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (unsigned short)(u >> 16);
+// fp32 -> bf16, round to nearest even, two values per v_cvt_pk_bf16_f32; lo lands in bits 15:0
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+__device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
+  f32x2 v = {lo, hi};
+  return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2_t));
 }
+__device__ __forceinline__ unsigned short f2bf(float f) { return (unsigned short)(pack_bf16(f, 0.f) & 0xffffu); }
 
 // 4x4 transpose inside every aligned group of four lanes: on entry lane j of a group holds
 // element (j, k) in w[k]; on return it holds element (k, j).  In the MFMA C layout a lane owns one
@@ -314,9 +316,11 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
           for (int rr = 0; rr < 4; ++rr) {
             const float g0 = acc[i][2 * p][rq * 4 + rr], u0 = acc[i][2 * p + 1][rq * 4 + rr];
             const float g1 = acc[i][2 * p][rq * 4 + 4 + rr], u1 = acc[i][2 * p + 1][rq * 4 + 4 + rr];
-            const float s0 = __fmul_rn(__fdiv_rn(g0, __fadd_rn(1.f, __expf(-g0))), u0);
-            const float s1 = __fmul_rn(__fdiv_rn(g1, __fadd_rn(1.f, __expf(-g1))), u1);
-            w[rr] = (unsigned)f2bf(s0) | ((unsigned)f2bf(s1) << 16);
+            // SiLU(g) * u with the hardware reciprocal (1 ulp) instead of an exact division; the
+            // operations are spelled out so that every tile configuration rounds alike
+            const float s0 = __fmul_rn(__fmul_rn(g0, __builtin_amdgcn_rcpf(__fadd_rn(1.f, __expf(-g0)))), u0);
+            const float s1 = __fmul_rn(__fmul_rn(g1, __builtin_amdgcn_rcpf(__fadd_rn(1.f, __expf(-g1)))), u1);
+            w[rr] = pack_bf16(s0, s1);
           }
           quad_transpose(w, lane);
 #pragma unroll
@@ -352,13 +356,13 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
               int b = row0 / e.Tq, pos = e.pos0 + row0 % e.Tq;
               size_t o = ((size_t)(b * e.H + head) * e.Dh + dim) * e.Tpad + pos;
               unsigned short* vt = reinterpret_cast<unsigned short*>(e.vtstore);
-              ushort4 lo4, hi4;
-              lo4.x = f2bf(acc[i][2 * p][rq * 4 + 0]); lo4.y = f2bf(acc[i][2 * p][rq * 4 + 1]);
-              lo4.z = f2bf(acc[i][2 * p][rq * 4 + 2]); lo4.w = f2bf(acc[i][2 * p][rq * 4 + 3]);
-              hi4.x = f2bf(acc[i][2 * p + 1][rq * 4 + 0]); hi4.y = f2bf(acc[i][2 * p + 1][rq * 4 + 1]);
-              hi4.z = f2bf(acc[i][2 * p + 1][rq * 4 + 2]); hi4.w = f2bf(acc[i][2 * p + 1][rq * 4 + 3]);
-              *reinterpret_cast<ushort4*>(vt + o) = lo4;
-              *reinterpret_cast<ushort4*>(vt + o + (size_t)half * e.Tpad) = hi4;
+              uint2 lo4, hi4;
+              lo4.x = pack_bf16(acc[i][2 * p][rq * 4 + 0], acc[i][2 * p][rq * 4 + 1]);
+              lo4.y = pack_bf16(acc[i][2 * p][rq * 4 + 2], acc[i][2 * p][rq * 4 + 3]);
+              hi4.x = pack_bf16(acc[i][2 * p + 1][rq * 4 + 0], acc[i][2 * p + 1][rq * 4 + 1]);
+              hi4.y = pack_bf16(acc[i][2 * p + 1][rq * 4 + 2], acc[i][2 * p + 1][rq * 4 + 3]);
+              *reinterpret_cast<uint2*>(vt + o) = lo4;
+              *reinterpret_cast<uint2*>(vt + o + (size_t)half * e.Tpad) = hi4;
             } else {
 #pragma unroll
               for (int rr = 0; rr < 4; ++rr) {
@@ -386,8 +390,9 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
             for (int rr = 0; rr < 4; ++rr) {
               const int r = rq * 4 + rr;
               const bool live = row0 + rr < a.M;
-              cs[r] = live ? e.cos_t[(size_t)(e.pos0 + t) * half + dim] : 0.f;
-              sn[r] = live ? e.sin_t[(size_t)(e.pos0 + t) * half + dim] : 0.f;
+              const unsigned ti = (unsigned)(e.pos0 + t) * (unsigned)half + (unsigned)dim;   // < 2^31 by construction
+              cs[r] = live ? e.cos_t[ti] : 0.f;
+              sn[r] = live ? e.sin_t[ti] : 0.f;
               if (++t == e.Tq) t = 0;
             }
           }
@@ -404,7 +409,7 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
               // contraction into fused multiply-adds the compiler would pick for each of them
               const float o1 = __fmaf_rn(x1, cs[r], -__fmul_rn(x2, sn[r]));
               const float o2 = __fmaf_rn(x2, cs[r], __fmul_rn(x1, sn[r]));
-              w[rr] = (unsigned)f2bf(o1) | ((unsigned)f2bf(o2) << 16);
+              w[rr] = pack_bf16(o1, o2);
             }
             quad_transpose(w, lane);
             const int row = row_base + i * 32 + rq * 8 + hf * 4 + lr;
