@@ -20,11 +20,11 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
 
-__device__ __forceinline__ unsigned int pack_bf16x2(float lo, float hi) {
-  unsigned int a = __float_as_uint(lo), b = __float_as_uint(hi);
-  a += 0x7fffu + ((a >> 16) & 1u);
-  b += 0x7fffu + ((b >> 16) & 1u);
-  return (a >> 16) | (b & 0xffff0000u);
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+__device__ __forceinline__ unsigned int pack_bf16x2(float lo, float hi) {   // v_cvt_pk_bf16_f32, round to nearest even
+  f32x2 v = {lo, hi};
+  return __builtin_bit_cast(unsigned int, __builtin_convertvector(v, bf16x2_t));
 }
 
 template <int DH, int NW>
@@ -140,7 +140,7 @@ __global__ void __launch_bounds__(NW * 64) k_attn_bf16(const bf16* __restrict__ 
       }
     tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
     const float mn = fmaxf(m, tmax);
-    const float alpha = exp2f(m - mn);       // m = -inf on the first tile gives 0
+    const float alpha = __builtin_amdgcn_exp2f(m - mn);       // m = -inf on the first tile gives 0
     m = mn;
     float ps = 0.f;
     unsigned int pk[2][8];                   // bf16 pairs: [sub][4 per 16-key step * 2 steps]
@@ -148,7 +148,8 @@ __global__ void __launch_bounds__(NW * 64) k_attn_bf16(const bf16* __restrict__ 
     for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
       for (int r = 0; r < 16; r += 2) {
-        float p0 = exp2f(s[sub][r] - mn), p1 = exp2f(s[sub][r + 1] - mn);
+        // v_exp_f32 directly: arguments are <= 0, and a result below the normal range may flush to zero
+        float p0 = __builtin_amdgcn_exp2f(s[sub][r] - mn), p1 = __builtin_amdgcn_exp2f(s[sub][r + 1] - mn);
         ps += p0 + p1;
         pk[sub][r >> 1] = pack_bf16x2(p0, p1);
       }

@@ -344,7 +344,7 @@ void launch_vocab_partials(float* logits, int rows, int V, int chunk, int mask_i
 // Per sequence: combine the vocabulary partials into conf / pre (Eq. 3, Eq. 4), evaluate the filter
 // p = sigmoid(W2 relu(W1 c + b1) + b2) on the block's confidences (committed positions enter as 1.0),
 // unmask where p > tau plus the most confident masked position, advance the block, apply EoTP.
-__global__ void __launch_bounds__(256) k_update(UpdateArgs a, Gate g) {
+__global__ void __launch_bounds__(1024) k_update(UpdateArgs a, Gate g) {
   if (gate_skip(g)) return;
   __shared__ float s_conf[256];
   __shared__ int s_pred[256];
@@ -360,19 +360,35 @@ __global__ void __launch_bounds__(256) k_update(UpdateArgs a, Gate g) {
   int32_t* X = a.X + (size_t)b * a.T;
   int32_t* st = a.state + b * 3;
 
-  for (int j = wave; j < s; j += 4) {
+  const int n_waves = blockDim.x >> 6;
+  for (int j = wave; j < s; j += n_waves) {
     size_t base = (size_t)(b * s + j) * a.n_part;
     float m = -INFINITY, sum = 0.f;
     int idx = 0x7fffffff;
-    for (int p = lane; p < a.n_part; p += 64) {
-      float pm = a.part_max[base + p], ps = a.part_sum[base + p];
-      int pi = a.part_idx[base + p];
-      if (pm > m) {
-        sum = sum * (m == -INFINITY ? 0.f : expf(m - pm)) + ps;
-        m = pm; idx = pi;
-      } else if (pm > -INFINITY) {
-        sum += ps * expf(pm - m);
-        if (pm == m && pi < idx) idx = pi;
+    // partials are fetched eight per lane at a time, all loads in flight together, and folded in
+    // ascending order of p
+    for (int p0 = lane; p0 < a.n_part; p0 += 64 * 8) {
+      float pm8[8], ps8[8];
+      int pi8[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int p = p0 + 64 * u;
+        const bool in = p < a.n_part;
+        pm8[u] = in ? a.part_max[base + p] : -INFINITY;
+        ps8[u] = in ? a.part_sum[base + p] : 0.f;
+        pi8[u] = in ? a.part_idx[base + p] : 0x7fffffff;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const float pm = pm8[u], ps = ps8[u];
+        const int pi = pi8[u];
+        if (pm > m) {
+          sum = sum * (m == -INFINITY ? 0.f : expf(m - pm)) + ps;
+          m = pm; idx = pi;
+        } else if (pm > -INFINITY) {
+          sum += ps * expf(pm - m);
+          if (pm == m && pi < idx) idx = pi;
+        }
       }
     }
 #pragma unroll
@@ -398,7 +414,7 @@ __global__ void __launch_bounds__(256) k_update(UpdateArgs a, Gate g) {
     if (mk) atomicAdd(&s_flag[0], 1);   // integer count of masked positions
   }
   __syncthreads();
-  for (int t = tid; t < a.hidden; t += 256) {
+  for (int t = tid; t < a.hidden; t += blockDim.x) {
     float acc = a.b1[t];
     const float* w = a.w1 + (size_t)t * s;
     for (int j = 0; j < s; ++j) acc += w[j] * s_cin[j];
@@ -436,7 +452,7 @@ __global__ void __launch_bounds__(256) k_update(UpdateArgs a, Gate g) {
   if (!mine) return;
   const bool complete = s_flag[1] == n_masked;   // also true when nothing was masked
   if (complete && a.eotp) {
-    for (int t = a.P + tid; t < lo + s; t += 256)
+    for (int t = a.P + tid; t < lo + s; t += blockDim.x)
       if (X[t] == a.eos_id) s_flag[2] = 1;
   }
   __syncthreads();
@@ -449,7 +465,7 @@ __global__ void __launch_bounds__(256) k_update(UpdateArgs a, Gate g) {
   }
 }
 void launch_update(const UpdateArgs& a, Gate g, hipStream_t s) {
-  hipLaunchKernelGGL(k_update, dim3(a.B), dim3(256), 0, s, a, g);
+  hipLaunchKernelGGL(k_update, dim3(a.B), dim3(1024), 0, s, a, g);   // 16 wavefronts share the block's rows
 }
 
 // response_i = X[P : P+G], steps, decoded length
