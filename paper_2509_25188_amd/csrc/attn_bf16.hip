@@ -1,9 +1,11 @@
 // Bidirectional (non-causal) flash-style attention on bf16 MFMA for gfx950.
 //
 // Inputs are what the QKV GEMM epilogue leaves: rotated queries q [B*Tq, d], rotated keys
-// kstore [B, Tpad, d] and transposed values vtstore [B, H, Dh, Tpad].  A workgroup owns 32*NW
-// queries of one (sequence, head); each wavefront owns 32 of them.  Key/value tiles of 64 keys are
-// staged in LDS (XOR-swizzled rows, double buffered) and shared by the workgroup's wavefronts.
+// kstore [B, Tpad, d] and transposed values vtstore [B, H, Dh, Tpad].  A workgroup owns 32*NQ
+// queries of one (sequence, head) and splits the keys into NSPL contiguous ranges; wavefront
+// (query group, key range) runs the online softmax of its 32 queries over its range, and the
+// ranges are merged at the end.  Key/value tiles of 64 keys are staged in LDS (XOR-swizzled rows,
+// double buffered), one tile per range and iteration, shared by the query groups.
 //
 // The wave computes S^T = K Q^T (keys are MFMA rows, queries are columns), so that a lane holds
 // scores of ONE query: the row maximum is 31 register maxima plus one cross-lane exchange, and the
@@ -27,11 +29,12 @@ __device__ __forceinline__ unsigned int pack_bf16x2(float lo, float hi) {   // v
   return __builtin_bit_cast(unsigned int, __builtin_convertvector(v, bf16x2_t));
 }
 
-template <int DH, int NW>
-__global__ void __launch_bounds__(NW * 64) k_attn_bf16(const bf16* __restrict__ q, const bf16* __restrict__ kstore,
-                                                       const bf16* __restrict__ vtstore, bf16* __restrict__ out,
-                                                       int B, int Tq, int Tk, int Tpad, int H, Gate g) {
+template <int DH, int NQ, int NSPL>
+__global__ void __launch_bounds__(NQ * NSPL * 64) k_attn_bf16(const bf16* __restrict__ q, const bf16* __restrict__ kstore,
+                                                              const bf16* __restrict__ vtstore, bf16* __restrict__ out,
+                                                              int B, int Tq, int Tk, int Tpad, int H, Gate g) {
   if (gate_skip(g)) return;
+  constexpr int NW = NQ * NSPL;
   constexpr int NT = NW * 64;
   constexpr int KT = 64;                       // keys per LDS tile
   constexpr int K_ROW = DH * 2;                // bytes per key row
@@ -42,12 +45,15 @@ __global__ void __launch_bounds__(NW * 64) k_attn_bf16(const bf16* __restrict__ 
   static_assert(KCH * NT * 16 == K_BYTES && VCH * NT * 16 == V_BYTES, "tile/threads mismatch");
   constexpr int KK = DH / 16;                  // MFMA steps over the feature dim
   constexpr int FO = DH / 32;                  // output row fragments
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int XW = FO * 16 + 2;              // floats a wave hands over per lane: O^T fragments, m, l
+  static_assert((NSPL - 1) * NQ * XW * 64 * 4 <= 2 * NSPL * STAGE, "exchange area must fit in the tile buffers");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // [2 stages][NSPL key ranges][K tile | V^T tile]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5, lj = lane & 31;
+  const int qg = wave % NQ, sp = wave / NQ;    // query group and key range of this wavefront
   const int b = blockIdx.z, h = blockIdx.y;
   const int d = H * DH;
-  const int q0 = blockIdx.x * (32 * NW) + wave * 32;
+  const int q0 = blockIdx.x * (32 * NQ) + qg * 32;
   const int qrow = min(q0 + lj, Tq - 1);
 
   // Q as the B operand: lane (query lj, half hf) holds features kk*16 + hf*8 .. +7
@@ -81,19 +87,31 @@ __global__ void __launch_bounds__(NW * 64) k_attn_bf16(const bf16* __restrict__ 
     srcV[i] = vbase + (size_t)r * Tpad + cc * 8;
     dstV[i] = K_BYTES + r * (KT * 2) + ((cc ^ ((r >> 1) & 7)) << 4);
   }
-  u32x4 rk[KCH], rv[VCH];
-  auto gload = [&](int k0) {
+  // The key tiles are dealt to the NSPL key ranges in contiguous runs of `per` tiles; every range
+  // is walked by NQ wavefronts (one per query group), and all ranges advance together, one tile
+  // per iteration, so the dependent chain of a wavefront is `per` tiles long instead of n_tiles.
+  const int n_tiles = (Tk + KT - 1) / KT;
+  const int per = (n_tiles + NSPL - 1) / NSPL;
+  u32x4 rk[NSPL][KCH], rv[NSPL][VCH];
+  auto gload = [&](int it) {
 #pragma unroll
-    for (int i = 0; i < KCH; ++i) rk[i] = *reinterpret_cast<const u32x4*>(srcK[i] + (size_t)k0 * d);
+    for (int x = 0; x < NSPL; ++x) {
+      const int k0 = min(x * per + it, n_tiles - 1) * KT;   // ranges that have run out re-read a valid tile
 #pragma unroll
-    for (int i = 0; i < VCH; ++i) rv[i] = *reinterpret_cast<const u32x4*>(srcV[i] + k0);
+      for (int i = 0; i < KCH; ++i) rk[x][i] = *reinterpret_cast<const u32x4*>(srcK[i] + (size_t)k0 * d);
+#pragma unroll
+      for (int i = 0; i < VCH; ++i) rv[x][i] = *reinterpret_cast<const u32x4*>(srcV[i] + k0);
+    }
   };
   auto sstore = [&](int stage) {
-    unsigned char* base = smem + stage * STAGE;
 #pragma unroll
-    for (int i = 0; i < KCH; ++i) *reinterpret_cast<u32x4*>(base + dstK[i]) = rk[i];
+    for (int x = 0; x < NSPL; ++x) {
+      unsigned char* base = smem + (stage * NSPL + x) * STAGE;
 #pragma unroll
-    for (int i = 0; i < VCH; ++i) *reinterpret_cast<u32x4*>(base + dstV[i]) = rv[i];
+      for (int i = 0; i < KCH; ++i) *reinterpret_cast<u32x4*>(base + dstK[i]) = rk[x][i];
+#pragma unroll
+      for (int i = 0; i < VCH; ++i) *reinterpret_cast<u32x4*>(base + dstV[i]) = rv[x][i];
+    }
   };
 
   f32x16 o[FO];
@@ -104,79 +122,111 @@ __global__ void __launch_bounds__(NW * 64) k_attn_bf16(const bf16* __restrict__ 
   float m = -INFINITY, lsum = 0.f;
   const float sc = rsqrtf((float)DH) * 1.4426950408889634f;   // softmax scale folded with log2(e)
   const int keyK = kkey(lj), keyV = (lj >> 1) & 7;   // fragment rows are lj modulo 32
+  const int my_first = sp * per, my_count = max(0, min(per, n_tiles - my_first));
 
-  const int n_tiles = (Tk + KT - 1) / KT;
   gload(0);
   sstore(0);
   __syncthreads();
-  for (int t = 0; t < n_tiles; ++t) {
-    const bool more = t + 1 < n_tiles;
-    if (more) gload((t + 1) * KT);
-    const unsigned char* base = smem + (t & 1) * STAGE;
-    const int k0 = t * KT;
+  for (int t = 0; t < per; ++t) {
+    const bool more = t + 1 < per;
+    if (more) gload(t + 1);
+    if (t < my_count) {
+      const unsigned char* base = smem + ((t & 1) * NSPL + sp) * STAGE;
+      const int k0 = (my_first + t) * KT;
 
-    // S^T for the two 32-key halves of the tile
-    f32x16 s[2];
+      // S^T for the two 32-key halves of the tile
+      f32x16 s[2];
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub) {
+      for (int sub = 0; sub < 2; ++sub) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[sub][r] = 0.f;
-      const unsigned char* krow = base + (sub * 32 + lj) * K_ROW;
+        for (int r = 0; r < 16; ++r) s[sub][r] = 0.f;
+        const unsigned char* krow = base + (sub * 32 + lj) * K_ROW;
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        bf16x8_t fk = *reinterpret_cast<const bf16x8_t*>(krow + (((kk * 2 + hf) ^ keyK) << 4));
-        s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk, fq[kk], s[sub], 0, 0, 0);
+        for (int kk = 0; kk < KK; ++kk) {
+          bf16x8_t fk = *reinterpret_cast<const bf16x8_t*>(krow + (((kk * 2 + hf) ^ keyK) << 4));
+          s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk, fq[kk], s[sub], 0, 0, 0);
+        }
       }
-    }
-    float tmax = -INFINITY;
+      float tmax = -INFINITY;
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub)
+      for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        int kidx = k0 + sub * 32 + (r >> 2) * 8 + hf * 4 + (r & 3);
-        float v = kidx < Tk ? s[sub][r] * sc : -INFINITY;
-        s[sub][r] = v;
-        tmax = fmaxf(tmax, v);
-      }
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-    const float mn = fmaxf(m, tmax);
-    const float alpha = __builtin_amdgcn_exp2f(m - mn);       // m = -inf on the first tile gives 0
-    m = mn;
-    float ps = 0.f;
-    unsigned int pk[2][8];                   // bf16 pairs: [sub][4 per 16-key step * 2 steps]
+        for (int r = 0; r < 16; ++r) {
+          int kidx = k0 + sub * 32 + (r >> 2) * 8 + hf * 4 + (r & 3);
+          float v = kidx < Tk ? s[sub][r] * sc : -INFINITY;
+          s[sub][r] = v;
+          tmax = fmaxf(tmax, v);
+        }
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+      const float mn = fmaxf(m, tmax);
+      const float alpha = __builtin_amdgcn_exp2f(m - mn);       // m = -inf on the first tile gives 0
+      m = mn;
+      float ps = 0.f;
+      unsigned int pk[2][8];                   // bf16 pairs: [sub][4 per 16-key step * 2 steps]
 #pragma unroll
-    for (int sub = 0; sub < 2; ++sub)
+      for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-      for (int r = 0; r < 16; r += 2) {
-        // v_exp_f32 directly: arguments are <= 0, and a result below the normal range may flush to zero
-        float p0 = __builtin_amdgcn_exp2f(s[sub][r] - mn), p1 = __builtin_amdgcn_exp2f(s[sub][r + 1] - mn);
-        ps += p0 + p1;
-        pk[sub][r >> 1] = pack_bf16x2(p0, p1);
-      }
-    lsum = lsum * alpha + ps;
+        for (int r = 0; r < 16; r += 2) {
+          // v_exp_f32 directly: arguments are <= 0, and a result below the normal range may flush to zero
+          float p0 = __builtin_amdgcn_exp2f(s[sub][r] - mn), p1 = __builtin_amdgcn_exp2f(s[sub][r + 1] - mn);
+          ps += p0 + p1;
+          pk[sub][r >> 1] = pack_bf16x2(p0, p1);
+        }
+      lsum = lsum * alpha + ps;
 #pragma unroll
-    for (int f = 0; f < FO; ++f)
+      for (int f = 0; f < FO; ++f)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) o[f][r] *= alpha;
+        for (int r = 0; r < 16; ++r) o[f][r] *= alpha;
 
-    // O^T += V^T P^T, 16 keys per MFMA
+      // O^T += V^T P^T, 16 keys per MFMA
 #pragma unroll
-    for (int m16 = 0; m16 < 4; ++m16) {
-      const int sub = m16 >> 1, mm = m16 & 1;
-      u32x4 pw = {pk[sub][mm * 4 + 0], pk[sub][mm * 4 + 1], pk[sub][mm * 4 + 2], pk[sub][mm * 4 + 3]};
-      bf16x8_t fp = __builtin_bit_cast(bf16x8_t, pw);
+      for (int m16 = 0; m16 < 4; ++m16) {
+        const int sub = m16 >> 1, mm = m16 & 1;
+        u32x4 pw = {pk[sub][mm * 4 + 0], pk[sub][mm * 4 + 1], pk[sub][mm * 4 + 2], pk[sub][mm * 4 + 3]};
+        bf16x8_t fp = __builtin_bit_cast(bf16x8_t, pw);
 #pragma unroll
-      for (int f = 0; f < FO; ++f) {
-        const unsigned char* vrow = base + K_BYTES + (f * 32 + lj) * (KT * 2) + hf * 8;
-        u32x2 v0 = *reinterpret_cast<const u32x2*>(vrow + (((m16 * 2) ^ keyV) << 4));
-        u32x2 v1 = *reinterpret_cast<const u32x2*>(vrow + (((m16 * 2 + 1) ^ keyV) << 4));
-        u32x4 vw = {v0.x, v0.y, v1.x, v1.y};
-        bf16x8_t fv = __builtin_bit_cast(bf16x8_t, vw);
-        o[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv, fp, o[f], 0, 0, 0);
+        for (int f = 0; f < FO; ++f) {
+          const unsigned char* vrow = base + K_BYTES + (f * 32 + lj) * (KT * 2) + hf * 8;
+          u32x2 v0 = *reinterpret_cast<const u32x2*>(vrow + (((m16 * 2) ^ keyV) << 4));
+          u32x2 v1 = *reinterpret_cast<const u32x2*>(vrow + (((m16 * 2 + 1) ^ keyV) << 4));
+          u32x4 vw = {v0.x, v0.y, v1.x, v1.y};
+          bf16x8_t fv = __builtin_bit_cast(bf16x8_t, vw);
+          o[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv, fp, o[f], 0, 0, 0);
+        }
       }
     }
     if (more) sstore((t + 1) & 1);
     __syncthreads();
+  }
+
+  // Merge the key ranges: range 0 of each query group folds in the others' (m, l, O^T), in range
+  // order, through the tile buffers (dead now).  A range without keys hands over m = -inf, l = 0.
+  if constexpr (NSPL > 1) {
+    float* xch = reinterpret_cast<float*>(smem);
+    if (sp > 0) {
+      float* mine = xch + (size_t)((sp - 1) * NQ + qg) * XW * 64 + lane;
+#pragma unroll
+      for (int f = 0; f < FO; ++f)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mine[(f * 16 + r) * 64] = o[f][r];
+      mine[(FO * 16) * 64] = m;
+      mine[(FO * 16 + 1) * 64] = lsum;
+    }
+    __syncthreads();
+    if (sp > 0) return;
+#pragma unroll
+    for (int x = 1; x < NSPL; ++x) {
+      const float* oth = xch + (size_t)((x - 1) * NQ + qg) * XW * 64 + lane;
+      const float m2 = oth[(FO * 16) * 64], l2 = oth[(FO * 16 + 1) * 64];
+      const float M = fmaxf(m, m2);   // m is finite: range 0 always holds the first tile
+      const float a1 = __builtin_amdgcn_exp2f(m - M), a2 = __builtin_amdgcn_exp2f(m2 - M);
+#pragma unroll
+      for (int f = 0; f < FO; ++f)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[f][r] = o[f][r] * a1 + oth[(f * 16 + r) * 64] * a2;
+      lsum = lsum * a1 + l2 * a2;
+      m = M;
+    }
   }
 
   const float l = lsum + __shfl_xor(lsum, 32, 64);
@@ -195,30 +245,27 @@ __global__ void __launch_bounds__(NW * 64) k_attn_bf16(const bf16* __restrict__ 
   }
 }
 
-template <int DH, int NW>
+template <int DH, int NQ, int NSPL>
 static void launch(const bf16* q, const bf16* kstore, const bf16* vtstore, bf16* out, int B, int Tq, int Tk,
                    int Tpad, int H, Gate g, hipStream_t s) {
-  auto kern = k_attn_bf16<DH, NW>;
-  constexpr int smem = 2 * (64 * DH * 2 + DH * 64 * 2);
+  auto kern = k_attn_bf16<DH, NQ, NSPL>;
+  constexpr int smem = 2 * NSPL * (64 * DH * 2 + DH * 64 * 2);
   static bool attr_done = false;
   if (!attr_done) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     attr_done = true;
   }
-  dim3 grid((Tq + 32 * NW - 1) / (32 * NW), H, B);
-  hipLaunchKernelGGL(kern, grid, dim3(NW * 64), smem, s, q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, g);
+  dim3 grid((Tq + 32 * NQ - 1) / (32 * NQ), H, B);
+  hipLaunchKernelGGL(kern, grid, dim3(NQ * NSPL * 64), smem, s, q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, g);
 }
 
+// 64 queries per workgroup, keys in two ranges: with one sequence of a few hundred tokens this
+// gives a workgroup to every CU and halves the chain of dependent key tiles per wavefront.  The
+// configuration depends on the head size only, so a sequence's result does not depend on its batch.
 void launch_attn_bf16(const bf16* q, const bf16* kstore, const bf16* vtstore, bf16* out, int B, int Tq, int Tk,
                       int Tpad, int H, int Dh, Gate g, hipStream_t s) {
-  const bool small = Tq <= 64;   // short query blocks (prefix-cache steps): 64 queries per workgroup
-  if (Dh == 128) {
-    if (small) launch<128, 2>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, g, s);
-    else launch<128, 4>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, g, s);
-  } else {
-    if (small) launch<64, 2>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, g, s);
-    else launch<64, 4>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, g, s);
-  }
+  if (Dh == 128) launch<128, 2, 2>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, g, s);
+  else launch<64, 2, 2>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, g, s);
 }
 
 }  // namespace l2pd
