@@ -86,6 +86,30 @@ def cpu_baseline(w, tokens_per_step, seed, n_layers_sample=2):
     }
 
 
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "gate_up_gemm_hbm_traffic.txt")
+GEMM_SOURCE = os.path.join(ROOT, "paper_2509_25188_amd", "csrc", "gemm_bf16.hip")
+
+
+def measured_traffic():
+    """HBM bytes per launch of the gate/up GEMM from the committed counter summary, or None when
+    there is none or the kernel source has changed since the counters were taken."""
+    import hashlib
+    try:
+        fields = {}
+        with open(TRAFFIC_FILE) as fh:
+            for line in fh:
+                if ":" in line and not line.startswith("#"):
+                    k, v = line.split(":", 1)
+                    fields[k.strip()] = v.strip()
+        with open(GEMM_SOURCE, "rb") as fh:
+            sha = hashlib.sha256(fh.read()).hexdigest()
+        if fields.get("kernel_source_sha256") != sha:
+            return None
+        return float(fields["hbm_bytes_per_launch"])
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -95,6 +119,8 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="reduced depth (debugging only; invalid as a result)")
     ap.add_argument("--seed", type=int, default=1234)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch a plain device copy of known size (reference for HBM counter runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -198,12 +224,20 @@ def main():
                                        if k_ != "tok_emb") / 1e9) / (ms_per_step * 1e-3),
         "roofline": {"bound": "mfma", "kernel": "k_gemm_bf16<SwiGLU gate/up>", "achieved": achieved,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": (achieved / PEAK_BF16_TFLOPS) if achieved else None, "traffic": None,
+                     "frac": (achieved / PEAK_BF16_TFLOPS) if achieved else None, "traffic": measured_traffic(),
                      "launches": n_launch, "avg_launch_ms": avg_kern_ms, "flop_per_launch": gu_flops},
         "setup_s": setup_s,
     }
+    if args.copy_calibration:
+        n = 1 << 28
+        src = torch.empty(n, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        result["copy_calibration"] = {"bytes_read_per_launch": n, "bytes_written_per_launch": n, "launches": 4}
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, tokens_per_step, args.seed)
+        result["cpu_baseline"] = cpu_baseline(w, tokens_per_step, args.seed, n_layers_sample=16)
     print(json.dumps(result))
 
 

@@ -524,7 +524,8 @@ static void launch(GemmArgs& a, hipStream_t s) {
 // keep its MFMAs fed (64 flop per loaded byte); 256-wide tiles halve that traffic and win whenever
 // there are enough of them to occupy the 256 CUs.  cost = rounds over the CUs x work per tile /
 // measured relative per-CU rate of the configuration.  256x192 exists because 512 rows x 24576
-// gate/up columns make exactly 256 such tiles, one round with every CU busy.  (With random operands
+// gate/up columns make exactly 256 such tiles, one round with every CU busy, and 128x192 does the
+// same for the 12288 Q/K/V columns.  (With random operands
 // the chip is power limited: the shader clock sits near 1.5-1.6 GHz inside these kernels, and a
 // register-resident MFMA stream alone tops out at 1.78 PFLOP/s.)
 static double tile_cost(int M, int N, int bm, int bn, double rate) {
@@ -532,12 +533,13 @@ static double tile_cost(int M, int N, int bm, int bn, double rate) {
   const double rounds = (double)(((long long)tiles + 255) / 256);
   return rounds * bm * bn / rate;
 }
-static int pick_tile(int M, int N) {   // 0: 128x128, 1: 256x128, 2: 256x256, 3: 256x192
+static int pick_tile(int M, int N) {   // 0: 128x128, 1: 256x128, 2: 256x256, 3: 256x192, 4: 128x192
   if (M <= 128) return 0;
-  const double c[4] = {tile_cost(M, N, 128, 128, 0.80), tile_cost(M, N, 256, 128, 0.95),
-                       tile_cost(M, N, 256, 256, 1.25), tile_cost(M, N, 256, 192, 1.15)};
+  const double c[5] = {tile_cost(M, N, 128, 128, 0.80), tile_cost(M, N, 256, 128, 0.95),
+                       tile_cost(M, N, 256, 256, 1.25), tile_cost(M, N, 256, 192, 1.15),
+                       tile_cost(M, N, 128, 192, 0.90)};
   int best = 0;
-  for (int i = 1; i < 4; ++i)
+  for (int i = 1; i < 5; ++i)
     if (c[i] < c[best]) best = i;
   return best;
 }
@@ -548,6 +550,7 @@ void launch_gemm_qkv_bf16(const bf16* A, const bf16* wq, const bf16* wk, const b
   a.A = A; a.B0 = wq; a.B1 = wk; a.B2 = wv;
   a.M = M; a.N = 3 * e.d; a.K = K; a.splits = 1; a.gate = g; a.qkv = e;
   switch (pick_tile(M, a.N)) {
+    case 4: launch<128, 192, 32, 4, 1, 4, EPI_QKV>(a, s); break;
     case 3: launch<256, 192, 32, 4, 1, 4, EPI_QKV>(a, s); break;
     case 2: launch<256, 256, 32, 4, 2, 4, EPI_QKV>(a, s); break;
     case 1: launch<256, 128, 32, 4, 2, 6, EPI_QKV>(a, s); break;
@@ -570,6 +573,7 @@ void launch_gemm_swiglu_bf16(const bf16* A, const bf16* wg, const bf16* wu, bf16
   a.A = A; a.B0 = wg; a.B1 = wu; a.M = M; a.N = 2 * F; a.K = K; a.splits = 1; a.gate = g;
   a.act = act; a.F = F;
   switch (pick_tile(M, a.N)) {
+    case 4: launch<128, 192, 32, 4, 1, 4, EPI_SWIGLU>(a, s); break;
     case 3: launch<256, 192, 32, 4, 1, 4, EPI_SWIGLU>(a, s); break;
     case 2: launch<256, 256, 32, 4, 2, 4, EPI_SWIGLU>(a, s); break;
     case 1: launch<256, 128, 32, 4, 2, 6, EPI_SWIGLU>(a, s); break;
