@@ -22,7 +22,14 @@ What it states, in the paper's order and notation:
   token is in the response (Alg. 3, Appendix A; Fig. 4 caption);
 * the prefix KV cache variant (Sec. 4.3 names the technique only): K/V of the
   prompt and finished blocks come from a forward over that prefix alone and
-  are refreshed once per block; a step recomputes only the active block.
+  are refreshed once per block; a step recomputes only the active block;
+* the dual KV cache variant (Sec. 4.3 and Table 2 name it and cite the work it
+  comes from; the mechanism restated here is that work's): at each block start a
+  full bidirectional forward over the whole current sequence stores every
+  position's K/V per layer; a step recomputes only the active block, whose fresh
+  K/V stand in for the stored ones at its positions, and attends to the stored
+  K/V of everything before AND after the block, which stay as they were at the
+  block start.
 
 Readings of points the paper leaves open (each also listed in the design notes):
 mask id excluded from the vocabulary distribution; ties -> lowest index;
@@ -200,6 +207,38 @@ class Model:
         return self.head(h)
 
 
+    # ---- dual KV cache (Sec. 4.3, Table 2) ----
+    def full_kv(self, tokens):
+        """Per-layer (K, V) of every position, from a full bidirectional forward over `tokens`."""
+        t = len(tokens)
+        pos = np.arange(t)
+        h = self.embed(tokens)
+        cache = []
+        for l in range(self.s.n_layers):
+            q, k, v = self.qkv(l, h, pos)
+            cache.append((k, v))
+            if l + 1 < self.s.n_layers:
+                h = self.finish_layer(l, h, attention(q, k, v, self.p_rin))
+        return cache
+
+    def forward_block_dual(self, cache, block_tokens, c):
+        """logits[s, V] for the active block at positions c..c+s-1: its queries attend to every
+        position of the sequence; keys/values of the block's own positions are recomputed from
+        `block_tokens`, all others are the stored ones."""
+        n = len(block_tokens)
+        pos = np.arange(c, c + n)
+        h = self.embed(block_tokens)
+        for l in range(self.s.n_layers):
+            q, k, v = self.qkv(l, h, pos)
+            kc, vc = cache[l]
+            kk = np.array(kc, copy=True)
+            vv = np.array(vc, copy=True)
+            kk[c:c + n] = k
+            vv[c:c + n] = v
+            h = self.finish_layer(l, h, attention(q, kk, vv, self.p_rin))
+        return self.head(h)
+
+
 # --------------------------------------------------------------------------- Eq. 3, Eq. 4
 def conf_pre(logits, mask_id):
     """pre_j = argmax_v p(v) (Eq. 3) and conf_j = p(pre_j) (Eq. 4) over the data vocabulary.
@@ -259,11 +298,14 @@ def decide(block_tokens, logits, mask_id, flt, tau):
     return dict(conf=conf, pre=pre, p=p, sel=sel, masked=masked)
 
 
-def denoise_step(model, X, prompt_len, b, block_len, mask_id, flt, tau, bias=None, cache=None):
-    """One pass of the while-loop body of Alg. 2 for block b of sequence X (modified in place)."""
+def denoise_step(model, X, prompt_len, b, block_len, mask_id, flt, tau, bias=None, cache=None, dual=False):
+    """One pass of the while-loop body of Alg. 2 for block b of sequence X (modified in place).
+    `cache` is None (full recompute), a prefix cache, or with `dual` a dual cache."""
     lo = prompt_len + b * block_len
     if cache is None:
         logits = model.forward(X, lo, block_len)
+    elif dual:
+        logits = model.forward_block_dual(cache, X[lo:lo + block_len], lo)
     else:
         logits = model.forward_block_cached(cache, X[lo:lo + block_len], lo)
     logits = apply_bias(logits, b * block_len, bias)
@@ -276,7 +318,7 @@ def denoise_step(model, X, prompt_len, b, block_len, mask_id, flt, tau, bias=Non
 
 # --------------------------------------------------------------------------- Alg. 2 / Alg. 3
 def generate(model, prompt, gen_len, block_len, mask_id, eos_id, flt, tau, eotp=False,
-             bias=None, prefix_cache=False, trace=None):
+             bias=None, prefix_cache=False, trace=None, dual_cache=False):
     """Decode one prompt.  Returns (response[gen_len], steps, decoded_len).
 
     `trace`, if a list, receives one record per step: the state before the step and the
@@ -290,10 +332,11 @@ def generate(model, prompt, gen_len, block_len, mask_id, eos_id, flt, tau, eotp=
     decoded_len = gen_len
     for b in range(gen_len // block_len):
         lo = P + b * block_len
-        cache = model.prefix_kv(X[:lo]) if prefix_cache else None
+        assert not (prefix_cache and dual_cache)
+        cache = model.prefix_kv(X[:lo]) if prefix_cache else (model.full_kv(X) if dual_cache else None)
         while np.any(X[lo:lo + block_len] == mask_id):
             before = X.copy() if trace is not None else None
-            d = denoise_step(model, X, P, b, block_len, mask_id, flt, tau, bias, cache)
+            d = denoise_step(model, X, P, b, block_len, mask_id, flt, tau, bias, cache, dual_cache)
             steps += 1
             if trace is not None:
                 d.update(X_before=before, block=b)

@@ -268,3 +268,44 @@ def test_generate_with_prefix_cache_one_layer_equals_truncated_full_recompute():
         lo = 3 + t["block"] * 4
         ref = m.forward(t["X_before"][:lo + 4], lo, 4)  # later blocks invisible
         np.testing.assert_allclose(t["logits"], ref, rtol=1e-9, atol=1e-11)
+
+
+# ----------------------------------------------------------------- dual-cache decode on a real (tiny) model
+def test_generate_with_dual_cache_one_layer_equals_full_recompute():
+    # One layer: stored K/V never go stale, so the dual-cache trajectory is the full-recompute one.
+    from tests.test_oracle_model import tiny_shape, tiny_weights
+    s = tiny_shape(L=1, V=13)
+    w = tiny_weights(s, 21, scale=1.0)
+    m = O.Model(s, w, np.float64)
+    r = np.random.default_rng(22)
+    flt = dict(w1=r.normal(size=(4, 4)), b1=r.normal(size=4), w2=r.normal(size=(4, 4)), b2=r.normal(size=4))
+    prompt = np.array([1, 5, 2])
+    full = O.generate(m, prompt, 12, 4, s.mask_id, s.eos_id, flt, 0.6)
+    dual = O.generate(m, prompt, 12, 4, s.mask_id, s.eos_id, flt, 0.6, dual_cache=True)
+    np.testing.assert_array_equal(full[0], dual[0])
+    assert full[1:] == dual[1:]
+
+
+def test_generate_with_dual_cache_first_step_of_each_block_is_the_full_forward():
+    # Several layers: the first step after every refresh sees nothing stale and must reproduce the
+    # full bidirectional forward on that state; later steps of a block may not.
+    from tests.test_oracle_model import tiny_shape, tiny_weights
+    s = tiny_shape(L=3, V=13)
+    w = tiny_weights(s, 23, scale=1.0)
+    m = O.Model(s, w, np.float64)
+    r = np.random.default_rng(24)
+    flt = dict(w1=r.normal(size=(4, 4)), b1=r.normal(size=4), w2=r.normal(size=(4, 4)), b2=r.normal(size=4))
+    prompt = np.array([3, 0, 7, 4])
+    trace = []
+    resp, steps, dl = O.generate(m, prompt, 12, 4, s.mask_id, s.eos_id, flt, 2.0, dual_cache=True, trace=trace)
+    assert not np.any(resp == s.mask_id) and steps == 12 and dl == 12     # tau > 1: one token per step
+    seen, stale = set(), 0
+    for t in trace:
+        lo = 4 + t["block"] * 4
+        ref = m.forward(t["X_before"], lo, 4)
+        if t["block"] not in seen:
+            seen.add(t["block"])
+            np.testing.assert_allclose(t["logits"], ref, rtol=1e-9, atol=1e-11)
+        elif np.max(np.abs(t["logits"] - ref)) > 1e-6:
+            stale += 1
+    assert seen == {0, 1, 2} and stale > 0

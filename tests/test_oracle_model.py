@@ -269,6 +269,110 @@ def bf_forward_cached(s, w, prefix, block):
     return [bf_matvec(W["lm_head"], bf_norm(hr, W["final_norm_g"], s.rms_eps)) for hr in hb]
 
 
+# ----------------------------------------------------------------- dual cache (Sec. 4.3, Table 2)
+def bf_forward_dual(s, w, x_old, x_new_block, c):
+    """Scalar loops: per-layer K/V of every position from a full forward over x_old; then the block
+    rows are run again on x_new_block, their own K/V replacing the stored ones at c..c+n-1."""
+    W = {k: np.asarray(v).tolist() for k, v in w.items()}
+    H, Dh = s.n_heads, s.head_dim
+    T, n = len(x_old), len(x_new_block)
+
+    def qkv_row(l, hr, t):
+        p = f"layers.{l}."
+        a = bf_norm(hr, W[p + "attn_norm_g"], s.rms_eps)
+        q, k, v = bf_matvec(W[p + "wq"], a), bf_matvec(W[p + "wk"], a), bf_matvec(W[p + "wv"], a)
+        for hh in range(H):
+            q[hh * Dh:(hh + 1) * Dh] = bf_rope_head(q[hh * Dh:(hh + 1) * Dh], t, s.rope_base)
+            k[hh * Dh:(hh + 1) * Dh] = bf_rope_head(k[hh * Dh:(hh + 1) * Dh], t, s.rope_base)
+        return q, k, v
+
+    def attend(q, keys, vals):
+        o = [0.0] * (H * Dh)
+        for hh in range(H):
+            sc = [sum(q[hh * Dh + e] * kk[hh * Dh + e] for e in range(Dh)) / math.sqrt(Dh) for kk in keys]
+            m = max(sc)
+            ex = [math.exp(x - m) for x in sc]
+            z = sum(ex)
+            for e in range(Dh):
+                o[hh * Dh + e] = sum(ex[u] / z * vals[u][hh * Dh + e] for u in range(len(keys)))
+        return o
+
+    def finish(l, hr, o):
+        p = f"layers.{l}."
+        hr = [x + y for x, y in zip(hr, bf_matvec(W[p + "wo"], o))]
+        f = bf_norm(hr, W[p + "ffn_norm_g"], s.rms_eps)
+        g, u = bf_matvec(W[p + "w_gate"], f), bf_matvec(W[p + "w_up"], f)
+        act = [gi / (1.0 + math.exp(-gi)) * ui for gi, ui in zip(g, u)]
+        return [x + y for x, y in zip(hr, bf_matvec(W[p + "w_down"], act))]
+
+    # pass 1: full forward over x_old, remembering every layer's K, V
+    h = [list(W["tok_emb"][t]) for t in x_old]
+    stored = []
+    for l in range(s.n_layers):
+        rows = [qkv_row(l, h[t], t) for t in range(T)]
+        ks, vs = [r[1] for r in rows], [r[2] for r in rows]
+        stored.append((ks, vs))
+        h = [finish(l, h[t], attend(rows[t][0], ks, vs)) for t in range(T)]
+    # pass 2: the block alone
+    hb = [list(W["tok_emb"][t]) for t in x_new_block]
+    for l in range(s.n_layers):
+        rows = [qkv_row(l, hb[j], c + j) for j in range(n)]
+        ks, vs = [list(r) for r in stored[l][0]], [list(r) for r in stored[l][1]]
+        for j in range(n):
+            ks[c + j], vs[c + j] = rows[j][1], rows[j][2]
+        hb = [finish(l, hb[j], attend(rows[j][0], ks, vs)) for j in range(n)]
+    return [bf_matvec(W["lm_head"], bf_norm(hr, W["final_norm_g"], s.rms_eps)) for hr in hb]
+
+
+def test_dual_cache_first_step_equals_full_forward():
+    # Right after the refresh nothing is stale: the block's fresh K/V equal the stored ones.
+    s = tiny_shape(L=3)
+    w = tiny_weights(s, 11)
+    m = O.Model(s, w, np.float64)
+    X = np.array([1, 2, 3, 10, 7, 10, 10, 10, 10])
+    c, n = 3, 3
+    got = m.forward_block_dual(m.full_kv(X), X[c:c + n], c)
+    np.testing.assert_allclose(got, m.forward(X, c, n), rtol=1e-9, atol=1e-11)
+
+
+def test_dual_cache_one_layer_is_exact_at_every_step():
+    # With one layer K and V of a position depend on its token alone, so stored entries outside
+    # the block never go stale: the cached step equals the full forward on the updated sequence.
+    s = tiny_shape(L=1)
+    w = tiny_weights(s, 12)
+    m = O.Model(s, w, np.float64)
+    X = np.array([1, 2, 3, 10, 10, 10, 10, 10, 10])
+    c, n = 3, 3
+    cache = m.full_kv(X)
+    X2 = X.copy()
+    X2[c:c + n] = [5, 10, 0]
+    got = m.forward_block_dual(cache, X2[c:c + n], c)
+    np.testing.assert_allclose(got, m.forward(X2, c, n), rtol=1e-10, atol=1e-12)
+
+
+def test_dual_cache_stale_step_matches_scalar_loops():
+    # Two layers, block in the middle, block tokens changed after the refresh: the stored K/V of
+    # the other positions are those of the OLD sequence.  Also: the positions after the block are
+    # attended to (unlike the prefix cache), and the result is not the full forward's.
+    s = tiny_shape(L=2)
+    w = tiny_weights(s, 13)
+    m = O.Model(s, w, np.float64)
+    X = np.array([1, 2, 3, 10, 10, 10, 10, 6, 10])
+    c, n = 3, 3
+    cache = m.full_kv(X)
+    newb = [4, 10, 8]
+    got = m.forward_block_dual(cache, np.array(newb), c)
+    ref = bf_forward_dual(s, w, X.tolist(), newb, c)
+    np.testing.assert_allclose(got, np.array(ref), rtol=1e-10, atol=1e-12)
+    X2 = X.copy()
+    X2[c:c + n] = newb
+    assert np.max(np.abs(got - m.forward(X2, c, n))) > 1e-6          # stale on purpose
+    Xs = X.copy()
+    Xs[7] = 9                                                          # a token after the block
+    other = m.forward_block_dual(m.full_kv(Xs), np.array(newb), c)
+    assert np.max(np.abs(other - got)) > 1e-6                         # the suffix is visible
+
+
 def test_round_bf16_matches_the_library_conversion_and_ties_to_even():
     import torch
     r = np.random.default_rng(3)
