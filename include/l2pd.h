@@ -87,13 +87,26 @@ typedef struct {
   float value;
 } l2pd_logit_bias;
 
+/* KV-cache variants of Sec. 4.3 / Table 2; the paper names them and cites their source, the
+ * mechanisms are that source's.  Both keep per-layer K (rotated) and V, rebuilt at every block start,
+ * and run the steps of a block on the block's rows only.
+ *   PREFIX: the store holds prompt + finished blocks, computed from a forward over that prefix alone;
+ *           a step attends to the stored prefix and to the block itself, not to later positions.
+ *   DUAL:   the store holds every position, computed from a full bidirectional forward over the
+ *           current sequence; a step attends to all positions, the block's own K/V fresh, the rest
+ *           (before and after the block) as stored at the block start. */
+enum { L2PD_CACHE_NONE = 0, L2PD_CACHE_PREFIX = 1, L2PD_CACHE_DUAL = 2 };
+
 /* Decode arguments of Alg. 2 / Alg. 3: generation length L_gen, block size s, threshold tau. */
 typedef struct {
   int32_t gen_len, block_len;       /* gen_len % block_len == 0, block_len <= 256 */
   float threshold;                  /* unmask position j when p_j > threshold (strict) */
   int32_t eotp;                     /* 1: stop after the first finished block whose response holds eos_id */
-  int32_t use_prefix_cache;         /* 1: K/V of prompt + finished blocks cached, refreshed once per block
-                                       (Sec. 4.3, "Prefix Cache"); needs a context created for it */
+  int32_t kv_cache;                 /* L2PD_CACHE_NONE, L2PD_CACHE_PREFIX or L2PD_CACHE_DUAL (Sec. 4.3, Table 2);
+                                       the cached modes need a context created with use_kv_cache */
+  int32_t keep_kv;                  /* l2pd_denoise_step in a cached mode: 0 rebuilds the K/V store from the
+                                       tokens first; 1 uses the store as the previous call left it (stepping
+                                       through a block after a call that rebuilt it).  l2pd_generate ignores it. */
   l2pd_logit_bias bias;
 } l2pd_decode_cfg;
 
@@ -102,12 +115,12 @@ typedef struct l2pd_ctx l2pd_ctx;
 /* Bytes of device workspace a context needs for batches <= max_batch and sequences <= max_seq
  * tokens (prompt + generation).  Returns 0 if the description is invalid. */
 size_t l2pd_workspace_bytes(const l2pd_model_desc* desc, int32_t max_batch, int32_t max_seq,
-                            int32_t use_prefix_cache);
+                            int32_t use_kv_cache);
 
 /* Creates a context.  workspace_dev must stay valid and untouched by the caller until
  * l2pd_destroy.  Host-only work: device-side tables are built by the first call that gets a stream. */
 int32_t l2pd_create(const l2pd_model_desc* desc, const l2pd_weights* weights, int32_t max_batch,
-                    int32_t max_seq, int32_t use_prefix_cache, void* workspace_dev,
+                    int32_t max_seq, int32_t use_kv_cache, void* workspace_dev,
                     size_t workspace_bytes, l2pd_ctx** out);
 void l2pd_destroy(l2pd_ctx* ctx);
 
@@ -128,8 +141,9 @@ int32_t l2pd_forward(l2pd_ctx* ctx, const int32_t* tokens_dev, int32_t B, int32_
  * Optional taps (NULL to skip), all for the active block, written before the update:
  *   logits_dev [B, s, vocab] fp32 (bias applied), conf_dev [B, s], pred_dev [B, s],
  *   filt_dev [B, s] (filter output p), unmask_dev [B, s] (1 where unmasked by this step).
- * With cfg.use_prefix_cache the call first reads state_dev back (it synchronises the stream) and
- * rebuilds the prefix cache for the active block. */
+ * With a cached mode in cfg.kv_cache the call first reads state_dev back (it synchronises the
+ * stream) and, unless cfg.keep_kv is set, rebuilds the K/V store for the active block from the
+ * tokens as they are. */
 int32_t l2pd_denoise_step(l2pd_ctx* ctx, int32_t* tokens_dev, int32_t B, int32_t prompt_len,
                           const l2pd_decode_cfg* cfg, const l2pd_filter* filter, int32_t* state_dev,
                           float* logits_dev, float* conf_dev, int32_t* pred_dev, float* filt_dev,

@@ -41,9 +41,12 @@ class LogitBias(C.Structure):
     _fields_ = [("token_id", C.c_int32), ("gen_pos_from", C.c_int32), ("value", C.c_float)]
 
 
+CACHE_NONE, CACHE_PREFIX, CACHE_DUAL = 0, 1, 2
+
+
 class DecodeCfg(C.Structure):
     _fields_ = [("gen_len", C.c_int32), ("block_len", C.c_int32), ("threshold", C.c_float), ("eotp", C.c_int32),
-                ("use_prefix_cache", C.c_int32), ("bias", LogitBias)]
+                ("kv_cache", C.c_int32), ("keep_kv", C.c_int32), ("bias", LogitBias)]
 
 
 EXPORTS = ("l2pd_workspace_bytes", "l2pd_create", "l2pd_destroy", "l2pd_forward", "l2pd_denoise_step",
@@ -117,6 +120,7 @@ class Engine:
 
     def __init__(self, shape: synth.ModelShape, weights: Dict[str, torch.Tensor], max_batch: int, max_seq: int,
                  prefix_cache: bool = False):
+        """`prefix_cache`: allocate the per-layer K/V stores that the cached decode modes (prefix or dual) need."""
         self.shape = shape
         self.weights = weights          # keeps the device tensors alive
         self.max_batch, self.max_seq, self.prefix_cache = max_batch, max_seq, prefix_cache
@@ -157,9 +161,12 @@ class Engine:
                       flt["b2"].data_ptr())
 
     @staticmethod
-    def cfg_struct(gen_len, block_len, threshold, eotp=False, prefix_cache=False, bias=None) -> DecodeCfg:
+    def cfg_struct(gen_len, block_len, threshold, eotp=False, prefix_cache=False, bias=None,
+                   dual_cache=False) -> DecodeCfg:
         b = LogitBias(0, 0, 0.0) if bias is None else LogitBias(int(bias[0]), int(bias[1]), float(bias[2]))
-        return DecodeCfg(gen_len, block_len, threshold, int(eotp), int(prefix_cache), b)
+        if prefix_cache and dual_cache:
+            raise ValueError("prefix_cache and dual_cache are alternatives")
+        return DecodeCfg(gen_len, block_len, threshold, int(eotp), CACHE_DUAL if dual_cache else int(bool(prefix_cache)), 0, b)
 
     # ---- entry points ----
     def forward(self, tokens: torch.Tensor, row_begin: int = 0, row_count: Optional[int] = None) -> torch.Tensor:
@@ -214,4 +221,4 @@ class Engine:
 
 def engine_for(w: synth.Workload, seed: int, device="cuda", max_batch: Optional[int] = None) -> Engine:
     weights = synth.make_weights(w.model, seed, device)
-    return Engine(w.model, weights, max_batch or w.batch, w.prompt_len + w.gen_len, w.prefix_cache)
+    return Engine(w.model, weights, max_batch or w.batch, w.prompt_len + w.gen_len, w.prefix_cache or w.dual_cache)

@@ -314,7 +314,8 @@ int check_decode_args(const l2pd_ctx* c, int B, int P, const l2pd_decode_cfg* cf
   if (f->in_dim != cfg->block_len || f->hidden < 1 || f->hidden > 1024) return L2PD_EINVAL;
   if (!f->w1_dev || !f->b1_dev || !f->w2_dev || !f->b2_dev) return L2PD_EINVAL;
   if (isnan(cfg->threshold)) return L2PD_EINVAL;
-  if (cfg->use_prefix_cache && !c->cache) return L2PD_EINVAL;
+  if (cfg->kv_cache < L2PD_CACHE_NONE || cfg->kv_cache > L2PD_CACHE_DUAL) return L2PD_EINVAL;
+  if (cfg->kv_cache && !c->cache) return L2PD_EINVAL;
   if (cfg->bias.value != 0.f && (cfg->bias.token_id < 0 || cfg->bias.token_id >= c->m.vocab)) return L2PD_EINVAL;
   if (isnan(cfg->bias.value)) return L2PD_EINVAL;
   return L2PD_OK;
@@ -328,11 +329,13 @@ struct StepTaps {
   uint8_t* unmask;
 };
 
-// Rebuild the prefix cache for block gb: K/V of a forward over X[0 : P + gb*s] alone.
+// Rebuild the K/V store for block gb.  Prefix cache: K/V of a forward over X[0 : P + gb*s] alone.
+// Dual cache: K/V of every position from a full bidirectional forward over X as it is now.
 void run_refresh(l2pd_ctx* c, const int32_t* X, int B, int P, const l2pd_decode_cfg* cfg, int gb, Gate g,
                  hipStream_t s) {
-  const int cpos = P + gb * cfg->block_len;
-  Pass p = {B, cpos, 0, cpos, P + cfg->gen_len, X, true, true};
+  const int T = P + cfg->gen_len;
+  const int rows = cfg->kv_cache == L2PD_CACHE_DUAL ? T : P + gb * cfg->block_len;
+  Pass p = {B, rows, 0, rows, T, X, true, true};
   run_layers(c, p, g, s);
 }
 
@@ -343,11 +346,13 @@ void run_step(l2pd_ctx* c, int32_t* X, int B, int P, const l2pd_decode_cfg* cfg,
   const int sl = cfg->block_len, T = P + cfg->gen_len, nb = cfg->gen_len / sl;
   int* ctl = c->at<int>(L.ctl);
   launch_prepare(state, B, nb, ctl, s);
-  Gate g = {ctl, cfg->use_prefix_cache ? host_gb : -1};
+  Gate g = {ctl, cfg->kv_cache ? host_gb : -1};
   BiasArgs bias = {cfg->bias.token_id, cfg->bias.gen_pos_from, sl, cfg->bias.value};
-  if (cfg->use_prefix_cache) {
+  if (cfg->kv_cache) {
+    // block rows only; their K/V go into the store at the block's positions, and the queries see
+    // the store up to the end of the block (prefix cache) or all of it (dual cache)
     const int cpos = P + host_gb * sl;
-    Pass p = {B, sl, cpos, cpos + sl, T, X, true, false};
+    Pass p = {B, sl, cpos, cfg->kv_cache == L2PD_CACHE_DUAL ? T : cpos + sl, T, X, true, false};
     run_layers(c, p, g, s);
     run_head(c, B, sl, RowMap{B * sl, 0, 0, 0}, taps.logits, true, bias, g, s);
   } else {
@@ -385,13 +390,13 @@ const char* l2pd_strerror(int32_t st) {
 }
 
 size_t l2pd_workspace_bytes(const l2pd_model_desc* desc, int32_t max_batch, int32_t max_seq,
-                            int32_t use_prefix_cache) {
+                            int32_t use_kv_cache) {
   if (!desc_ok(desc) || desc_supported(desc) != L2PD_OK || max_batch < 1 || max_seq < 2) return 0;
-  return make_layout(*desc, max_batch, max_seq, use_prefix_cache).total;
+  return make_layout(*desc, max_batch, max_seq, use_kv_cache).total;
 }
 
 int32_t l2pd_create(const l2pd_model_desc* desc, const l2pd_weights* w, int32_t max_batch, int32_t max_seq,
-                    int32_t use_prefix_cache, void* workspace_dev, size_t workspace_bytes, l2pd_ctx** out) {
+                    int32_t use_kv_cache, void* workspace_dev, size_t workspace_bytes, l2pd_ctx** out) {
   if (!out) return L2PD_EINVAL;
   *out = nullptr;
   if (!desc_ok(desc) || !w || !workspace_dev || max_batch < 1 || max_seq < 2) return L2PD_EINVAL;
@@ -405,7 +410,7 @@ int32_t l2pd_create(const l2pd_model_desc* desc, const l2pd_weights* w, int32_t 
         !w->w_gate[l] || !w->w_up[l] || !w->w_down[l])
       return L2PD_EINVAL;
   if ((uintptr_t)workspace_dev % 256) return L2PD_EINVAL;
-  Layout L = make_layout(*desc, max_batch, max_seq, use_prefix_cache);
+  Layout L = make_layout(*desc, max_batch, max_seq, use_kv_cache);
   if (workspace_bytes < L.total) return L2PD_ENOMEM;
   l2pd_ctx* c = new (std::nothrow) l2pd_ctx();
   if (!c) return L2PD_ENOMEM;
@@ -417,7 +422,7 @@ int32_t l2pd_create(const l2pd_model_desc* desc, const l2pd_weights* w, int32_t 
   c->wo.assign(w->wo, w->wo + n); c->ffn_g.assign(w->ffn_norm_g, w->ffn_norm_g + n);
   c->wg.assign(w->w_gate, w->w_gate + n); c->wu.assign(w->w_up, w->w_up + n);
   c->wd.assign(w->w_down, w->w_down + n);
-  c->max_batch = max_batch; c->max_seq = max_seq; c->cache = use_prefix_cache ? 1 : 0;
+  c->max_batch = max_batch; c->max_seq = max_seq; c->cache = use_kv_cache ? 1 : 0;
   c->ws = static_cast<unsigned char*>(workspace_dev);
   c->ws_bytes = workspace_bytes;
   c->L = L;
@@ -471,7 +476,7 @@ int32_t l2pd_denoise_step(l2pd_ctx* c, int32_t* tokens_dev, int32_t B, int32_t p
   st = ensure_device(c, s);
   if (st) return st;
   int host_gb = -1;
-  if (cfg->use_prefix_cache) {
+  if (cfg->kv_cache) {
     std::vector<int32_t> hs((size_t)B * 3);
     HIP_TRY(c, hipMemcpyAsync(hs.data(), state_dev, hs.size() * 4, hipMemcpyDeviceToHost, s));
     HIP_TRY(c, hipStreamSynchronize(s));
@@ -481,7 +486,7 @@ int32_t l2pd_denoise_step(l2pd_ctx* c, int32_t* tokens_dev, int32_t B, int32_t p
       if (!hs[b * 3 + 2] && hs[b * 3] < host_gb) host_gb = hs[b * 3];
     if (host_gb >= nb) return L2PD_OK;   // every sequence is done: nothing to do
     if (host_gb < 0) return L2PD_EINVAL;
-    run_refresh(c, tokens_dev, B, prompt_len, cfg, host_gb, Gate{nullptr, -1}, s);
+    if (!cfg->keep_kv) run_refresh(c, tokens_dev, B, prompt_len, cfg, host_gb, Gate{nullptr, -1}, s);
   }
   StepTaps taps = {logits_dev, conf_dev, pred_dev, filt_dev, unmask_dev};
   run_step(c, tokens_dev, B, prompt_len, cfg, f, state_dev, host_gb, taps, s);
@@ -541,7 +546,7 @@ int32_t l2pd_generate(l2pd_ctx* c, const int32_t* prompt_dev, int32_t B, int32_t
     return c->pinned[last * CTL_WORDS + CTL_ALL_DONE] ? 1 : 0;
   };
 
-  if (cfg->use_prefix_cache) {
+  if (cfg->kv_cache) {
     for (int gb = 0; gb < nb; ++gb) {
       launch_prepare(state, B, nb, ctl, s);
       run_refresh(c, X, B, P, cfg, gb, Gate{ctl, -1}, s);

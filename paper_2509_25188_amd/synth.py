@@ -63,6 +63,7 @@ class Workload:
     threshold: float
     eotp: bool = False
     prefix_cache: bool = False
+    dual_cache: bool = False
     bias_from: int = -1      # generation position from which the EOS logit bias applies (-1: none)
     bias_value: float = 0.0
     prompt_hi: int = 0       # prompt ids are uniform in [0, prompt_hi)
@@ -77,6 +78,8 @@ WORKLOADS: Dict[str, Workload] = {
     "mid": Workload("mid", _MID, 8, 128, 256, 32, 128, 0.7, prompt_hi=31998),
     "8b_g256": Workload("8b_g256", _8B, 1, 256, 256, 32, 128, 0.9, prompt_hi=126081),
     "8b_g1024_eotp": Workload("8b_g1024_eotp", _8B, 1, 256, 1024, 32, 128, 0.9, eotp=True,
+                              bias_from=300, bias_value=20.0, prompt_hi=126081),
+    "8b_g1024_dual": Workload("8b_g1024_dual", _8B, 1, 256, 1024, 32, 128, 0.9, eotp=True, dual_cache=True,
                               bias_from=300, bias_value=20.0, prompt_hi=126081),
     "8b_b32_prefix": Workload("8b_b32_prefix", _8B, 32, 512, 512, 64, 128, 0.9, eotp=True,
                               prefix_cache=True, bias_from=400, bias_value=20.0, prompt_hi=126081),

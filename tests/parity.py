@@ -133,6 +133,12 @@ def teacher_forced(engine: Bd.Engine, trace_per_seq, prompt_len, cfg, flt_dev, s
                 continue
             X = torch.tensor(rec["X_before"], dtype=torch.int32, device=dev).view(1, -1)
             state = torch.tensor([[rec["block"], i, 0]], dtype=torch.int32, device=dev)
+            # dual cache: the stored K/V are those of the block's first state; later steps of the
+            # block must run on that store, not on one rebuilt from their own state
+            first_of_block = i == 0 or trace[i - 1]["block"] != rec["block"]
+            if cfg.kv_cache == Bd.CACHE_DUAL:
+                assert not sample, "dual-cache steps depend on the block's earlier calls: no sampling"
+                cfg.keep_kv = 0 if first_of_block else 1
             taps = engine.denoise_step(X, prompt_len, state, flt_dev, cfg, want_logits=want_logits)
             torch.cuda.synchronize()
             same = check_step(rec, taps, 0, shape, tau, tol, rep, check_logits=want_logits)
@@ -152,13 +158,13 @@ def oracle_generate(model, prompt_row, w: synth.Workload, flt_np, trace=None, ta
     bias = (w.model.eos_id, w.bias_from, w.bias_value) if w.bias_value else None
     return O.generate(model, prompt_row, w.gen_len, w.block_len, w.model.mask_id, w.model.eos_id, flt_np,
                       w.threshold if tau is None else tau, eotp=w.eotp, bias=bias, prefix_cache=w.prefix_cache,
-                      trace=trace)
+                      trace=trace, dual_cache=w.dual_cache)
 
 
 def cfg_for(w: synth.Workload, tau=None):
     bias = (w.model.eos_id, w.bias_from, w.bias_value) if w.bias_value else None
     return Bd.Engine.cfg_struct(w.gen_len, w.block_len, w.threshold if tau is None else tau, w.eotp,
-                                w.prefix_cache, bias)
+                                w.prefix_cache, bias, w.dual_cache)
 
 
 def random_state(w: synth.Workload, seed: int, block: int, n_committed: int, b: int = 0):
@@ -178,8 +184,9 @@ def oracle_step_record(model, X, w: synth.Workload, flt_np, block: int):
     """The oracle's record of one step taken from state X (X is not modified)."""
     bias = (w.model.eos_id, w.bias_from, w.bias_value) if w.bias_value else None
     Xc = np.array(X, copy=True)
-    cache = model.prefix_kv(Xc[:w.prompt_len + block * w.block_len]) if w.prefix_cache else None
+    cache = model.prefix_kv(Xc[:w.prompt_len + block * w.block_len]) if w.prefix_cache else (
+        model.full_kv(Xc) if w.dual_cache else None)
     rec = O.denoise_step(model, Xc, w.prompt_len, block, w.block_len, w.model.mask_id, flt_np, w.threshold, bias,
-                         cache)
+                         cache, w.dual_cache)
     rec.update(X_before=np.array(X, copy=True), block=block)
     return rec

@@ -21,7 +21,8 @@ def small_bf16(name, L, d, H, Dh, F, V, B, P, G, s, hidden=32, tau=0.7, **kw):
 
 def build(w: synth.Workload, seed=SEED, lm_head_scale=1.0, max_batch=None):
     weights = synth.make_weights(w.model, seed, "cpu", lm_head_scale=lm_head_scale)
-    eng = Bd.Engine(w.model, Pz.to_dev(weights), max_batch or w.batch, w.prompt_len + w.gen_len, w.prefix_cache)
+    eng = Bd.Engine(w.model, Pz.to_dev(weights), max_batch or w.batch, w.prompt_len + w.gen_len,
+                    w.prefix_cache or w.dual_cache)
     ora = Pz.oracle_model(w.model, weights)
     flt = synth.make_filter(seed, w.block_len, w.filter_hidden, "cpu")
     prompt = synth.make_prompt(seed, w.batch, w.prompt_len, w.prompt_hi, "cpu")
@@ -180,7 +181,59 @@ def test_prefix_cache_fp32_matches_oracle():
         assert int(st[b]) == outs[b][1]
 
 
+def test_dual_cache_fp32_matches_oracle():
+    # Two layers: stored K/V outside the block go stale within a block, and the library must follow
+    # the oracle's stale trajectory, not the full-recompute one.
+    m = synth.WORKLOADS["tiny"].model
+    w = synth.Workload("tiny_dc", m, 2, 24, 96, 32, 48, 0.5, dual_cache=True, prompt_hi=1022)
+    eng, ora, flt, prompt = build(w, lm_head_scale=25.0)
+    fdev = {k: v.cuda() for k, v in flt.items()}
+    cfg = Pz.cfg_for(w)
+    traces, outs = [], []
+    for b in range(2):
+        tr = []
+        outs.append(Pz.oracle_generate(ora, prompt[b].numpy(), w, Pz.np_filter(flt), tr))
+        traces.append(tr)
+    # the case is discriminating: some later step of a block differs from the full forward on its state
+    gaps = [Pz.rel_err(ora.forward(t["X_before"], w.prompt_len + t["block"] * 32, 32), t["logits"])
+            for i, t in enumerate(traces[0]) if i and traces[0][i - 1]["block"] == t["block"]]
+    assert max(gaps) > 1e-3
+    rep = Pz.StepReport()
+    Pz.teacher_forced(eng, traces, w.prompt_len, cfg, fdev, w.model, w.threshold, rep)
+    print("dual-cache fp32 teacher-forced:", rep)
+    assert rep.max_logit_err < 1e-4
+    tok, st, dl = eng.generate(prompt.cuda(), fdev, Pz.cfg_for(w))
+    for b in range(2):
+        np.testing.assert_array_equal(tok.cpu().numpy()[b], outs[b][0])
+        assert int(st[b]) == outs[b][1]
+
+
 # ------------------------------------------------------------------------------------------ decode, bf16
+def test_bf16_dual_cache_and_eotp():
+    w = small_bf16("bf_dc", 2, 256, 2, 128, 320, 1500, 3, 33, 192, 64, hidden=32, tau=0.8, eotp=True,
+                   dual_cache=True, bias_from=70, bias_value=30.0)
+    eng, ora, flt, prompt = build(w, lm_head_scale=25.0)
+    fdev = {k: v.cuda() for k, v in flt.items()}
+    cfg = Pz.cfg_for(w)
+    traces, outs = [], []
+    for b in range(3):
+        tr = []
+        outs.append(Pz.oracle_generate(ora, prompt[b].numpy(), w, Pz.np_filter(flt), tr))
+        traces.append(tr)
+        assert outs[b][2] == 128          # EOS bias from position 70: stop after block 1 of 3
+    rep = Pz.StepReport()
+    same = Pz.teacher_forced(eng, traces, w.prompt_len, cfg, fdev, w.model, w.threshold, rep)
+    print("bf16 dual-cache teacher-forced:", rep)
+    assert rep.max_logit_err < 2e-2
+    tok, st, dl = eng.generate(prompt.cuda(), fdev, Pz.cfg_for(w))
+    assert dl.tolist() == [128, 128, 128]
+    assert np.all(tok.cpu().numpy()[:, 128:] == w.model.mask_id)
+    if same:
+        for b in range(3):
+            np.testing.assert_array_equal(tok.cpu().numpy()[b], outs[b][0])
+            assert int(st[b]) == outs[b][1]
+
+
 def test_bf16_small_teacher_forced_and_generate():
     w = small_bf16("bf_dec", 2, 256, 4, 64, 512, 2000, 2, 40, 64, 32, tau=0.7)
     eng, ora, flt, prompt = build(w, lm_head_scale=25.0)

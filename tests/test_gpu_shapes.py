@@ -18,7 +18,7 @@ SEED = 1234
 def setup(w: synth.Workload, max_batch=1):
     weights = synth.make_weights(w.model, SEED, "cpu")
     ora = Pz.oracle_model(w.model, weights)
-    eng = Bd.Engine(w.model, Pz.to_dev(weights), max_batch, w.prompt_len + w.gen_len, w.prefix_cache)
+    eng = Bd.Engine(w.model, Pz.to_dev(weights), max_batch, w.prompt_len + w.gen_len, w.prefix_cache or w.dual_cache)
     del weights
     flt = synth.make_filter(SEED, w.block_len, w.filter_hidden)
     return eng, ora, flt
@@ -69,6 +69,43 @@ def test_8b_width_prefix_cache_block64():
     rep = Pz.StepReport()
     forced_steps(w, eng, ora, flt, [(0, 0, 6), (5, 40, 7)], rep)
     print("8b width, prefix cache, block 64:", rep)
+    assert rep.max_logit_err < 2e-2
+
+
+def test_8b_width_dual_cache_fresh_and_stale_step():
+    # T = 1280, two layers: a step right after the store is rebuilt, then a step on a later state of
+    # the same block that must still see the store of the block's first state (stale outside the block)
+    w = synth.with_layers(synth.WORKLOADS["8b_g1024_dual"], 2)
+    eng, ora, flt = setup(w)
+    fdev = {k: v.cuda() for k, v in flt.items()}
+    fnp = Pz.np_filter(flt)
+    cfg = Pz.cfg_for(w)
+    block = 9
+    lo = w.prompt_len + block * w.block_len
+    bias = (w.model.eos_id, w.bias_from, w.bias_value)
+    XA = Pz.random_state(w, 11, block, 3)
+    XB = np.array(XA, copy=True)
+    rng = np.random.default_rng(12)
+    masked = np.nonzero(XB[lo:lo + w.block_len] == w.model.mask_id)[0]
+    XB[lo + masked[:10]] = rng.integers(0, w.prompt_hi, 10)          # ten more positions committed
+    cache = ora.full_kv(XA)
+    rep = Pz.StepReport()
+    for X, keep in ((XA, 0), (XB, 1)):
+        Xc = np.array(X, copy=True)
+        rec = Pz.O.denoise_step(ora, Xc, w.prompt_len, block, w.block_len, w.model.mask_id, fnp, w.threshold, bias,
+                                cache, True)
+        rec.update(X_before=np.array(X, copy=True), block=block)
+        if keep:
+            fresh = ora.forward(X, lo, w.block_len)
+            stale_gap = Pz.rel_err(Pz.O.apply_bias(fresh, block * w.block_len, bias), rec["logits"])
+            print(f"dual cache: stale step differs from the full forward by {stale_gap:.3e}")
+        Xd = torch.tensor(X, dtype=torch.int32, device="cuda").view(1, -1)
+        state = torch.tensor([[block, 5, 0]], dtype=torch.int32, device="cuda")
+        cfg.keep_kv = keep
+        taps = eng.denoise_step(Xd, w.prompt_len, state, fdev, cfg, want_logits=True)
+        torch.cuda.synchronize()
+        Pz.check_step(rec, taps, 0, w.model, w.threshold, Pz.tol_for(w.model), rep)
+    print("8b width, dual cache:", rep)
     assert rep.max_logit_err < 2e-2
 
 
