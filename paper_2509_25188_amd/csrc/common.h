@@ -44,9 +44,10 @@ void launch_init_decode(int32_t* X, const int32_t* prompt, int B, int P, int G, 
 void launch_prepare(const int32_t* state, int B, int n_blocks, int* ctl, hipStream_t s);
 void launch_embed(float* h, const void* emb, int dtype, const int32_t* tokens, RowMap tokmap, int rows, int d,
                   Gate g, hipStream_t s);
-// h (+= p0 + p1 when given; written back) -> y = rmsnorm(h) * gain, rows taken through `src`.
-void launch_rmsnorm(float* h, const float* p0, const float* p1, RowMap src, const void* gain, int dtype,
-                    void* y, int rows, int d, float eps, Gate g, hipStream_t s);
+// h (+= part[0] + ... + part[n_parts-1] in that order when given; written back) -> y = rmsnorm(h) * gain,
+// rows taken through `src`.  part z is at parts + z * part_stride, laid out like h.
+void launch_rmsnorm(float* h, const float* parts, int n_parts, size_t part_stride, RowMap src, const void* gain,
+                    int dtype, void* y, int rows, int d, float eps, Gate g, hipStream_t s);
 struct UpdateArgs {
   int32_t* X;            // [B, T]
   int32_t* state;        // [B, 3]
@@ -101,8 +102,20 @@ struct QkvEpilogue {
 void launch_gemm_qkv_bf16(const bf16* A, const bf16* wq, const bf16* wk, const bf16* wv, int M, int K,
                           const QkvEpilogue& e, Gate g, hipStream_t s);
 // partial[z][M,N] = A[:, z-th K slice] * W[:, slice]^T, z < splits (1 or 2)
-void launch_gemm_partial_bf16(const bf16* A, const bf16* W, float* part0, float* part1, int M, int N, int K,
+void launch_gemm_partial_bf16(const bf16* A, const bf16* W, float* parts, size_t part_stride, int M, int N, int K,
                               int splits, Gate g, hipStream_t s);
+// Few-row GEMMs (block-only steps of the cached decode modes, at most kSkinnyRows rows) stream their
+// weights once; K is split until a launch has a few hundred workgroups, each K range staying a
+// multiple of the 64-wide stage.
+constexpr int kSkinnyRows = 64;
+int skinny_splits(int N, int K);
+void launch_gemm_skinny_bf16(const bf16* A, const bf16* w0, const bf16* w1, const bf16* w2, int n_sub, float* parts,
+                             size_t part_stride, int M, int N, int K, int splits, Gate g, hipStream_t s);
+// sums of the skinny GEMM's partials -> rotated q, K store, V^T store / SiLU(gate) * up
+void launch_skinny_qkv_finish(const float* parts, int n_parts, size_t part_stride, int rows, const QkvEpilogue& e,
+                              Gate g, hipStream_t s);
+void launch_skinny_swiglu_finish(const float* parts, int n_parts, size_t part_stride, int rows, int F, bf16* act,
+                                 Gate g, hipStream_t s);
 // act[M, F] = silu(A Wg^T) * (A Wu^T)
 void launch_gemm_swiglu_bf16(const bf16* A, const bf16* wg, const bf16* wu, bf16* act, int M, int F, int K, Gate g,
                              hipStream_t s);

@@ -34,9 +34,10 @@ struct GemmArgs {
   int M, N, K;          // N counts tile-space columns (for pair epilogues: both sides)
   int tiles_m, tiles_n, splits;
   Gate gate;
-  // EPI_PARTIAL
-  float* part0;
-  float* part1;
+  // EPI_PARTIAL: K range z writes to parts + z * part_stride (fp32 [M, N])
+  float* parts;
+  size_t part_stride;
+  int n_sub;            // > 0: the N rows are the rows of B0, B1, B2 stacked, n_sub rows each
   // EPI_SWIGLU
   bf16* act;
   int F;
@@ -159,8 +160,14 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
       const bf16* base;
       size_t grow;
       if constexpr (!PAIR) {
+        int gn = min(n0 + r, a.N - 1);
         base = a.B0;
-        grow = (size_t)min(n0 + r, a.N - 1);
+        if (a.n_sub > 0) {
+          const int mat = gn / a.n_sub;
+          gn -= mat * a.n_sub;
+          base = mat == 0 ? a.B0 : (mat == 1 ? a.B1 : a.B2);
+        }
+        grow = (size_t)gn;
       } else {
         int rw = r / (32 * FN), f = (r >> 5) % FN, j = r & 31;
         int G = tile_n * (BN / 64) + rw * (FN / 2) + (f >> 1), side = f & 1;
@@ -289,7 +296,7 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
   // C layout of the 32x32 MFMA: register r of a lane is row (r/4)*8 + hf*4 + r%4, column lj.
   const int row_base = m0 + wm * (BM / WM);
   if constexpr (EPI == EPI_PARTIAL) {
-    float* out = z == 0 ? a.part0 : a.part1;
+    float* out = a.parts + (size_t)z * a.part_stride;
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -558,13 +565,35 @@ void launch_gemm_qkv_bf16(const bf16* A, const bf16* wq, const bf16* wk, const b
   }
 }
 
-void launch_gemm_partial_bf16(const bf16* A, const bf16* W, float* part0, float* part1, int M, int N, int K,
+void launch_gemm_partial_bf16(const bf16* A, const bf16* W, float* parts, size_t part_stride, int M, int N, int K,
                               int splits, Gate g, hipStream_t s) {
   GemmArgs a = {};
   a.A = A; a.B0 = W; a.M = M; a.N = N; a.K = K; a.splits = splits; a.gate = g;
-  a.part0 = part0; a.part1 = part1;
+  a.parts = parts; a.part_stride = part_stride;
   if (splits == 1 && pick_tile(M, N) == 2) launch<256, 256, 32, 4, 2, 4, EPI_PARTIAL>(a, s);
   else launch<128, 128, 64, 2, 2, 4, EPI_PARTIAL>(a, s);
+}
+
+int skinny_splits(int N, int K) {
+  const int tiles = (N + 127) / 128;
+  int S = 1;
+  while (tiles * S < 256 && S < 16 && K % (S * 2 * 64) == 0 && K / (S * 2) >= 256) S *= 2;
+  return S;
+}
+
+// Few rows (a block-only step of the cached decode modes: 32 or 64 rows): every GEMM is bound by
+// streaming its weights once, which needs several workgroups per CU with deep rings in flight.
+// 32- or 64-row tiles, 128 columns, K split `splits` ways into fp32 partials; up to three weight
+// matrices of n_sub rows each are stacked along N (Q/K/V, gate/up) so that one launch covers them.
+// The nonlinear epilogues (RoPE, SwiGLU) run afterwards on the summed partials.
+void launch_gemm_skinny_bf16(const bf16* A, const bf16* w0, const bf16* w1, const bf16* w2, int n_sub, float* parts,
+                             size_t part_stride, int M, int N, int K, int splits, Gate g, hipStream_t s) {
+  GemmArgs a = {};
+  a.A = A; a.B0 = w0; a.B1 = w1; a.B2 = w2; a.n_sub = w1 ? n_sub : 0;
+  a.M = M; a.N = N; a.K = K; a.splits = splits; a.gate = g;
+  a.parts = parts; a.part_stride = part_stride;
+  if (M <= 32) launch<32, 128, 64, 1, 4, 4, EPI_PARTIAL>(a, s);
+  else launch<64, 128, 64, 2, 2, 4, EPI_PARTIAL>(a, s);
 }
 
 void launch_gemm_swiglu_bf16(const bf16* A, const bf16* wg, const bf16* wu, bf16* act, int M, int F, int K, Gate g,

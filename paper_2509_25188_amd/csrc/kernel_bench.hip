@@ -77,20 +77,16 @@ static int bench_layer(int rows, int d, int F, int H) {
   bf16 *wg = random_bf16((size_t)F * d, 7, 0.02f), *wu = random_bf16((size_t)F * d, 8, 0.02f),
        *wd = random_bf16((size_t)d * F, 9, 0.02f), *gain = random_bf16(d, 10, 1.f);
   bf16 *q, *ks, *vts, *ao, *act;
-  float *p0, *p1, *h, *cs, *sn;
+  float *parts, *h, *cs, *sn;
   CK(hipMalloc(&q, (size_t)rows * d * 2));
   CK(hipMalloc(&ks, (size_t)Tpad * d * 2));
   CK(hipMalloc(&vts, (size_t)Tpad * d * 2));
   CK(hipMalloc(&ao, (size_t)rows * d * 2));
   CK(hipMalloc(&act, (size_t)rows * F * 2));
-  CK(hipMalloc(&p0, (size_t)rows * d * 4));
-  CK(hipMalloc(&p1, (size_t)rows * d * 4));
   CK(hipMalloc(&h, (size_t)rows * d * 4));
   CK(hipMalloc(&cs, (size_t)Tpad * (Dh / 2) * 4));
   CK(hipMalloc(&sn, (size_t)Tpad * (Dh / 2) * 4));
   CK(hipMemset(h, 0, (size_t)rows * d * 4));
-  CK(hipMemset(p0, 0, (size_t)rows * d * 4));
-  CK(hipMemset(p1, 0, (size_t)rows * d * 4));
   CK(hipMemset(ks, 0, (size_t)Tpad * d * 2));
   CK(hipMemset(vts, 0, (size_t)Tpad * d * 2));
   {
@@ -102,31 +98,63 @@ static int bench_layer(int rows, int d, int F, int H) {
   const Gate g = {nullptr, -1};
   const RowMap ident = {rows, 0, 0, 0};
   const QkvEpilogue qe = {q, ks, vts, cs, sn, rows, 0, Tpad, H, Dh, d};
-  // the library splits K in two on the [d, d] and [d, F] projections when there are few row tiles
+  // routing and split counts as in the library: the few-row path up to kSkinnyRows rows, else the wide path,
+  // which splits K in two on the [d, d] and [d, F] projections when there are few row tiles
+  const bool skinny = rows <= kSkinnyRows;
   const int tiles = ((rows + 127) / 128) * (d / 128);
-  const int so = (tiles < 256 && (d / 64) % 2 == 0) ? 2 : 1, sd = (tiles < 256 && (F / 64) % 2 == 0) ? 2 : 1;
-  printf("one layer, %d rows (one sequence), d_model %d, d_ffn %d, %d heads of %d; bf16, random operands\n", rows, d, F,
-         H, Dh);
+  const int so = skinny ? skinny_splits(d, d) : ((tiles < 256 && (d / 64) % 2 == 0) ? 2 : 1);
+  const int sd = skinny ? skinny_splits(d, F) : ((tiles < 256 && (F / 64) % 2 == 0) ? 2 : 1);
+  const int sq = skinny ? skinny_splits(3 * d, d) : 1, sg = skinny ? skinny_splits(2 * F, d) : 1;
+  size_t pbytes = (size_t)2 * rows * d * 4;
+  for (size_t b : {(size_t)sq * rows * 3 * d * 4, (size_t)sg * rows * 2 * F * 4, (size_t)so * rows * d * 4,
+                   (size_t)sd * rows * d * 4})
+    if (b > pbytes) pbytes = b;
+  CK(hipMalloc(&parts, pbytes));
+  CK(hipMemset(parts, 0, pbytes));
+  const size_t stride_d = (size_t)rows * d;
+  printf("one layer, %d rows (one sequence), d_model %d, d_ffn %d, %d heads of %d; bf16, random operands; %s path\n", rows,
+         d, F, H, Dh, skinny ? "few-row" : "wide");
   auto line = [](const char* name, float us, double flop, double bytes) {
-    printf("  %-44s %8.1f us", name, us);
+    printf("  %-52s %8.1f us", name, us);
     if (flop > 0) printf("  %7.1f TFLOP/s", flop / us / 1e6);
     if (bytes > 0) printf("  %7.1f GB/s", bytes / us / 1e3);
     printf("\n");
     fflush(stdout);
   };
+  const double wb = 2.0;   // bytes per weight
   float t;
-  t = time_us([&] { launch_rmsnorm(h, p0, so > 1 ? p1 : nullptr, ident, gain, L2PD_BF16, xn, rows, d, 1e-5f, g, 0); });
+  t = time_us([&] { launch_rmsnorm(h, parts, so, stride_d, ident, gain, L2PD_BF16, xn, rows, d, 1e-5f, g, 0); });
   line("RMSNorm (+ fold of split-K partials)", t, 0, (double)rows * d * (4.0 * (2 + so) + 2));
-  t = time_us([&] { launch_gemm_qkv_bf16(xn, wq, wk, wv, rows, d, qe, g, 0); });
-  line("QKV projection + RoPE + K / V^T store", t, 2.0 * rows * d * 3 * d, 0);
+  if (skinny) {
+    t = time_us([&] {
+      launch_gemm_skinny_bf16(xn, wq, wk, wv, d, parts, (size_t)rows * 3 * d, rows, 3 * d, d, sq, g, 0);
+      launch_skinny_qkv_finish(parts, sq, (size_t)rows * 3 * d, rows, qe, g, 0);
+    });
+    line("QKV projection (split-K) + RoPE / store kernel", t, 0, wb * 3 * d * d);
+  } else {
+    t = time_us([&] { launch_gemm_qkv_bf16(xn, wq, wk, wv, rows, d, qe, g, 0); });
+    line("QKV projection + RoPE + K / V^T store", t, 2.0 * rows * d * 3 * d, 0);
+  }
   t = time_us([&] { launch_attn_bf16(q, ks, vts, ao, 1, rows, rows, Tpad, H, Dh, g, 0); });
-  line("bidirectional attention", t, 4.0 * rows * rows * d, 0);
-  t = time_us([&] { launch_gemm_partial_bf16(ao, wo, p0, p1, rows, d, d, so, g, 0); });
-  line("output projection (split-K partials)", t, 2.0 * rows * d * d, 0);
-  t = time_us([&] { launch_gemm_swiglu_bf16(xn, wg, wu, act, rows, F, d, g, 0); });
-  line("gate / up projection + SwiGLU", t, 2.0 * rows * d * 2 * F, 0);
-  t = time_us([&] { launch_gemm_partial_bf16(act_in, wd, p0, p1, rows, d, F, sd, g, 0); });
-  line("down projection (split-K partials)", t, 2.0 * rows * d * F, 0);
+  line("bidirectional attention (keys = rows)", t, 4.0 * rows * rows * d, 0);
+  if (skinny) {
+    t = time_us([&] { launch_gemm_skinny_bf16(ao, wo, nullptr, nullptr, 0, parts, stride_d, rows, d, d, so, g, 0); });
+    line("output projection (split-K partials)", t, 0, wb * d * d);
+    t = time_us([&] {
+      launch_gemm_skinny_bf16(xn, wg, wu, nullptr, F, parts, (size_t)rows * 2 * F, rows, 2 * F, d, sg, g, 0);
+      launch_skinny_swiglu_finish(parts, sg, (size_t)rows * 2 * F, rows, F, act, g, 0);
+    });
+    line("gate / up projection (split-K) + SwiGLU kernel", t, 0, wb * 2 * F * d);
+    t = time_us([&] { launch_gemm_skinny_bf16(act_in, wd, nullptr, nullptr, 0, parts, stride_d, rows, d, F, sd, g, 0); });
+    line("down projection (split-K partials)", t, 0, wb * d * F);
+  } else {
+    t = time_us([&] { launch_gemm_partial_bf16(ao, wo, parts, stride_d, rows, d, d, so, g, 0); });
+    line("output projection (split-K partials)", t, 2.0 * rows * d * d, 0);
+    t = time_us([&] { launch_gemm_swiglu_bf16(xn, wg, wu, act, rows, F, d, g, 0); });
+    line("gate / up projection + SwiGLU", t, 2.0 * rows * d * 2 * F, 0);
+    t = time_us([&] { launch_gemm_partial_bf16(act_in, wd, parts, stride_d, rows, d, F, sd, g, 0); });
+    line("down projection (split-K partials)", t, 2.0 * rows * d * F, 0);
+  }
   return 0;
 }
 

@@ -111,24 +111,23 @@ __device__ __forceinline__ float wave_sum(float v) {
 }
 
 // One wavefront per row: the row's sum of squares is a 64-lane butterfly, no LDS.
-// When partial buffers are given the residual update h += p0 + p1 (fixed order) is folded in.
+// When partial buffers are given the residual update h += part[0] + part[1] + ... (that order) is
+// folded in; part z is at parts + z * part_stride, laid out like h.
 template <typename T>
-__global__ void k_rmsnorm(float* h, const float* p0, const float* p1, RowMap src, const T* gain, T* y, int rows,
-                          int d, float eps, Gate g) {
+__global__ void k_rmsnorm(float* h, const float* parts, int n_parts, size_t part_stride, RowMap src, const T* gain,
+                          T* y, int rows, int d, float eps, Gate g) {
   if (gate_skip(g)) return;
   int lane = threadIdx.x & 63;
   int r = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (r >= rows) return;
   size_t srow = (size_t)map_row(src, r, g.ctl);
   float* x = h + srow * d;
-  const float* a0 = p0 ? p0 + srow * d : nullptr;
-  const float* a1 = p1 ? p1 + srow * d : nullptr;
+  const float* a0 = parts + srow * d;
   float ss = 0.f;
   for (int i = lane; i < d; i += 64) {
     float v = x[i];
-    if (a0) {
-      v += a0[i];
-      if (a1) v += a1[i];
+    if (n_parts > 0) {
+      for (int z = 0; z < n_parts; ++z) v += a0[z * part_stride + i];
       x[i] = v;
     }
     ss += v * v;
@@ -141,8 +140,9 @@ __global__ void k_rmsnorm(float* h, const float* p0, const float* p1, RowMap src
 // Same, with the row held in registers: VPL float4 per lane, all loads of a row in flight at once,
 // one pass over memory.  Used when d is a multiple of 4 and d <= 1024 * VPL.
 template <typename T, int VPL>
-__global__ void __launch_bounds__(256) k_rmsnorm_vec(float* h, const float* p0, const float* p1, RowMap src,
-                                                    const T* gain, T* y, int rows, int d, float eps, Gate g) {
+__global__ void __launch_bounds__(256) k_rmsnorm_vec(float* h, const float* parts, int n_parts, size_t part_stride,
+                                                    RowMap src, const T* gain, T* y, int rows, int d, float eps,
+                                                    Gate g) {
   if (gate_skip(g)) return;
   const int lane = threadIdx.x & 63;
   const int r = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
@@ -150,27 +150,28 @@ __global__ void __launch_bounds__(256) k_rmsnorm_vec(float* h, const float* p0, 
   const size_t srow = (size_t)map_row(src, r, g.ctl);
   const int d4 = d >> 2;
   float4* x = reinterpret_cast<float4*>(h + srow * d);
-  const float4* a0 = p0 ? reinterpret_cast<const float4*>(p0 + srow * d) : nullptr;
-  const float4* a1 = p1 ? reinterpret_cast<const float4*>(p1 + srow * d) : nullptr;
   float4 v[VPL];
 #pragma unroll
   for (int k = 0; k < VPL; ++k) {
     const int i = lane + 64 * k;
     v[k] = i < d4 ? x[i] : make_float4(0.f, 0.f, 0.f, 0.f);
   }
-  if (a0) {
+  if (n_parts > 0) {
+    for (int z = 0; z < n_parts; ++z) {
+      const float4* az = reinterpret_cast<const float4*>(parts + z * part_stride + srow * d);
+#pragma unroll
+      for (int k = 0; k < VPL; ++k) {
+        const int i = lane + 64 * k;
+        if (i < d4) {
+          float4 t = az[i];
+          v[k].x += t.x; v[k].y += t.y; v[k].z += t.z; v[k].w += t.w;
+        }
+      }
+    }
 #pragma unroll
     for (int k = 0; k < VPL; ++k) {
       const int i = lane + 64 * k;
-      if (i < d4) {
-        float4 t = a0[i];
-        v[k].x += t.x; v[k].y += t.y; v[k].z += t.z; v[k].w += t.w;
-        if (a1) {
-          float4 u = a1[i];
-          v[k].x += u.x; v[k].y += u.y; v[k].z += u.z; v[k].w += u.w;
-        }
-        x[i] = v[k];
-      }
+      if (i < d4) x[i] = v[k];
     }
   }
   float ss = 0.f;
@@ -203,8 +204,9 @@ __global__ void __launch_bounds__(256) k_rmsnorm_vec(float* h, const float* p0, 
 // The choice between the two depends on d only, never on the number of rows, so that a row's
 // result does not depend on the batch it is part of.
 template <typename T, int VPL>
-__global__ void __launch_bounds__(256) k_rmsnorm_row(float* h, const float* p0, const float* p1, RowMap src,
-                                                    const T* gain, T* y, int rows, int d, float eps, Gate g) {
+__global__ void __launch_bounds__(256) k_rmsnorm_row(float* h, const float* parts, int n_parts, size_t part_stride,
+                                                    RowMap src, const T* gain, T* y, int rows, int d, float eps,
+                                                    Gate g) {
   if (gate_skip(g)) return;
   __shared__ float s_part[4];
   const int tid = threadIdx.x;
@@ -212,26 +214,36 @@ __global__ void __launch_bounds__(256) k_rmsnorm_row(float* h, const float* p0, 
   const size_t srow = (size_t)map_row(src, r, g.ctl);
   const int d4 = d >> 2;
   float4* x = reinterpret_cast<float4*>(h + srow * d);
-  const float4* a0 = p0 ? reinterpret_cast<const float4*>(p0 + srow * d) : nullptr;
-  const float4* a1 = p1 ? reinterpret_cast<const float4*>(p1 + srow * d) : nullptr;
-  float4 v[VPL], t0[VPL], t1[VPL];
+  float4 v[VPL];
 #pragma unroll
   for (int k = 0; k < VPL; ++k) {
     const int i = tid + 256 * k;
-    const bool in = i < d4;
-    v[k] = in ? x[i] : make_float4(0.f, 0.f, 0.f, 0.f);
-    t0[k] = (in && a0) ? a0[i] : make_float4(0.f, 0.f, 0.f, 0.f);
-    t1[k] = (in && a1) ? a1[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+    v[k] = i < d4 ? x[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  // partials two at a time: both groups of loads are in flight together, the adds stay in order
+  for (int z = 0; z < n_parts; z += 2) {
+    const bool two = z + 1 < n_parts;
+    const float4* a0 = reinterpret_cast<const float4*>(parts + z * part_stride + srow * d);
+    const float4* a1 = reinterpret_cast<const float4*>(parts + (two ? z + 1 : z) * part_stride + srow * d);
+    float4 t0[VPL], t1[VPL];
+#pragma unroll
+    for (int k = 0; k < VPL; ++k) {
+      const int i = tid + 256 * k;
+      const bool in = i < d4;
+      t0[k] = in ? a0[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+      t1[k] = (in && two) ? a1[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int k = 0; k < VPL; ++k) {
+      v[k].x += t0[k].x; v[k].y += t0[k].y; v[k].z += t0[k].z; v[k].w += t0[k].w;
+      if (two) { v[k].x += t1[k].x; v[k].y += t1[k].y; v[k].z += t1[k].z; v[k].w += t1[k].w; }
+    }
   }
   float ss = 0.f;
 #pragma unroll
   for (int k = 0; k < VPL; ++k) {
     const int i = tid + 256 * k;
-    if (a0) {
-      v[k].x += t0[k].x; v[k].y += t0[k].y; v[k].z += t0[k].z; v[k].w += t0[k].w;
-      if (a1) { v[k].x += t1[k].x; v[k].y += t1[k].y; v[k].z += t1[k].z; v[k].w += t1[k].w; }
-      if (i < d4) x[i] = v[k];
-    }
+    if (n_parts > 0 && i < d4) x[i] = v[k];
     ss += v[k].x * v[k].x + v[k].y * v[k].y + v[k].z * v[k].z + v[k].w * v[k].w;
   }
   ss = wave_sum(ss);
@@ -259,29 +271,98 @@ __global__ void __launch_bounds__(256) k_rmsnorm_row(float* h, const float* p0, 
 }
 
 template <typename T>
-static void launch_rmsnorm_t(float* h, const float* p0, const float* p1, RowMap src, const T* gain, T* y, int rows,
-                             int d, float eps, Gate g, hipStream_t s) {
+static void launch_rmsnorm_t(float* h, const float* parts, int n_parts, size_t part_stride, RowMap src, const T* gain,
+                             T* y, int rows, int d, float eps, Gate g, hipStream_t s) {
   dim3 grid((rows + 3) / 4), block(256);
   if (rows <= 4096) { grid = dim3(rows); block = dim3(64); }   // few rows: one wavefront per workgroup fills more CUs
   if (d % 4 == 0 && d >= 2048 && d <= 4096)
-    hipLaunchKernelGGL((k_rmsnorm_row<T, 4>), dim3(rows), dim3(256), 0, s, h, p0, p1, src, gain, y, rows, d, eps, g);
+    hipLaunchKernelGGL((k_rmsnorm_row<T, 4>), dim3(rows), dim3(256), 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, g);
   else if (d % 4 == 0 && d > 4096 && d <= 8192)
-    hipLaunchKernelGGL((k_rmsnorm_row<T, 8>), dim3(rows), dim3(256), 0, s, h, p0, p1, src, gain, y, rows, d, eps, g);
+    hipLaunchKernelGGL((k_rmsnorm_row<T, 8>), dim3(rows), dim3(256), 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, g);
   else if (d % 4 == 0 && d <= 1024)
-    hipLaunchKernelGGL((k_rmsnorm_vec<T, 4>), grid, block, 0, s, h, p0, p1, src, gain, y, rows, d, eps, g);
+    hipLaunchKernelGGL((k_rmsnorm_vec<T, 4>), grid, block, 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, g);
   else if (d % 4 == 0 && d <= 4096)
-    hipLaunchKernelGGL((k_rmsnorm_vec<T, 16>), grid, block, 0, s, h, p0, p1, src, gain, y, rows, d, eps, g);
+    hipLaunchKernelGGL((k_rmsnorm_vec<T, 16>), grid, block, 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, g);
   else if (d % 4 == 0 && d <= 8192)
-    hipLaunchKernelGGL((k_rmsnorm_vec<T, 32>), grid, block, 0, s, h, p0, p1, src, gain, y, rows, d, eps, g);
+    hipLaunchKernelGGL((k_rmsnorm_vec<T, 32>), grid, block, 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, g);
   else
-    hipLaunchKernelGGL(k_rmsnorm<T>, grid, block, 0, s, h, p0, p1, src, gain, y, rows, d, eps, g);
+    hipLaunchKernelGGL(k_rmsnorm<T>, grid, block, 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, g);
 }
-void launch_rmsnorm(float* h, const float* p0, const float* p1, RowMap src, const void* gain, int dtype, void* y,
-                    int rows, int d, float eps, Gate g, hipStream_t s) {
+void launch_rmsnorm(float* h, const float* parts, int n_parts, size_t part_stride, RowMap src, const void* gain,
+                    int dtype, void* y, int rows, int d, float eps, Gate g, hipStream_t s) {
+  if (!parts) n_parts = 0;
   if (dtype == L2PD_FP32)
-    launch_rmsnorm_t<float>(h, p0, p1, src, (const float*)gain, (float*)y, rows, d, eps, g, s);
+    launch_rmsnorm_t<float>(h, parts, n_parts, part_stride, src, (const float*)gain, (float*)y, rows, d, eps, g, s);
   else
-    launch_rmsnorm_t<bf16>(h, p0, p1, src, (const bf16*)gain, (bf16*)y, rows, d, eps, g, s);
+    launch_rmsnorm_t<bf16>(h, parts, n_parts, part_stride, src, (const bf16*)gain, (bf16*)y, rows, d, eps, g, s);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Finishing kernels of the few-row ("skinny") GEMM path: the GEMM leaves fp32 partial products per
+// K range; these sum them in ascending range order and apply what the wide path fuses into its
+// GEMM epilogues.  Rows are few (<= 64 per launch), so this is a few hundred KB of traffic.
+__device__ __forceinline__ unsigned short bf16_bits(float f) { return __builtin_bit_cast(unsigned short, (__bf16)f); }
+
+// parts [n_parts][rows, 3d] (Q | K | V columns) -> rotated q [rows, d], K store, V^T store
+__global__ void __launch_bounds__(256) k_skinny_qkv_finish(const float* parts, int n_parts, size_t part_stride,
+                                                          int rows, QkvEpilogue e, Gate g) {
+  if (gate_skip(g)) return;
+  const int half = e.Dh / 2, per_row = 3 * e.H * half;
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  if (t >= rows * per_row) return;
+  const int row = t / per_row, rem = t % per_row;
+  const int hg = rem / half, i = rem % half;
+  const int mat = hg / e.H, head = hg % e.H;
+  const size_t col = (size_t)mat * e.d + head * e.Dh + i;
+  const float* p = parts + (size_t)row * 3 * e.d + col;
+  float x1 = 0.f, x2 = 0.f;
+  for (int z = 0; z < n_parts; ++z) {
+    x1 += p[z * part_stride];
+    x2 += p[z * part_stride + half];
+  }
+  const int b = row / e.Tq, pos = e.pos0 + row % e.Tq;
+  if (mat == 2) {
+    unsigned short* vt = reinterpret_cast<unsigned short*>(e.vtstore);
+    const size_t o = ((size_t)(b * e.H + head) * e.Dh + i) * e.Tpad + pos;
+    vt[o] = bf16_bits(x1);
+    vt[o + (size_t)half * e.Tpad] = bf16_bits(x2);
+    return;
+  }
+  const float cs = e.cos_t[(size_t)pos * half + i], sn = e.sin_t[(size_t)pos * half + i];
+  const float o1 = __fmaf_rn(x1, cs, -__fmul_rn(x2, sn)), o2 = __fmaf_rn(x2, cs, __fmul_rn(x1, sn));
+  unsigned short* dst = reinterpret_cast<unsigned short*>(mat == 0 ? e.q : e.kstore);
+  const size_t o = (mat == 0 ? (size_t)row * e.d : ((size_t)b * e.Tpad + pos) * e.d) + head * e.Dh + i;
+  dst[o] = bf16_bits(o1);
+  dst[o + half] = bf16_bits(o2);
+}
+void launch_skinny_qkv_finish(const float* parts, int n_parts, size_t part_stride, int rows, const QkvEpilogue& e,
+                              Gate g, hipStream_t s) {
+  const int n = rows * 3 * e.H * (e.Dh / 2);
+  hipLaunchKernelGGL(k_skinny_qkv_finish, dim3((n + 255) / 256), dim3(256), 0, s, parts, n_parts, part_stride, rows, e,
+                     g);
+}
+
+// parts [n_parts][rows, 2F] (gate | up columns) -> act [rows, F] = SiLU(gate) * up
+__global__ void __launch_bounds__(256) k_skinny_swiglu_finish(const float* parts, int n_parts, size_t part_stride,
+                                                             int rows, int F, bf16* act, Gate g) {
+  if (gate_skip(g)) return;
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  if (t >= rows * F) return;
+  const int row = t / F, col = t % F;
+  const float* p = parts + (size_t)row * 2 * F + col;
+  float gt = 0.f, up = 0.f;
+  for (int z = 0; z < n_parts; ++z) {
+    gt += p[z * part_stride];
+    up += p[z * part_stride + F];
+  }
+  const float v = __fmul_rn(__fmul_rn(gt, __builtin_amdgcn_rcpf(__fadd_rn(1.f, __expf(-gt)))), up);
+  reinterpret_cast<unsigned short*>(act)[t] = bf16_bits(v);
+}
+void launch_skinny_swiglu_finish(const float* parts, int n_parts, size_t part_stride, int rows, int F, bf16* act,
+                                 Gate g, hipStream_t s) {
+  const int n = rows * F;
+  hipLaunchKernelGGL(k_skinny_swiglu_finish, dim3((n + 255) / 256), dim3(256), 0, s, parts, n_parts, part_stride, rows,
+                     F, act, g);
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -25,7 +25,7 @@ struct Carver {
 
 struct Layout {
   // offsets into the workspace
-  size_t cos_t, sin_t, ctl, state, X, h, xn, q, attn, act, part0, part1, kstore, vstore, tmp_k, tmp_v, gate_up,
+  size_t cos_t, sin_t, ctl, state, X, h, xn, q, attn, act, parts, kstore, vstore, tmp_k, tmp_v, gate_up,
       xn_head, logits, part_max, part_sum, part_idx, conf, pred, total;
   size_t kv_layer_stride_k, kv_layer_stride_v;
   int Tpad, n_part, lm_chunk;
@@ -55,6 +55,7 @@ struct l2pd_ctx {
   std::vector<ProfileEv> prof_pool;
   int last_hip_error = 0;
   int pend_splits = 0;   // bf16: split-K partials of the last down projection still to be folded into h
+  size_t pend_stride = 0;
 
   template <typename T>
   T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
@@ -117,8 +118,17 @@ Layout make_layout(const l2pd_model_desc& m, int max_batch, int max_seq, int cac
     L.gate_up = c.take(rows * F * 4 * 2);
     L.logits = c.take(head_rows * V * 4);
   } else {
-    L.part0 = c.take(rows * d * 4);
-    L.part1 = c.take(rows * d * 4);
+    // fp32 split-K partials: two [rows, d] buffers on the wide path; on the few-row path up to
+    // kSkinnyRows rows of every K range of the widest stacked projection
+    size_t skinny = 0;
+    const int shapes[4][2] = {{3 * m.d_model, m.d_model}, {m.d_model, m.d_model}, {2 * m.d_ffn, m.d_model},
+                              {m.d_model, m.d_ffn}};
+    for (auto& sh : shapes) {
+      const size_t b = (size_t)skinny_splits(sh[0], sh[1]) * kSkinnyRows * sh[0] * 4;
+      if (b > skinny) skinny = b;
+    }
+    const size_t wide = 2 * rows * d * 4;
+    L.parts = c.take(wide > skinny ? wide : skinny);
   }
   L.xn_head = c.take(rows * d * es);   // l2pd_forward may ask for every row
   L.part_max = c.take(head_rows * L.n_part * 4);
@@ -194,6 +204,7 @@ void run_layers(l2pd_ctx* c, const Pass& p, Gate g, hipStream_t s) {
   const float* sin_t = c->at<float>(L.sin_t);
   bool pending = false;   // bf16: split-K partials of the previous projection not yet folded into h
   int pend_splits = 0;
+  size_t pend_stride = 0;
   for (int l = 0; l < m.n_layers; ++l) {
     const size_t kvo_k = p.per_layer_kv ? L.kv_layer_stride_k * l : 0;
     const size_t kvo_v = p.per_layer_kv ? L.kv_layer_stride_v * l : 0;
@@ -203,7 +214,7 @@ void run_layers(l2pd_ctx* c, const Pass& p, Gate g, hipStream_t s) {
       float* ks = reinterpret_cast<float*>(c->ws + L.kstore + kvo_k);
       float* vs = reinterpret_cast<float*>(c->ws + L.vstore + kvo_v);
       { Timed t(c, L2PD_K_NORM, s);
-        launch_rmsnorm(h, nullptr, nullptr, ident, c->attn_g[l], m.dtype, xn, rows, d, m.rms_eps, g, s); }
+        launch_rmsnorm(h, nullptr, 0, 0, ident, c->attn_g[l], m.dtype, xn, rows, d, m.rms_eps, g, s); }
       { Timed t(c, L2PD_K_GEMM_QKV, s);
         launch_gemm_f32(xn, (const float*)c->wq[l], q, rows, d, d, 0, g, s);
         launch_gemm_f32(xn, (const float*)c->wk[l], c->at<float>(L.tmp_k), rows, d, d, 0, g, s);
@@ -216,7 +227,7 @@ void run_layers(l2pd_ctx* c, const Pass& p, Gate g, hipStream_t s) {
       { Timed t(c, L2PD_K_GEMM_O, s);
         launch_gemm_f32(c->at<float>(L.attn), (const float*)c->wo[l], h, rows, d, d, 1, g, s); }
       { Timed t(c, L2PD_K_NORM, s);
-        launch_rmsnorm(h, nullptr, nullptr, ident, c->ffn_g[l], m.dtype, xn, rows, d, m.rms_eps, g, s); }
+        launch_rmsnorm(h, nullptr, 0, 0, ident, c->ffn_g[l], m.dtype, xn, rows, d, m.rms_eps, g, s); }
       float* gt = c->at<float>(L.gate_up);
       float* up = gt + (size_t)rows * F;
       { Timed t(c, L2PD_K_GEMM_GATEUP, s);
@@ -230,39 +241,67 @@ void run_layers(l2pd_ctx* c, const Pass& p, Gate g, hipStream_t s) {
       bf16* q = c->at<bf16>(L.q);
       bf16* ks = reinterpret_cast<bf16*>(c->ws + L.kstore + kvo_k);
       bf16* vts = reinterpret_cast<bf16*>(c->ws + L.vstore + kvo_v);
-      float* p0 = c->at<float>(L.part0);
-      float* p1 = c->at<float>(L.part1);
+      float* parts = c->at<float>(L.parts);
+      const bool skinny = rows <= kSkinnyRows;
       { Timed t(c, L2PD_K_NORM, s);
-        launch_rmsnorm(h, pending ? p0 : nullptr, (pending && pend_splits > 1) ? p1 : nullptr, ident, c->attn_g[l],
-                       m.dtype, xn, rows, d, m.rms_eps, g, s); }
+        launch_rmsnorm(h, pending ? parts : nullptr, pend_splits, pend_stride, ident, c->attn_g[l], m.dtype, xn, rows,
+                       d, m.rms_eps, g, s); }
       pending = false;
       QkvEpilogue e = {q, ks, vts, cos_t, sin_t, p.Tq, p.pos0, L.Tpad, H, Dh, d};
       { Timed t(c, L2PD_K_GEMM_QKV, s);
-        launch_gemm_qkv_bf16(xn, (const bf16*)c->wq[l], (const bf16*)c->wk[l], (const bf16*)c->wv[l], rows, d, e, g,
-                             s); }
+        if (skinny) {
+          const int S = skinny_splits(3 * d, d);
+          const size_t stride = (size_t)rows * 3 * d;
+          launch_gemm_skinny_bf16(xn, (const bf16*)c->wq[l], (const bf16*)c->wk[l], (const bf16*)c->wv[l], d, parts,
+                                  stride, rows, 3 * d, d, S, g, s);
+          launch_skinny_qkv_finish(parts, S, stride, rows, e, g, s);
+        } else {
+          launch_gemm_qkv_bf16(xn, (const bf16*)c->wq[l], (const bf16*)c->wk[l], (const bf16*)c->wv[l], rows, d, e, g,
+                               s);
+        } }
       if (p.kv_only_last && l + 1 == m.n_layers) break;
       bf16* ao = c->at<bf16>(L.attn);
       { Timed t(c, L2PD_K_ATTN, s);
         launch_attn_bf16(q, ks, vts, ao, p.B, p.Tq, p.Tk, L.Tpad, H, Dh, g, s); }
-      // Few row tiles leave half of the CUs idle on the [d, d] and [d, F] projections: split K in two.
+      // Few row tiles leave half of the CUs idle on the [d, d] and [d, F] projections: split K in two
+      // (wide path), or as far as skinny_splits says (few-row path).
       const int tiles = ((rows + 127) / 128) * (d / 128);
-      int so = (tiles < 256 && (d / 64) % 2 == 0) ? 2 : 1;
-      int sd = (tiles < 256 && (F / 64) % 2 == 0) ? 2 : 1;
+      const int so = skinny ? skinny_splits(d, d) : ((tiles < 256 && (d / 64) % 2 == 0) ? 2 : 1);
+      const int sd = skinny ? skinny_splits(d, F) : ((tiles < 256 && (F / 64) % 2 == 0) ? 2 : 1);
+      const size_t stride_d = (size_t)rows * d;
       { Timed t(c, L2PD_K_GEMM_O, s);
-        launch_gemm_partial_bf16(ao, (const bf16*)c->wo[l], p0, p1, rows, d, d, so, g, s); }
+        if (skinny)
+          launch_gemm_skinny_bf16(ao, (const bf16*)c->wo[l], nullptr, nullptr, 0, parts, stride_d, rows, d, d, so, g,
+                                  s);
+        else
+          launch_gemm_partial_bf16(ao, (const bf16*)c->wo[l], parts, stride_d, rows, d, d, so, g, s); }
       { Timed t(c, L2PD_K_NORM, s);
-        launch_rmsnorm(h, p0, so > 1 ? p1 : nullptr, ident, c->ffn_g[l], m.dtype, xn, rows, d, m.rms_eps, g, s); }
+        launch_rmsnorm(h, parts, so, stride_d, ident, c->ffn_g[l], m.dtype, xn, rows, d, m.rms_eps, g, s); }
       bf16* act = c->at<bf16>(L.act);
       { Timed t(c, L2PD_K_GEMM_GATEUP, s);
-        launch_gemm_swiglu_bf16(xn, (const bf16*)c->wg[l], (const bf16*)c->wu[l], act, rows, F, d, g, s); }
+        if (skinny) {
+          const int S = skinny_splits(2 * F, d);
+          const size_t stride = (size_t)rows * 2 * F;
+          launch_gemm_skinny_bf16(xn, (const bf16*)c->wg[l], (const bf16*)c->wu[l], nullptr, F, parts, stride, rows,
+                                  2 * F, d, S, g, s);
+          launch_skinny_swiglu_finish(parts, S, stride, rows, F, act, g, s);
+        } else {
+          launch_gemm_swiglu_bf16(xn, (const bf16*)c->wg[l], (const bf16*)c->wu[l], act, rows, F, d, g, s);
+        } }
       { Timed t(c, L2PD_K_GEMM_DOWN, s);
-        launch_gemm_partial_bf16(act, (const bf16*)c->wd[l], p0, p1, rows, d, F, sd, g, s); }
+        if (skinny)
+          launch_gemm_skinny_bf16(act, (const bf16*)c->wd[l], nullptr, nullptr, 0, parts, stride_d, rows, d, F, sd, g,
+                                  s);
+        else
+          launch_gemm_partial_bf16(act, (const bf16*)c->wd[l], parts, stride_d, rows, d, F, sd, g, s); }
       pending = true;
       pend_splits = sd;
+      pend_stride = stride_d;
     }
   }
   // bf16: the last down projection's partials are folded in by the final norm (see run_head)
   c->pend_splits = pending ? pend_splits : 0;
+  c->pend_stride = pend_stride;
 }
 
 // Final RMSNorm of the selected rows + LM head.  Produces the vocabulary partials (and optionally
@@ -276,7 +315,7 @@ void run_head(l2pd_ctx* c, int B, int n_rows_per_seq, RowMap src, float* logits_
   if (m.dtype == L2PD_FP32) {
     float* xh = c->at<float>(L.xn_head);
     { Timed t(c, L2PD_K_NORM, s);
-      launch_rmsnorm(h, nullptr, nullptr, src, c->final_g, m.dtype, xh, hr, d, m.rms_eps, g, s); }
+      launch_rmsnorm(h, nullptr, 0, 0, src, c->final_g, m.dtype, xh, hr, d, m.rms_eps, g, s); }
     float* lg = logits_out ? logits_out : c->at<float>(L.logits);
     Timed t(c, L2PD_K_LMHEAD, s);
     launch_gemm_f32(xh, (const float*)c->lm_head, lg, hr, V, d, 0, g, s);
@@ -288,8 +327,8 @@ void run_head(l2pd_ctx* c, int B, int n_rows_per_seq, RowMap src, float* logits_
     bf16* xh = c->at<bf16>(L.xn_head);
     const int sd = c->pend_splits;
     { Timed t(c, L2PD_K_NORM, s);
-      launch_rmsnorm(h, sd > 0 ? c->at<float>(L.part0) : nullptr, sd > 1 ? c->at<float>(L.part1) : nullptr, src,
-                     c->final_g, m.dtype, xh, hr, d, m.rms_eps, g, s); }
+      launch_rmsnorm(h, sd > 0 ? c->at<float>(L.parts) : nullptr, sd, c->pend_stride, src, c->final_g, m.dtype, xh, hr,
+                     d, m.rms_eps, g, s); }
     LmHeadEpilogue e = {};
     e.logits = logits_out;
     if (want_parts) {

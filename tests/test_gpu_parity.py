@@ -209,27 +209,29 @@ def test_dual_cache_fp32_matches_oracle():
 
 
 # ------------------------------------------------------------------------------------------ decode, bf16
-def test_bf16_dual_cache_and_eotp():
-    w = small_bf16("bf_dc", 2, 256, 2, 128, 320, 1500, 3, 33, 192, 64, hidden=32, tau=0.8, eotp=True,
-                   dual_cache=True, bias_from=70, bias_value=30.0)
+@pytest.mark.parametrize("B,s,dual", [(3, 64, True), (1, 64, True), (1, 32, True), (2, 32, False), (1, 32, False)])
+def test_bf16_kv_cache_and_eotp(B, s, dual):
+    # B * s rows per step: 192 rows take the wide GEMM path, 64 and 32 rows the few-row path (both tile heights)
+    w = small_bf16("bf_kv", 2, 256, 2, 128, 320, 1500, B, 33, 192, s, hidden=32, tau=0.8, eotp=True,
+                   dual_cache=dual, prefix_cache=not dual, bias_from=70, bias_value=60.0)
     eng, ora, flt, prompt = build(w, lm_head_scale=25.0)
     fdev = {k: v.cuda() for k, v in flt.items()}
     cfg = Pz.cfg_for(w)
     traces, outs = [], []
-    for b in range(3):
+    for b in range(B):
         tr = []
         outs.append(Pz.oracle_generate(ora, prompt[b].numpy(), w, Pz.np_filter(flt), tr))
         traces.append(tr)
-        assert outs[b][2] == 128          # EOS bias from position 70: stop after block 1 of 3
+        assert outs[b][2] == (128 if s == 64 else 96)     # EOS forced from position 70: stop after the block holding it
     rep = Pz.StepReport()
     same = Pz.teacher_forced(eng, traces, w.prompt_len, cfg, fdev, w.model, w.threshold, rep)
-    print("bf16 dual-cache teacher-forced:", rep)
+    print(f"bf16 {'dual' if dual else 'prefix'}-cache B={B} s={s} teacher-forced:", rep)
     assert rep.max_logit_err < 2e-2
     tok, st, dl = eng.generate(prompt.cuda(), fdev, Pz.cfg_for(w))
-    assert dl.tolist() == [128, 128, 128]
-    assert np.all(tok.cpu().numpy()[:, 128:] == w.model.mask_id)
+    assert dl.tolist() == [outs[0][2]] * B
+    assert np.all(tok.cpu().numpy()[:, outs[0][2]:] == w.model.mask_id)
     if same:
-        for b in range(3):
+        for b in range(B):
             np.testing.assert_array_equal(tok.cpu().numpy()[b], outs[b][0])
             assert int(st[b]) == outs[b][1]
 
