@@ -32,7 +32,8 @@ __device__ __forceinline__ unsigned int pack_bf16x2(float lo, float hi) {   // v
 template <int DH, int NQ, int NSPL>
 __global__ void __launch_bounds__(NQ * NSPL * 64) k_attn_bf16(const bf16* __restrict__ q, const bf16* __restrict__ kstore,
                                                               const bf16* __restrict__ vtstore, bf16* __restrict__ out,
-                                                              int B, int Tq, int Tk, int Tpad, int H, Gate g) {
+                                                              int B, int Tq, int Tk, int Tpad, int H, int n_chunks,
+                                                              float* __restrict__ chunk_out, Gate g) {
   if (gate_skip(g)) return;
   constexpr int NW = NQ * NSPL;
   constexpr int NT = NW * 64;
@@ -53,7 +54,11 @@ __global__ void __launch_bounds__(NQ * NSPL * 64) k_attn_bf16(const bf16* __rest
   const int qg = wave % NQ, sp = wave / NQ;    // query group and key range of this wavefront
   const int b = blockIdx.z, h = blockIdx.y;
   const int d = H * DH;
-  const int q0 = blockIdx.x * (32 * NQ) + qg * 32;
+  // With n_chunks > 1 the keys are also dealt to n_chunks workgroups per query tile (few queries,
+  // many keys: one workgroup per head would leave most CUs idle); each writes its unnormalised
+  // (O^T, m, l) to chunk_out and k_attn_merge combines them.
+  const int qt = blockIdx.x / n_chunks, ch = blockIdx.x % n_chunks;
+  const int q0 = qt * (32 * NQ) + qg * 32;
   const int qrow = min(q0 + lj, Tq - 1);
 
   // Q as the B operand: lane (query lj, half hf) holds features kk*16 + hf*8 .. +7
@@ -91,12 +96,14 @@ __global__ void __launch_bounds__(NQ * NSPL * 64) k_attn_bf16(const bf16* __rest
   // is walked by NQ wavefronts (one per query group), and all ranges advance together, one tile
   // per iteration, so the dependent chain of a wavefront is `per` tiles long instead of n_tiles.
   const int n_tiles = (Tk + KT - 1) / KT;
-  const int per = (n_tiles + NSPL - 1) / NSPL;
+  const int per_chunk = (n_tiles + n_chunks - 1) / n_chunks;    // the host picks n_chunks so that no chunk is empty
+  const int wg_first = ch * per_chunk, wg_count = min(per_chunk, n_tiles - wg_first);
+  const int per = (wg_count + NSPL - 1) / NSPL;
   u32x4 rk[NSPL][KCH], rv[NSPL][VCH];
   auto gload = [&](int it) {
 #pragma unroll
     for (int x = 0; x < NSPL; ++x) {
-      const int k0 = min(x * per + it, n_tiles - 1) * KT;   // ranges that have run out re-read a valid tile
+      const int k0 = min(wg_first + x * per + it, n_tiles - 1) * KT;   // ranges that have run out re-read a valid tile
 #pragma unroll
       for (int i = 0; i < KCH; ++i) rk[x][i] = *reinterpret_cast<const u32x4*>(srcK[i] + (size_t)k0 * d);
 #pragma unroll
@@ -122,7 +129,7 @@ __global__ void __launch_bounds__(NQ * NSPL * 64) k_attn_bf16(const bf16* __rest
   float m = -INFINITY, lsum = 0.f;
   const float sc = rsqrtf((float)DH) * 1.4426950408889634f;   // softmax scale folded with log2(e)
   const int keyK = kkey(lj), keyV = (lj >> 1) & 7;   // fragment rows are lj modulo 32
-  const int my_first = sp * per, my_count = max(0, min(per, n_tiles - my_first));
+  const int my_first = wg_first + sp * per, my_count = max(0, min(per, wg_first + wg_count - my_first));
 
   gload(0);
   sstore(0);
@@ -230,6 +237,19 @@ __global__ void __launch_bounds__(NQ * NSPL * 64) k_attn_bf16(const bf16* __rest
   }
 
   const float l = lsum + __shfl_xor(lsum, 32, 64);
+  if (n_chunks > 1) {
+    if (q0 + lj < Tq) {
+      float* po = chunk_out + ((((size_t)b * H + h) * Tq + q0 + lj) * n_chunks + ch) * (DH + 2);
+#pragma unroll
+      for (int f = 0; f < FO; ++f)
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq)
+          *reinterpret_cast<float4*>(po + f * 32 + rq * 8 + hf * 4) =
+              make_float4(o[f][rq * 4 + 0], o[f][rq * 4 + 1], o[f][rq * 4 + 2], o[f][rq * 4 + 3]);
+      if (hf == 0) { po[DH] = m; po[DH + 1] = l; }
+    }
+    return;
+  }
   const float inv = 1.f / l;
   if (q0 + lj < Tq) {
     unsigned short* op = reinterpret_cast<unsigned short*>(out) + ((size_t)b * Tq + q0 + lj) * d + h * DH;
@@ -245,9 +265,37 @@ __global__ void __launch_bounds__(NQ * NSPL * 64) k_attn_bf16(const bf16* __rest
   }
 }
 
+// One thread per (sequence, head, query, 4 features): combines the key chunks in ascending order.
+template <int DH>
+__global__ void __launch_bounds__(256) k_attn_merge(const float* __restrict__ chunk_out, bf16* __restrict__ out, int B,
+                                                   int Tq, int H, int n_chunks, Gate g) {
+  if (gate_skip(g)) return;
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  const int per_q = DH / 4;
+  if (t >= B * H * Tq * per_q) return;
+  const int f4 = t % per_q, qi = (t / per_q) % Tq, h = (t / per_q / Tq) % H, b = t / per_q / Tq / H;
+  const float* p = chunk_out + ((((size_t)b * H + h) * Tq + qi) * n_chunks) * (DH + 2);
+  float M = -INFINITY;
+  for (int c = 0; c < n_chunks; ++c) M = fmaxf(M, p[c * (DH + 2) + DH]);
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  float L = 0.f;
+  for (int c = 0; c < n_chunks; ++c) {
+    const float w = __builtin_amdgcn_exp2f(p[c * (DH + 2) + DH] - M);
+    const float4 v = *reinterpret_cast<const float4*>(p + c * (DH + 2) + f4 * 4);
+    acc.x += v.x * w; acc.y += v.y * w; acc.z += v.z * w; acc.w += v.w * w;
+    L += p[c * (DH + 2) + DH + 1] * w;
+  }
+  const float inv = 1.f / L;
+  u32x2 w2;
+  w2.x = pack_bf16x2(acc.x * inv, acc.y * inv);
+  w2.y = pack_bf16x2(acc.z * inv, acc.w * inv);
+  unsigned short* op = reinterpret_cast<unsigned short*>(out) + ((size_t)b * Tq + qi) * (H * DH) + h * DH + f4 * 4;
+  *reinterpret_cast<u32x2*>(op) = w2;
+}
+
 template <int DH, int NQ, int NSPL>
 static void launch(const bf16* q, const bf16* kstore, const bf16* vtstore, bf16* out, int B, int Tq, int Tk,
-                   int Tpad, int H, Gate g, hipStream_t s) {
+                   int Tpad, int H, float* chunk_ws, size_t chunk_ws_bytes, Gate g, hipStream_t s) {
   auto kern = k_attn_bf16<DH, NQ, NSPL>;
   constexpr int smem = 2 * NSPL * (64 * DH * 2 + DH * 64 * 2);
   static bool attr_done = false;
@@ -255,17 +303,34 @@ static void launch(const bf16* q, const bf16* kstore, const bf16* vtstore, bf16*
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     attr_done = true;
   }
-  dim3 grid((Tq + 32 * NQ - 1) / (32 * NQ), H, B);
-  hipLaunchKernelGGL(kern, grid, dim3(NQ * NSPL * 64), smem, s, q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, g);
+  const int q_tiles = (Tq + 32 * NQ - 1) / (32 * NQ), n_tiles = (Tk + 63) / 64;
+  // few queries against many keys: deal the key tiles to several workgroups per query tile
+  int n_chunks = 1;
+  if (chunk_ws && q_tiles * H * B < 128 && n_tiles >= 4) {
+    int want = (256 + q_tiles * H * B - 1) / (q_tiles * H * B);
+    if (want > 16) want = 16;
+    if (want > n_tiles / 2) want = n_tiles / 2;
+    const int per_chunk = (n_tiles + want - 1) / want;
+    n_chunks = (n_tiles + per_chunk - 1) / per_chunk;       // every chunk gets at least one tile
+    if ((size_t)B * H * Tq * n_chunks * (DH + 2) * 4 > chunk_ws_bytes) n_chunks = 1;
+  }
+  dim3 grid(q_tiles * n_chunks, H, B);
+  hipLaunchKernelGGL(kern, grid, dim3(NQ * NSPL * 64), smem, s, q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, n_chunks,
+                     chunk_ws, g);
+  if (n_chunks > 1) {
+    const int n = B * H * Tq * (DH / 4);
+    hipLaunchKernelGGL(k_attn_merge<DH>, dim3((n + 255) / 256), dim3(256), 0, s, chunk_ws, out, B, Tq, H, n_chunks, g);
+  }
 }
 
 // 64 queries per workgroup, keys in two ranges: with one sequence of a few hundred tokens this
 // gives a workgroup to every CU and halves the chain of dependent key tiles per wavefront.  The
-// configuration depends on the head size only, so a sequence's result does not depend on its batch.
+// configuration depends on the head size only, and the chunking across workgroups on the shape of
+// the launch, never on the data.
 void launch_attn_bf16(const bf16* q, const bf16* kstore, const bf16* vtstore, bf16* out, int B, int Tq, int Tk,
-                      int Tpad, int H, int Dh, Gate g, hipStream_t s) {
-  if (Dh == 128) launch<128, 2, 2>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, g, s);
-  else launch<64, 2, 2>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, g, s);
+                      int Tpad, int H, int Dh, float* chunk_ws, size_t chunk_ws_bytes, Gate g, hipStream_t s) {
+  if (Dh == 128) launch<128, 2, 2>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, chunk_ws, chunk_ws_bytes, g, s);
+  else launch<64, 2, 2>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, chunk_ws, chunk_ws_bytes, g, s);
 }
 
 }  // namespace l2pd

@@ -108,6 +108,7 @@ void launch_gemm_partial_bf16(const bf16* A, const bf16* W, float* parts, size_t
 // weights once; K is split until a launch has a few hundred workgroups, each K range staying a
 // multiple of the 64-wide stage.
 constexpr int kSkinnyRows = 64;
+constexpr int kSkinnyRowsAttn = 64;   // B * Tq up to which attention may chunk the keys across workgroups
 int skinny_splits(int N, int K);
 void launch_gemm_skinny_bf16(const bf16* A, const bf16* w0, const bf16* w1, const bf16* w2, int n_sub, float* parts,
                              size_t part_stride, int M, int N, int K, int splits, Gate g, hipStream_t s);
@@ -132,6 +133,8 @@ int lmhead_n_part(int V);
 void launch_gemm_lmhead_bf16(const bf16* A, const bf16* W, int M, int V, int K, const LmHeadEpilogue& e, Gate g,
                              hipStream_t s);
 void launch_attn_bf16(const bf16* q, const bf16* kstore, const bf16* vtstore, bf16* out, int B, int Tq, int Tk,
-                      int Tpad, int H, int Dh, Gate g, hipStream_t s);
+                      int Tpad, int H, int Dh, float* chunk_ws, size_t chunk_ws_bytes, Gate g, hipStream_t s);
+// bytes of chunk workspace that lets launch_attn_bf16 spread few queries' keys over workgroups
+inline size_t attn_chunk_ws_bytes(int H, int Dh) { return (size_t)kSkinnyRowsAttn * H * 16 * (Dh + 2) * 4; }
 
 }  // namespace l2pd

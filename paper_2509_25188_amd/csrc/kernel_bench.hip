@@ -1,7 +1,8 @@
 // Stand-alone timing of the library's bf16 kernels at one layer's shapes, and a probe of the MFMA
 // rate the chip sustains with different operand data.  Measurement tool; not part of libl2pd.so.
 //
-//   kernel_bench layer [rows] [d_model] [d_ffn] [heads]   per-kernel time of one transformer layer
+//   kernel_bench layer [rows] [d_model] [d_ffn] [heads] [keys]   per-kernel time of one transformer layer
+//                                                               (keys > rows: a block-only step over a K/V store)
 //   kernel_bench mfma                                     register-resident MFMA stream + shader clock
 //
 // "layer" calls the same launchers the library calls (same tile choice), on random operands that
@@ -64,8 +65,9 @@ static float time_us(F f, int iters = 300) {   // tens of milliseconds per kerne
   return ms * 1e3f / iters;
 }
 
-static int bench_layer(int rows, int d, int F, int H) {
-  const int Dh = d / H, Tpad = ((rows + 63) / 64) * 64;
+static int bench_layer(int rows, int d, int F, int H, int keys) {
+  if (keys < rows) keys = rows;
+  const int Dh = d / H, Tpad = ((keys + 63) / 64) * 64;
   if (d % 64 || F % 64 || (Dh != 64 && Dh != 128)) {
     fprintf(stderr, "unsupported shape\n");
     return 2;
@@ -135,8 +137,12 @@ static int bench_layer(int rows, int d, int F, int H) {
     t = time_us([&] { launch_gemm_qkv_bf16(xn, wq, wk, wv, rows, d, qe, g, 0); });
     line("QKV projection + RoPE + K / V^T store", t, 2.0 * rows * d * 3 * d, 0);
   }
-  t = time_us([&] { launch_attn_bf16(q, ks, vts, ao, 1, rows, rows, Tpad, H, Dh, g, 0); });
-  line("bidirectional attention (keys = rows)", t, 4.0 * rows * rows * d, 0);
+  float* aws;
+  CK(hipMalloc(&aws, attn_chunk_ws_bytes(H, Dh)));
+  t = time_us([&] { launch_attn_bf16(q, ks, vts, ao, 1, rows, keys, Tpad, H, Dh, aws, attn_chunk_ws_bytes(H, Dh), g, 0); });
+  char an[64];
+  snprintf(an, sizeof an, "bidirectional attention, %d keys", keys);
+  line(an, t, 4.0 * rows * keys * d, 0);
   if (skinny) {
     t = time_us([&] { launch_gemm_skinny_bf16(ao, wo, nullptr, nullptr, 0, parts, stride_d, rows, d, d, so, g, 0); });
     line("output projection (split-K partials)", t, 0, wb * d * d);
@@ -239,13 +245,14 @@ int main(int argc, char** argv) {
   }
   if (!strcmp(mode, "layer")) {
     const int rows = argc > 2 ? atoi(argv[2]) : 512, d = argc > 3 ? atoi(argv[3]) : 4096,
-              F = argc > 4 ? atoi(argv[4]) : 12288, H = argc > 5 ? atoi(argv[5]) : 32;
-    if (rows < 1 || rows > 65536 || d < 128 || H < 1 || d % H) {
+              F = argc > 4 ? atoi(argv[4]) : 12288, H = argc > 5 ? atoi(argv[5]) : 32,
+              keys = argc > 6 ? atoi(argv[6]) : 0;
+    if (rows < 1 || rows > 65536 || keys > 65536 || d < 128 || H < 1 || d % H) {
       fprintf(stderr, "bad shape\n");
       return 2;
     }
-    return bench_layer(rows, d, F, H);
+    return bench_layer(rows, d, F, H, keys);
   }
-  fprintf(stderr, "usage: kernel_bench layer [rows d_model d_ffn heads] | kernel_bench mfma\n");
+  fprintf(stderr, "usage: kernel_bench layer [rows d_model d_ffn heads keys] | kernel_bench mfma\n");
   return 2;
 }

@@ -25,7 +25,7 @@ struct Carver {
 
 struct Layout {
   // offsets into the workspace
-  size_t cos_t, sin_t, ctl, state, X, h, xn, q, attn, act, parts, kstore, vstore, tmp_k, tmp_v, gate_up,
+  size_t cos_t, sin_t, ctl, state, X, h, xn, q, attn, act, parts, attn_ws, attn_ws_bytes, kstore, vstore, tmp_k, tmp_v, gate_up,
       xn_head, logits, part_max, part_sum, part_idx, conf, pred, total;
   size_t kv_layer_stride_k, kv_layer_stride_v;
   int Tpad, n_part, lm_chunk;
@@ -129,6 +129,8 @@ Layout make_layout(const l2pd_model_desc& m, int max_batch, int max_seq, int cac
     }
     const size_t wide = 2 * rows * d * 4;
     L.parts = c.take(wide > skinny ? wide : skinny);
+    L.attn_ws_bytes = attn_chunk_ws_bytes(m.n_heads, m.head_dim);
+    L.attn_ws = c.take(L.attn_ws_bytes);
   }
   L.xn_head = c.take(rows * d * es);   // l2pd_forward may ask for every row
   L.part_max = c.take(head_rows * L.n_part * 4);
@@ -262,7 +264,8 @@ void run_layers(l2pd_ctx* c, const Pass& p, Gate g, hipStream_t s) {
       if (p.kv_only_last && l + 1 == m.n_layers) break;
       bf16* ao = c->at<bf16>(L.attn);
       { Timed t(c, L2PD_K_ATTN, s);
-        launch_attn_bf16(q, ks, vts, ao, p.B, p.Tq, p.Tk, L.Tpad, H, Dh, g, s); }
+        launch_attn_bf16(q, ks, vts, ao, p.B, p.Tq, p.Tk, L.Tpad, H, Dh, c->at<float>(L.attn_ws), L.attn_ws_bytes, g,
+                         s); }
       // Few row tiles leave half of the CUs idle on the [d, d] and [d, F] projections: split K in two
       // (wide path), or as far as skinny_splits says (few-row path).
       const int tiles = ((rows + 127) / 128) * (d / 128);
