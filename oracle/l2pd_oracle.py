@@ -20,6 +20,10 @@ What it states, in the paper's order and notation:
   when p_j > tau (Alg. 2);
 * End-of-Text Prediction: after a block's loop ends, stop if an end-of-text
   token is in the response (Alg. 3, Appendix A; Fig. 4 caption);
+* step-granular End-of-Text Prediction (Sec. 3.3, the text, as opposed to the
+  block-granular Alg. 3): after every step, once the response holds an
+  end-of-text token, everything after its first occurrence is discarded and
+  the next step runs on the shortened sequence;
 * the prefix KV cache variant (Sec. 4.3 names the technique only): K/V of the
   prompt and finished blocks come from a forward over that prefix alone and
   are refreshed once per block; a step recomputes only the active block;
@@ -36,7 +40,12 @@ mask id excluded from the vocabulary distribution; ties -> lowest index;
 already-committed block positions feed the filter the constant 1.0; the masked
 position with the highest confidence is always unmasked (progress guarantee);
 the end-of-text search covers the response region only; after an early stop
-the undecoded tail keeps the mask id.
+the undecoded tail keeps the mask id.  Step-granular EoTP: positions of the
+active block after the first end-of-text leave the mask set undecoded; the
+filter still takes block_len inputs and discarded positions enter as 1.0 like
+committed ones; the block's loop ends when no masked position is left up to the
+end-of-text; discarded positions come back as mask id, decoded_len counts the
+response up to and including the end-of-text.
 
 Parity pins: every function below is pinned by tests/test_oracle_*.py against
 brute-force loops, closed forms and invariants, except the whole trajectory on
@@ -314,6 +323,62 @@ def denoise_step(model, X, prompt_len, b, block_len, mask_id, flt, tau, bias=Non
         X[lo + j] = d["pre"][j]
     d["logits"] = logits
     return d
+
+
+# --------------------------------------------------------------------------- Sec. 3.3 (step-granular EoTP)
+def first_eot(X, prompt_len, eos_id):
+    """Index in X of the first end-of-text token of the response region, or None."""
+    hit = np.nonzero(np.asarray(X[prompt_len:]) == eos_id)[0]
+    return prompt_len + int(hit[0]) if len(hit) else None
+
+
+def denoise_step_shortened(model, X, t_eff, prompt_len, b, block_len, mask_id, flt, tau, bias=None):
+    """One step of block b on the shortened sequence X[0:t_eff] (X modified in place).  Only the
+    n = min(block_len, t_eff - lo) positions of the block that still exist are predicted; the filter
+    sees block_len inputs, the discarded ones as 1.0."""
+    lo = prompt_len + b * block_len
+    n = min(block_len, t_eff - lo)
+    logits = model.forward(X[:t_eff], lo, n)
+    logits = apply_bias(logits, b * block_len, bias)
+    conf, pre = conf_pre(logits, mask_id)
+    masked = np.asarray(X[lo:lo + n]) == mask_id
+    cin = np.ones(block_len, dtype=conf.dtype)
+    cin[:n] = np.where(masked, conf, conf.dtype.type(1.0))
+    p = filter_prob(cin, flt)[:n]
+    sel = masked & (p > p.dtype.type(tau))
+    if masked.any():
+        cm = np.where(masked, conf, -np.inf)
+        sel[int(np.argmax(cm))] = True
+    for j in np.nonzero(sel)[0]:
+        X[lo + j] = pre[j]
+    return dict(conf=conf, pre=pre, p=p, sel=sel, masked=masked, logits=logits, n=n)
+
+
+def generate_eotp_step(model, prompt, gen_len, block_len, mask_id, eos_id, flt, tau, bias=None, trace=None):
+    """Alg. 2 with the step-granular EoTP of Sec. 3.3 (full recompute).  Returns
+    (response[gen_len], steps, decoded_len)."""
+    assert gen_len % block_len == 0
+    P = len(prompt)
+    X = np.concatenate([np.asarray(prompt, dtype=np.int64), np.full(gen_len, mask_id, dtype=np.int64)])
+    t_eff = P + gen_len
+    steps = 0
+    for b in range(gen_len // block_len):
+        lo = P + b * block_len
+        while np.any(X[lo:min(lo + block_len, t_eff)] == mask_id):
+            before = X.copy() if trace is not None else None
+            d = denoise_step_shortened(model, X, t_eff, P, b, block_len, mask_id, flt, tau, bias)
+            steps += 1
+            if trace is not None:
+                d.update(X_before=before, block=b, t_eff=t_eff)
+                trace.append(d)
+            e = first_eot(X[:t_eff], P, eos_id)
+            if e is not None:
+                t_eff = e + 1                     # everything after the first end-of-text is discarded
+        if first_eot(X[:t_eff], P, eos_id) is not None:
+            break
+    resp = X[P:P + gen_len].copy()
+    resp[t_eff - P:] = mask_id
+    return resp, steps, t_eff - P
 
 
 # --------------------------------------------------------------------------- Alg. 2 / Alg. 3

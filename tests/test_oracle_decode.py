@@ -309,3 +309,88 @@ def test_generate_with_dual_cache_first_step_of_each_block_is_the_full_forward()
         elif np.max(np.abs(t["logits"] - ref)) > 1e-6:
             stale += 1
     assert seen == {0, 1, 2} and stale > 0
+
+
+# ----------------------------------------------------------------- Sec. 3.3: step-granular EoTP
+class LengthRecordingModel(ScriptedModel):
+    """ScriptedModel that also records the length of every sequence it is given."""
+
+    def __init__(self, table, prompt_len):
+        super().__init__(table, prompt_len)
+        self.lengths = []
+
+    def forward(self, X, lo, n):
+        self.lengths.append(len(X))
+        return super().forward(X, lo, n)
+
+
+def test_step_eotp_without_eot_equals_plain_decoding():
+    P, G, s, V = 3, 48, 16, 30
+    mask, eos = V - 1, V - 2
+    table = rand_table(G, V, 31)
+    table[:, eos] = -30.0
+    flt = pass_all_filter(s)
+    a = O.generate_eotp_step(ScriptedModel(table, P), np.arange(P), G, s, mask, eos, flt, 0.5)
+    b = O.generate(ScriptedModel(table, P), np.arange(P), G, s, mask, eos, flt, 0.5)
+    np.testing.assert_array_equal(a[0], b[0])
+    assert a[1:] == b[1:]
+
+
+def test_step_eotp_discards_after_the_first_eot_and_shortens_the_next_input():
+    # One token per step in order of confidence (tau = 1, "never" filter).  Block 1 = generation
+    # positions 16..31; end-of-text is the greedy token at 21, 24 and 27.  Confidence order inside the
+    # block is fixed by the raised logit: position 24 first, then 18, 21, 16, ... so that the
+    # truncation happens twice (first at 24, then at 21) with masked positions left before it.
+    P, G, s, V = 4, 64, 16, 12
+    mask, eos = V - 1, V - 2
+    table = np.zeros((G, V))
+    for g in range(G):
+        table[g, g % 7] = 3.0                       # greedy token, moderate confidence
+    order = [24, 18, 21, 16, 17, 19, 20, 22, 23, 25]
+    for rank, g in enumerate(order):
+        table[g, g % 7] = 0.0
+        tok = eos if g in (21, 24, 27) else g % 7
+        table[g, tok] = 12.0 - rank                  # decreasing confidence in this order
+    table[27, :] = 0.0
+    table[27, eos] = 1.0                             # would be end-of-text too, but is discarded first
+    never = dict(w1=np.zeros((2, s)), b1=np.zeros(2), w2=np.zeros((s, 2)), b2=np.full(s, -50.0))
+    m = LengthRecordingModel(table, P)
+    trace = []
+    resp, steps, dl = O.generate_eotp_step(m, np.arange(P), G, s, mask, eos, never, 1.0, trace=trace)
+    T = P + G
+    # block 0: 16 steps on the full length; block 1: step 1 commits 24 (EoT) -> length P+25;
+    # step 2 commits 18; step 3 commits 21 (EoT) -> length P+22; then 16, 17, 19, 20 remain: 4 steps
+    assert m.lengths[:17] == [T] * 17
+    assert m.lengths[17:19] == [P + 25] * 2
+    assert m.lengths[19:] == [P + 22] * 4
+    assert steps == 16 + 3 + 4 and dl == 22
+    assert resp[21] == eos and not np.any(resp[:21] == eos)
+    assert np.all(resp[22:] == mask) and not np.any(resp[:22] == mask)
+    # the rows predicted shrink with the sequence: 16, then 9 (16..24), then 6 (16..21)
+    assert [t["n"] for t in trace[16:]] == [16, 9, 9, 6, 6, 6, 6]
+    # block-granular Alg. 3 on the same table decodes the whole block and keeps positions after the EoT
+    r3, st3, dl3 = O.generate(ScriptedModel(table, P), np.arange(P), G, s, mask, eos, never, 1.0, eotp=True)
+    assert st3 == 32 and dl3 == 32
+    np.testing.assert_array_equal(r3[:22], resp[:22])
+
+
+def test_step_eotp_discarded_positions_feed_the_filter_one():
+    # A filter that passes position 0 only if the LAST input is >= 0.99: with the block shortened
+    # to one live position (the rest discarded), that input is the constant 1.0 of a discarded slot.
+    P, G, s, V = 2, 8, 4, 9
+    mask, eos = V - 1, V - 2
+    table = np.zeros((G, V))
+    table[0, 3] = 0.5                                # low confidence at generation position 0
+    table[1, eos] = 9.0                              # end-of-text, unmasked first (highest confidence)
+    table[2, 2] = 1.0
+    table[3, 1] = 1.0
+    flt = dict(w1=np.array([[0.0, 0.0, 0.0, 100.0]]), b1=np.array([-99.0]),
+               w2=np.array([[50.0], [0.0], [0.0], [0.0]]), b2=np.array([-25.0, -50.0, -50.0, -50.0]))
+    trace = []
+    resp, steps, dl = O.generate_eotp_step(ScriptedModel(table, P), np.arange(P), G, s, mask, eos, flt, 0.5,
+                                           trace=trace)
+    # step 1: input 3 is the confidence of masked position 3 (< 0.99): only the forced top-1 (the EoT at 1) goes
+    assert trace[0]["sel"].tolist() == [False, True, False, False]
+    # step 2: sequence is P+2 long, positions 2, 3 discarded and enter as 1.0 -> p_0 = sigmoid(25) > tau
+    assert trace[1]["n"] == 2 and trace[1]["p"][0] > 0.99
+    assert steps == 2 and dl == 2 and resp[1] == eos and resp[0] == 3
