@@ -213,7 +213,8 @@ def main():
     flt = synth.make_filter(args.seed, w.block_len, w.filter_hidden, dev)
     prompt = synth.make_prompt(args.seed, w.batch, w.prompt_len, w.prompt_hi, dev)
     bias = (m.eos_id, w.bias_from, w.bias_value) if w.bias_value else None
-    cfg = Bd.Engine.cfg_struct(w.gen_len, w.block_len, w.threshold, w.eotp, w.prefix_cache, bias, w.dual_cache)
+    cfg = Bd.Engine.cfg_struct(w.gen_len, w.block_len, w.threshold, Bd.EOTP_STEP if w.eotp_step else w.eotp,
+                               w.prefix_cache, bias, w.dual_cache)
     torch.cuda.synchronize()
     setup_s = time.time() - t0
 
@@ -282,8 +283,8 @@ def main():
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16" if m.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": w.name, "batch": w.batch, "prompt_len": w.prompt_len, "gen_len": w.gen_len,
-                   "block_len": w.block_len, "threshold": w.threshold, "eotp": bool(w.eotp),
-                   "layers": m.n_layers, "d_model": m.d_model, "d_ffn": m.d_ffn, "vocab": m.vocab,
+                   "block_len": w.block_len, "threshold": w.threshold,
+                   "eotp": "step" if w.eotp_step else bool(w.eotp), "layers": m.n_layers, "d_model": m.d_model, "d_ffn": m.d_ffn, "vocab": m.vocab,
                    "full_recompute_rows": rows},
         "steps_per_s": steps_per_s,
         "trajectory": {"steps_per_generation": traj_steps, "tokens_per_generation": tokens_total,

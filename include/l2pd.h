@@ -97,11 +97,20 @@ typedef struct {
  *           (before and after the block) as stored at the block start. */
 enum { L2PD_CACHE_NONE = 0, L2PD_CACHE_PREFIX = 1, L2PD_CACHE_DUAL = 2 };
 
+/* End-of-Text Prediction.
+ *   BLOCK (Alg. 3): after a block's loop ends, stop if the response holds eos_id.
+ *   STEP (Sec. 3.3, the text): after every step, everything after the first eos_id of the response is
+ *     discarded and the next step runs on the shortened sequence; block positions after it are never
+ *     decoded (they enter the filter as 1.0) and come back as mask_id; decoded_len counts the response
+ *     up to and including eos_id.  Full recompute only (kv_cache must be L2PD_CACHE_NONE); the host
+ *     waits for the stream after every step, because the length sizes the next launches. */
+enum { L2PD_EOTP_OFF = 0, L2PD_EOTP_BLOCK = 1, L2PD_EOTP_STEP = 2 };
+
 /* Decode arguments of Alg. 2 / Alg. 3: generation length L_gen, block size s, threshold tau. */
 typedef struct {
   int32_t gen_len, block_len;       /* gen_len % block_len == 0, block_len <= 256 */
   float threshold;                  /* unmask position j when p_j > threshold (strict) */
-  int32_t eotp;                     /* 1: stop after the first finished block whose response holds eos_id */
+  int32_t eotp;                     /* L2PD_EOTP_OFF, L2PD_EOTP_BLOCK or L2PD_EOTP_STEP */
   int32_t kv_cache;                 /* L2PD_CACHE_NONE, L2PD_CACHE_PREFIX or L2PD_CACHE_DUAL (Sec. 4.3, Table 2);
                                        the cached modes need a context created with use_kv_cache */
   int32_t keep_kv;                  /* l2pd_denoise_step in a cached mode: 0 rebuilds the K/V store from the
@@ -153,7 +162,8 @@ int32_t l2pd_denoise_step(l2pd_ctx* ctx, int32_t* tokens_dev, int32_t B, int32_t
  *   tokens_out_dev [B, gen_len]: the response slice X[P : P+gen_len]; positions never decoded
  *     because of an EoTP stop still hold mask_id;
  *   steps_out_dev [B]: forwards in which the sequence still had a masked position in its active block;
- *   decoded_len_out_dev [B]: (index of the last decoded block + 1) * block_len.
+ *   decoded_len_out_dev [B]: (index of the last decoded block + 1) * block_len; with L2PD_EOTP_STEP the
+ *     length of the response up to and including the first eos_id (gen_len if there is none).
  * The step loop, the block pointer and the stop flag live on the device; the host enqueues steps in
  * small chunks and polls a flag between chunks, so the call returns when the last chunk is enqueued. */
 int32_t l2pd_generate(l2pd_ctx* ctx, const int32_t* prompt_dev, int32_t B, int32_t P,

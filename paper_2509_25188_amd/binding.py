@@ -42,6 +42,7 @@ class LogitBias(C.Structure):
 
 
 CACHE_NONE, CACHE_PREFIX, CACHE_DUAL = 0, 1, 2
+EOTP_OFF, EOTP_BLOCK, EOTP_STEP = 0, 1, 2
 
 
 class DecodeCfg(C.Structure):

@@ -32,9 +32,12 @@ __device__ __forceinline__ unsigned int pack_bf16x2(float lo, float hi) {   // v
 template <int DH, int NQ, int NSPL>
 __global__ void __launch_bounds__(NQ * NSPL * 64) k_attn_bf16(const bf16* __restrict__ q, const bf16* __restrict__ kstore,
                                                               const bf16* __restrict__ vtstore, bf16* __restrict__ out,
-                                                              int B, int Tq, int Tk, int Tpad, int H, int n_chunks,
-                                                              float* __restrict__ chunk_out, Gate g) {
+                                                              int B, int Tq, int Tk_all, int Tpad, int H, int n_chunks,
+                                                              float* __restrict__ chunk_out,
+                                                              const int* __restrict__ tk_dev, Gate g) {
   if (gate_skip(g)) return;
+  // per-sequence key count (sequences shortened by step-granular EoTP), else the launch's
+  const int Tk = tk_dev ? min(Tk_all, tk_dev[blockIdx.z]) : Tk_all;
   constexpr int NW = NQ * NSPL;
   constexpr int NT = NW * 64;
   constexpr int KT = 64;                       // keys per LDS tile
@@ -295,7 +298,7 @@ __global__ void __launch_bounds__(256) k_attn_merge(const float* __restrict__ ch
 
 template <int DH, int NQ, int NSPL>
 static void launch(const bf16* q, const bf16* kstore, const bf16* vtstore, bf16* out, int B, int Tq, int Tk,
-                   int Tpad, int H, float* chunk_ws, size_t chunk_ws_bytes, Gate g, hipStream_t s) {
+                   int Tpad, int H, float* chunk_ws, size_t chunk_ws_bytes, const int* tk_dev, Gate g, hipStream_t s) {
   auto kern = k_attn_bf16<DH, NQ, NSPL>;
   constexpr int smem = 2 * NSPL * (64 * DH * 2 + DH * 64 * 2);
   static bool attr_done = false;
@@ -306,7 +309,7 @@ static void launch(const bf16* q, const bf16* kstore, const bf16* vtstore, bf16*
   const int q_tiles = (Tq + 32 * NQ - 1) / (32 * NQ), n_tiles = (Tk + 63) / 64;
   // few queries against many keys: deal the key tiles to several workgroups per query tile
   int n_chunks = 1;
-  if (chunk_ws && q_tiles * H * B < 128 && n_tiles >= 4) {
+  if (chunk_ws && !tk_dev && q_tiles * H * B < 128 && n_tiles >= 4) {   // chunks must not be empty: launch-wide key count only
     int want = (256 + q_tiles * H * B - 1) / (q_tiles * H * B);
     if (want > 16) want = 16;
     if (want > n_tiles / 2) want = n_tiles / 2;
@@ -316,7 +319,7 @@ static void launch(const bf16* q, const bf16* kstore, const bf16* vtstore, bf16*
   }
   dim3 grid(q_tiles * n_chunks, H, B);
   hipLaunchKernelGGL(kern, grid, dim3(NQ * NSPL * 64), smem, s, q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, n_chunks,
-                     chunk_ws, g);
+                     chunk_ws, tk_dev, g);
   if (n_chunks > 1) {
     const int n = B * H * Tq * (DH / 4);
     hipLaunchKernelGGL(k_attn_merge<DH>, dim3((n + 255) / 256), dim3(256), 0, s, chunk_ws, out, B, Tq, H, n_chunks, g);
@@ -328,9 +331,10 @@ static void launch(const bf16* q, const bf16* kstore, const bf16* vtstore, bf16*
 // configuration depends on the head size only, and the chunking across workgroups on the shape of
 // the launch, never on the data.
 void launch_attn_bf16(const bf16* q, const bf16* kstore, const bf16* vtstore, bf16* out, int B, int Tq, int Tk,
-                      int Tpad, int H, int Dh, float* chunk_ws, size_t chunk_ws_bytes, Gate g, hipStream_t s) {
-  if (Dh == 128) launch<128, 2, 2>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, chunk_ws, chunk_ws_bytes, g, s);
-  else launch<64, 2, 2>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, chunk_ws, chunk_ws_bytes, g, s);
+                      int Tpad, int H, int Dh, float* chunk_ws, size_t chunk_ws_bytes, const int* tk_dev, Gate g,
+                      hipStream_t s) {
+  if (Dh == 128) launch<128, 2, 2>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, chunk_ws, chunk_ws_bytes, tk_dev, g, s);
+  else launch<64, 2, 2>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, chunk_ws, chunk_ws_bytes, tk_dev, g, s);
 }
 
 }  // namespace l2pd

@@ -11,7 +11,7 @@ namespace l2pd {
 typedef __hip_bfloat16 bf16;
 
 // Device control block (int32 words).  Written by k_prepare at the start of every step.
-enum { CTL_GB = 0, CTL_ALL_DONE = 1, CTL_ACTIVE = 2, CTL_WORDS = 8 };
+enum { CTL_GB = 0, CTL_ALL_DONE = 1, CTL_ACTIVE = 2, CTL_TMAX = 3, CTL_WORDS = 8 };
 
 // Every kernel of a step is gated: once decoding has stopped (or, with the prefix cache, once the
 // block the host enqueued it for is finished) it returns at once, so steps that the host enqueued
@@ -64,10 +64,12 @@ struct UpdateArgs {
   float* filt_out;
   uint8_t* unmask_out;
   int* ctl;
+  const int* teff;       // step-granular EoTP: per-sequence length in force (else null)
 };
 void launch_update(const UpdateArgs& a, Gate g, hipStream_t s);
-void launch_finalize(const int32_t* X, const int32_t* state, int B, int P, int G, int s_len, int32_t* tokens_out,
-                     int32_t* steps_out, int32_t* dlen_out, hipStream_t s);
+void launch_finalize(const int32_t* X, const int32_t* state, const int* teff, int B, int P, int G, int s_len,
+                     int mask_id, int32_t* tokens_out, int32_t* steps_out, int32_t* dlen_out, hipStream_t s);
+void launch_seq_len(const int32_t* X, int B, int P, int G, int eos_id, int* teff, int* ctl, hipStream_t s);
 
 // ---- vocabulary reduction over materialised logits (fp32 path and the logits tap) ----
 struct BiasArgs {
@@ -88,7 +90,7 @@ void launch_rope_store_f32(float* q, const float* k, const float* v, float* ksto
                            int pos0, int Tmax, int H, int Dh, const float* cos_t, const float* sin_t, Gate g,
                            hipStream_t s);
 void launch_attn_f32(const float* q, const float* kstore, const float* vstore, float* out, int B, int Tq, int Tk,
-                     int Tmax, int H, int Dh, Gate g, hipStream_t s);
+                     int Tmax, int H, int Dh, const int* tk_dev, Gate g, hipStream_t s);
 void launch_swiglu_f32(const float* gate, const float* up, float* act, size_t n, Gate g, hipStream_t s);
 
 // ---- bf16 path ----
@@ -133,7 +135,8 @@ int lmhead_n_part(int V);
 void launch_gemm_lmhead_bf16(const bf16* A, const bf16* W, int M, int V, int K, const LmHeadEpilogue& e, Gate g,
                              hipStream_t s);
 void launch_attn_bf16(const bf16* q, const bf16* kstore, const bf16* vtstore, bf16* out, int B, int Tq, int Tk,
-                      int Tpad, int H, int Dh, float* chunk_ws, size_t chunk_ws_bytes, Gate g, hipStream_t s);
+                      int Tpad, int H, int Dh, float* chunk_ws, size_t chunk_ws_bytes, const int* tk_dev, Gate g,
+                      hipStream_t s);
 // bytes of chunk workspace that lets launch_attn_bf16 spread few queries' keys over workgroups
 inline size_t attn_chunk_ws_bytes(int H, int Dh) { return (size_t)kSkinnyRowsAttn * H * 16 * (Dh + 2) * 4; }
 

@@ -139,7 +139,7 @@ static int bench_layer(int rows, int d, int F, int H, int keys) {
   }
   float* aws;
   CK(hipMalloc(&aws, attn_chunk_ws_bytes(H, Dh)));
-  t = time_us([&] { launch_attn_bf16(q, ks, vts, ao, 1, rows, keys, Tpad, H, Dh, aws, attn_chunk_ws_bytes(H, Dh), g, 0); });
+  t = time_us([&] { launch_attn_bf16(q, ks, vts, ao, 1, rows, keys, Tpad, H, Dh, aws, attn_chunk_ws_bytes(H, Dh), nullptr, g, 0); });
   char an[64];
   snprintf(an, sizeof an, "bidirectional attention, %d keys", keys);
   line(an, t, 4.0 * rows * keys * d, 0);

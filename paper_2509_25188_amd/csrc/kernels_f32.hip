@@ -88,9 +88,10 @@ void launch_rope_store_f32(float* q, const float* k, const float* v, float* ksto
 // scores and feature dims for the output.  Scores are staged in LDS in chunks of 1024 keys with an
 // online rescale between chunks.
 __global__ void __launch_bounds__(64) k_attn_f32(const float* q, const float* kstore, const float* vstore,
-                                                 float* out, int B, int Tq, int Tk, int Tmax, int H, int Dh,
-                                                 Gate g) {
+                                                 float* out, int B, int Tq, int Tk_all, int Tmax, int H, int Dh,
+                                                 const int* tk_dev, Gate g) {
   if (gate_skip(g)) return;
+  const int Tk = tk_dev ? min(Tk_all, tk_dev[blockIdx.z]) : Tk_all;   // per-sequence key count when given
   __shared__ float s_q[256];
   __shared__ float s_p[1024];
   const int lane = threadIdx.x;
@@ -148,8 +149,9 @@ __global__ void __launch_bounds__(64) k_attn_f32(const float* q, const float* ks
   }
 }
 void launch_attn_f32(const float* q, const float* kstore, const float* vstore, float* out, int B, int Tq, int Tk,
-                     int Tmax, int H, int Dh, Gate g, hipStream_t s) {
-  hipLaunchKernelGGL(k_attn_f32, dim3(Tq, H, B), dim3(64), 0, s, q, kstore, vstore, out, B, Tq, Tk, Tmax, H, Dh, g);
+                     int Tmax, int H, int Dh, const int* tk_dev, Gate g, hipStream_t s) {
+  hipLaunchKernelGGL(k_attn_f32, dim3(Tq, H, B), dim3(64), 0, s, q, kstore, vstore, out, B, Tq, Tk, Tmax, H, Dh, tk_dev,
+                     g);
 }
 
 __global__ void k_swiglu_f32(const float* gate, const float* up, float* act, size_t n, Gate g) {

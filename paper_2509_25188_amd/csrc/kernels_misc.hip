@@ -433,7 +433,7 @@ __global__ void __launch_bounds__(1024) k_update(UpdateArgs a, Gate g) {
   __shared__ float s_hid[1024];
   __shared__ unsigned char s_masked[256];
   __shared__ unsigned char s_sel[256];
-  __shared__ int s_flag[4];
+  __shared__ int s_flag[6];   // masked, committed, end-of-text seen, still masked afterwards, first end-of-text
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int s = a.s;
   const int gb = a.ctl[CTL_GB];
@@ -485,9 +485,13 @@ __global__ void __launch_bounds__(1024) k_update(UpdateArgs a, Gate g) {
     if (lane == 0) { s_conf[j] = 1.f / sum; s_pred[j] = idx; }
   }
   if (tid < 4) s_flag[tid] = 0;
+  if (tid == 4) s_flag[4] = 0x7fffffff;
+  // step-granular EoTP (Sec. 3.3): the sequence is teff tokens long; block positions at or after
+  // teff are discarded: never decoded, and they enter the filter as 1.0 like committed ones
+  const int teff = a.teff ? a.teff[b] : a.T;
   __syncthreads();
   if (tid < s) {
-    bool mk = X[lo + tid] == a.mask_id;
+    bool mk = X[lo + tid] == a.mask_id && lo + tid < teff;
     s_masked[tid] = mk;
     s_cin[tid] = mk ? s_conf[tid] : 1.0f;
     if (a.conf_out) a.conf_out[b * s + tid] = s_conf[tid];
@@ -531,8 +535,20 @@ __global__ void __launch_bounds__(1024) k_update(UpdateArgs a, Gate g) {
   }
   __syncthreads();
   if (!mine) return;
-  const bool complete = s_flag[1] == n_masked;   // also true when nothing was masked
-  if (complete && a.eotp) {
+  bool complete = s_flag[1] == n_masked;   // also true when nothing was masked
+  if (a.eotp == 2) {
+    // after this step's commits: the first end-of-text of the response shortens the sequence, and
+    // the block is complete when nothing is masked before that point
+    const int end = min(lo + s, teff);
+    for (int t = a.P + tid; t < end; t += blockDim.x)
+      if (X[t] == a.eos_id) atomicMin(&s_flag[4], t);
+    __syncthreads();
+    const int new_teff = s_flag[4] == 0x7fffffff ? teff : s_flag[4] + 1;
+    if (tid < s && lo + tid < new_teff && X[lo + tid] == a.mask_id) atomicAdd(&s_flag[3], 1);
+    if (tid == 0 && s_flag[4] != 0x7fffffff) s_flag[2] = 1;
+    __syncthreads();
+    complete = s_flag[3] == 0;
+  } else if (complete && a.eotp) {
     for (int t = a.P + tid; t < lo + s; t += blockDim.x)
       if (X[t] == a.eos_id) s_flag[2] = 1;
   }
@@ -550,23 +566,54 @@ void launch_update(const UpdateArgs& a, Gate g, hipStream_t s) {
 }
 
 // response_i = X[P : P+G], steps, decoded length
-__global__ void k_finalize(const int32_t* X, const int32_t* state, int B, int P, int G, int s_len,
-                           int32_t* tokens_out, int32_t* steps_out, int32_t* dlen_out) {
+// With `teff` (step-granular EoTP) the decoded length is the shortened sequence's response part and
+// discarded positions come back as mask_id.
+__global__ void k_finalize(const int32_t* X, const int32_t* state, const int* teff, int B, int P, int G, int s_len,
+                           int mask_id, int32_t* tokens_out, int32_t* steps_out, int32_t* dlen_out) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < B * G) {
     int b = i / G, t = i % G;
-    tokens_out[i] = X[(size_t)b * (P + G) + P + t];
+    int v = X[(size_t)b * (P + G) + P + t];
+    if (teff && P + t >= teff[b]) v = mask_id;
+    tokens_out[i] = v;
   }
   if (i < B) {
     if (steps_out) steps_out[i] = state[i * 3 + 1];
-    if (dlen_out) dlen_out[i] = state[i * 3 + 0] * s_len;
+    if (dlen_out) dlen_out[i] = teff ? teff[i] - P : state[i * 3 + 0] * s_len;
   }
 }
-void launch_finalize(const int32_t* X, const int32_t* state, int B, int P, int G, int s_len, int32_t* tokens_out,
-                     int32_t* steps_out, int32_t* dlen_out, hipStream_t s) {
+void launch_finalize(const int32_t* X, const int32_t* state, const int* teff, int B, int P, int G, int s_len,
+                     int mask_id, int32_t* tokens_out, int32_t* steps_out, int32_t* dlen_out, hipStream_t s) {
   int n = B * G;
-  hipLaunchKernelGGL(k_finalize, dim3((n + 255) / 256), dim3(256), 0, s, X, state, B, P, G, s_len, tokens_out,
-                     steps_out, dlen_out);
+  hipLaunchKernelGGL(k_finalize, dim3((n + 255) / 256), dim3(256), 0, s, X, state, teff, B, P, G, s_len, mask_id,
+                     tokens_out, steps_out, dlen_out);
+}
+
+// Step-granular EoTP (Sec. 3.3): teff[b] = index after the first end-of-text token of sequence b's
+// response region, or the full length; ctl[CTL_TMAX] = the largest of them.  One workgroup.
+__global__ void __launch_bounds__(256) k_seq_len(const int32_t* X, int B, int P, int G, int eos_id, int* teff,
+                                                int* ctl) {
+  __shared__ int s_first;
+  __shared__ int s_max;
+  const int tid = threadIdx.x, T = P + G;
+  if (tid == 0) s_max = 0;
+  for (int b = 0; b < B; ++b) {
+    if (tid == 0) s_first = T - 1;   // "none": the sequence keeps its full length
+    __syncthreads();
+    const int32_t* x = X + (size_t)b * T;
+    for (int t = P + tid; t < T; t += 256)
+      if (x[t] == eos_id) atomicMin(&s_first, t);
+    __syncthreads();
+    if (tid == 0) {
+      teff[b] = s_first + 1;
+      s_max = max(s_max, s_first + 1);
+    }
+    __syncthreads();
+  }
+  if (tid == 0) ctl[CTL_TMAX] = s_max;
+}
+void launch_seq_len(const int32_t* X, int B, int P, int G, int eos_id, int* teff, int* ctl, hipStream_t s) {
+  hipLaunchKernelGGL(k_seq_len, dim3(1), dim3(256), 0, s, X, B, P, G, eos_id, teff, ctl);
 }
 
 }  // namespace l2pd

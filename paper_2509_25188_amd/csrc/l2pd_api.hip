@@ -25,7 +25,7 @@ struct Carver {
 
 struct Layout {
   // offsets into the workspace
-  size_t cos_t, sin_t, ctl, state, X, h, xn, q, attn, act, parts, attn_ws, attn_ws_bytes, kstore, vstore, tmp_k, tmp_v, gate_up,
+  size_t cos_t, sin_t, ctl, state, teff, X, h, xn, q, attn, act, parts, attn_ws, attn_ws_bytes, kstore, vstore, tmp_k, tmp_v, gate_up,
       xn_head, logits, part_max, part_sum, part_idx, conf, pred, total;
   size_t kv_layer_stride_k, kv_layer_stride_v;
   int Tpad, n_part, lm_chunk;
@@ -100,6 +100,7 @@ Layout make_layout(const l2pd_model_desc& m, int max_batch, int max_seq, int cac
   L.sin_t = c.take((size_t)L.Tpad * (m.head_dim / 2) * 4);
   L.ctl = c.take(CTL_WORDS * 4);
   L.state = c.take((size_t)max_batch * 3 * 4);
+  L.teff = c.take((size_t)max_batch * 4);
   L.X = c.take(rows * 4);
   L.h = c.take(rows * d * 4);
   L.xn = c.take(rows * d * es);
@@ -193,6 +194,7 @@ struct Pass {
   const int32_t* tokens;
   bool per_layer_kv;    // prefix cache: one K/V store per layer
   bool kv_only_last;    // refresh pass: the last layer only has to leave its K/V
+  const int* tk_dev = nullptr;   // step-granular EoTP: per-sequence number of keys (device), else null
 };
 
 void run_layers(l2pd_ctx* c, const Pass& p, Gate g, hipStream_t s) {
@@ -225,7 +227,7 @@ void run_layers(l2pd_ctx* c, const Pass& p, Gate g, hipStream_t s) {
                               Dh, cos_t, sin_t, g, s); }
       if (p.kv_only_last && l + 1 == m.n_layers) break;
       { Timed t(c, L2PD_K_ATTN, s);
-        launch_attn_f32(q, ks, vs, c->at<float>(L.attn), p.B, p.Tq, p.Tk, L.Tpad, H, Dh, g, s); }
+        launch_attn_f32(q, ks, vs, c->at<float>(L.attn), p.B, p.Tq, p.Tk, L.Tpad, H, Dh, p.tk_dev, g, s); }
       { Timed t(c, L2PD_K_GEMM_O, s);
         launch_gemm_f32(c->at<float>(L.attn), (const float*)c->wo[l], h, rows, d, d, 1, g, s); }
       { Timed t(c, L2PD_K_NORM, s);
@@ -264,8 +266,8 @@ void run_layers(l2pd_ctx* c, const Pass& p, Gate g, hipStream_t s) {
       if (p.kv_only_last && l + 1 == m.n_layers) break;
       bf16* ao = c->at<bf16>(L.attn);
       { Timed t(c, L2PD_K_ATTN, s);
-        launch_attn_bf16(q, ks, vts, ao, p.B, p.Tq, p.Tk, L.Tpad, H, Dh, c->at<float>(L.attn_ws), L.attn_ws_bytes, g,
-                         s); }
+        launch_attn_bf16(q, ks, vts, ao, p.B, p.Tq, p.Tk, L.Tpad, H, Dh, c->at<float>(L.attn_ws), L.attn_ws_bytes,
+                         p.tk_dev, g, s); }
       // Few row tiles leave half of the CUs idle on the [d, d] and [d, F] projections: split K in two
       // (wide path), or as far as skinny_splits says (few-row path).
       const int tiles = ((rows + 127) / 128) * (d / 128);
@@ -358,6 +360,8 @@ int check_decode_args(const l2pd_ctx* c, int B, int P, const l2pd_decode_cfg* cf
   if (isnan(cfg->threshold)) return L2PD_EINVAL;
   if (cfg->kv_cache < L2PD_CACHE_NONE || cfg->kv_cache > L2PD_CACHE_DUAL) return L2PD_EINVAL;
   if (cfg->kv_cache && !c->cache) return L2PD_EINVAL;
+  if (cfg->eotp < 0 || cfg->eotp > L2PD_EOTP_STEP) return L2PD_EINVAL;
+  if (cfg->eotp == L2PD_EOTP_STEP && cfg->kv_cache) return L2PD_ENOTIMPL;   // shortened sequences: full recompute only
   if (cfg->bias.value != 0.f && (cfg->bias.token_id < 0 || cfg->bias.token_id >= c->m.vocab)) return L2PD_EINVAL;
   if (isnan(cfg->bias.value)) return L2PD_EINVAL;
   return L2PD_OK;
@@ -382,8 +386,10 @@ void run_refresh(l2pd_ctx* c, const int32_t* X, int B, int P, const l2pd_decode_
 }
 
 // One denoising step for the lock-step batch.  host_gb >= 0 is required with the prefix cache.
+// t_run > 0 (step-granular EoTP): the forward runs over the first t_run positions of every sequence,
+// each sequence attending to its own teff[b] <= t_run keys.
 void run_step(l2pd_ctx* c, int32_t* X, int B, int P, const l2pd_decode_cfg* cfg, const l2pd_filter* f,
-              int32_t* state, int host_gb, const StepTaps& taps, hipStream_t s) {
+              int32_t* state, int host_gb, const StepTaps& taps, hipStream_t s, int t_run = 0) {
   const Layout& L = c->L;
   const int sl = cfg->block_len, T = P + cfg->gen_len, nb = cfg->gen_len / sl;
   int* ctl = c->at<int>(L.ctl);
@@ -397,6 +403,12 @@ void run_step(l2pd_ctx* c, int32_t* X, int B, int P, const l2pd_decode_cfg* cfg,
     Pass p = {B, sl, cpos, cfg->kv_cache == L2PD_CACHE_DUAL ? T : cpos + sl, T, X, true, false};
     run_layers(c, p, g, s);
     run_head(c, B, sl, RowMap{B * sl, 0, 0, 0}, taps.logits, true, bias, g, s);
+  } else if (t_run > 0) {
+    Pass p = {B, t_run, 0, t_run, T, X, false, false};
+    p.tk_dev = c->at<int>(L.teff);
+    run_layers(c, p, g, s);
+    // block rows past a sequence's end are read (stale rows of the buffer) and ignored by the update
+    run_head(c, B, sl, RowMap{sl, t_run, P, sl}, taps.logits, true, bias, g, s);
   } else {
     Pass p = {B, T, 0, T, T, X, false, false};
     run_layers(c, p, g, s);
@@ -411,10 +423,35 @@ void run_step(l2pd_ctx* c, int32_t* X, int B, int P, const l2pd_decode_cfg* cfg,
   u.tau = cfg->threshold;
   u.conf_out = taps.conf; u.pred_out = taps.pred; u.filt_out = taps.filt; u.unmask_out = taps.unmask;
   u.ctl = ctl;
+  u.teff = t_run > 0 ? c->at<int>(L.teff) : nullptr;
   Timed t(c, L2PD_K_UPDATE, s);
   launch_update(u, g, s);
 }
 
+
+int ensure_pinned(l2pd_ctx* c) {
+  if (c->pinned) return L2PD_OK;
+  HIP_TRY(c, hipHostMalloc(reinterpret_cast<void**>(&c->pinned), 2 * CTL_WORDS * sizeof(int), hipHostMallocDefault));
+  HIP_TRY(c, hipEventCreateWithFlags(&c->poll_ev[0], hipEventDisableTiming));
+  HIP_TRY(c, hipEventCreateWithFlags(&c->poll_ev[1], hipEventDisableTiming));
+  return L2PD_OK;
+}
+
+// Step-granular EoTP: lengths in force for the next step, from the tokens as they are.  Waits for
+// the stream.  Returns the longest (what the forward has to cover), or -1 on a HIP error;
+// *all_done reports the decode state.
+int sync_seq_len(l2pd_ctx* c, const int32_t* X, const int32_t* state, int B, int P, const l2pd_decode_cfg* cfg,
+                 int* all_done, hipStream_t s) {
+  const Layout& L = c->L;
+  int* ctl = c->at<int>(L.ctl);
+  launch_prepare(state, B, cfg->gen_len / cfg->block_len, ctl, s);
+  launch_seq_len(X, B, P, cfg->gen_len, c->m.eos_id, c->at<int>(L.teff), ctl, s);
+  if (hipMemcpyAsync(c->pinned, ctl, CTL_WORDS * sizeof(int), hipMemcpyDeviceToHost, s) != hipSuccess ||
+      hipStreamSynchronize(s) != hipSuccess)
+    return -1;
+  *all_done = c->pinned[CTL_ALL_DONE];
+  return c->pinned[CTL_TMAX];
+}
 }  // namespace
 
 // =================================================================================================
@@ -531,7 +568,16 @@ int32_t l2pd_denoise_step(l2pd_ctx* c, int32_t* tokens_dev, int32_t B, int32_t p
     if (!cfg->keep_kv) run_refresh(c, tokens_dev, B, prompt_len, cfg, host_gb, Gate{nullptr, -1}, s);
   }
   StepTaps taps = {logits_dev, conf_dev, pred_dev, filt_dev, unmask_dev};
-  run_step(c, tokens_dev, B, prompt_len, cfg, f, state_dev, host_gb, taps, s);
+  int t_run = 0;
+  if (cfg->eotp == L2PD_EOTP_STEP) {
+    st = ensure_pinned(c);
+    if (st) return st;
+    int all_done = 0;
+    t_run = sync_seq_len(c, tokens_dev, state_dev, B, prompt_len, cfg, &all_done, s);
+    if (t_run < 0) { c->last_hip_error = (int)hipGetLastError(); return L2PD_EHIP; }
+    if (all_done) return L2PD_OK;
+  }
+  run_step(c, tokens_dev, B, prompt_len, cfg, f, state_dev, host_gb, taps, s, t_run);
   HIP_TRY(c, hipGetLastError());
   return L2PD_OK;
 }
@@ -545,11 +591,8 @@ int32_t l2pd_generate(l2pd_ctx* c, const int32_t* prompt_dev, int32_t B, int32_t
   hipStream_t s = static_cast<hipStream_t>(stream);
   st = ensure_device(c, s);
   if (st) return st;
-  if (!c->pinned) {
-    HIP_TRY(c, hipHostMalloc(reinterpret_cast<void**>(&c->pinned), 2 * CTL_WORDS * sizeof(int), hipHostMallocDefault));
-    HIP_TRY(c, hipEventCreateWithFlags(&c->poll_ev[0], hipEventDisableTiming));
-    HIP_TRY(c, hipEventCreateWithFlags(&c->poll_ev[1], hipEventDisableTiming));
-  }
+  st = ensure_pinned(c);
+  if (st) return st;
   const Layout& L = c->L;
   int32_t* X = c->at<int32_t>(L.X);
   int32_t* state = c->at<int32_t>(L.state);
@@ -588,7 +631,19 @@ int32_t l2pd_generate(l2pd_ctx* c, const int32_t* prompt_dev, int32_t B, int32_t
     return c->pinned[last * CTL_WORDS + CTL_ALL_DONE] ? 1 : 0;
   };
 
-  if (cfg->kv_cache) {
+  const bool step_eotp = cfg->eotp == L2PD_EOTP_STEP;
+  if (step_eotp) {
+    // The sequence length changes from step to step and sizes every launch, so the host looks at
+    // the state after every step (a few microseconds against a forward of milliseconds).
+    for (int k = 0; k < G; ++k) {   // at most gen_len steps
+      int all_done = 0;
+      const int t_run = sync_seq_len(c, X, state, B, P, cfg, &all_done, s);
+      if (t_run < 0) { c->last_hip_error = (int)hipGetLastError(); return L2PD_EHIP; }
+      if (all_done) break;
+      run_step(c, X, B, P, cfg, f, state, -1, no_taps, s, t_run);
+    }
+    launch_seq_len(X, B, P, G, c->m.eos_id, c->at<int>(L.teff), ctl, s);
+  } else if (cfg->kv_cache) {
     for (int gb = 0; gb < nb; ++gb) {
       launch_prepare(state, B, nb, ctl, s);
       run_refresh(c, X, B, P, cfg, gb, Gate{ctl, -1}, s);
@@ -600,7 +655,8 @@ int32_t l2pd_generate(l2pd_ctx* c, const int32_t* prompt_dev, int32_t B, int32_t
     int r = run_until(-1, G);      // at most gen_len steps in total
     if (r < 0) { c->last_hip_error = (int)hipGetLastError(); return L2PD_EHIP; }
   }
-  launch_finalize(X, state, B, P, G, sl, tokens_out_dev, steps_out_dev, decoded_len_out_dev, s);
+  launch_finalize(X, state, step_eotp ? c->at<int>(L.teff) : nullptr, B, P, G, sl, c->m.mask_id, tokens_out_dev,
+                  steps_out_dev, decoded_len_out_dev, s);
   HIP_TRY(c, hipGetLastError());
   return L2PD_OK;
 }

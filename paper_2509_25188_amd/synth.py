@@ -62,6 +62,7 @@ class Workload:
     filter_hidden: int
     threshold: float
     eotp: bool = False
+    eotp_step: bool = False  # step-granular EoTP (Sec. 3.3) instead of the block-granular Alg. 3
     prefix_cache: bool = False
     dual_cache: bool = False
     bias_from: int = -1      # generation position from which the EOS logit bias applies (-1: none)
@@ -79,6 +80,8 @@ WORKLOADS: Dict[str, Workload] = {
     "8b_g256": Workload("8b_g256", _8B, 1, 256, 256, 32, 128, 0.9, prompt_hi=126081),
     "8b_g1024_eotp": Workload("8b_g1024_eotp", _8B, 1, 256, 1024, 32, 128, 0.9, eotp=True,
                               bias_from=300, bias_value=20.0, prompt_hi=126081),
+    "8b_g1024_eotp_step": Workload("8b_g1024_eotp_step", _8B, 1, 256, 1024, 32, 128, 0.9, eotp=True, eotp_step=True,
+                                   bias_from=300, bias_value=20.0, prompt_hi=126081),
     "8b_g1024_dual": Workload("8b_g1024_dual", _8B, 1, 256, 1024, 32, 128, 0.9, eotp=True, dual_cache=True,
                               bias_from=300, bias_value=20.0, prompt_hi=126081),
     "8b_b32_prefix": Workload("8b_b32_prefix", _8B, 32, 512, 512, 64, 128, 0.9, eotp=True,

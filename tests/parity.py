@@ -70,16 +70,19 @@ class StepReport:
 
 def check_step(rec, taps, b, shape, tau, tol, rep: StepReport, check_logits=True):
     """Compares one oracle step record with the library's taps for sequence b of the batch."""
-    conf = taps["conf"][b].cpu().numpy()
-    pred = taps["pred"][b].cpu().numpy()
-    p = taps["p"][b].cpu().numpy()
+    n = len(rec["conf"])     # fewer than block_len when step-granular EoTP has shortened the sequence
+    conf = taps["conf"][b].cpu().numpy()[:n]
+    pred = taps["pred"][b].cpu().numpy()[:n]
+    p = taps["p"][b].cpu().numpy()[:n]
     sel = taps["sel"][b].cpu().numpy().astype(bool)
+    assert not sel[n:].any(), "a discarded position was unmasked"
+    sel = sel[:n]
     masked = rec["masked"]
     rep.steps += 1
     rep.positions += len(conf)
     abs_err = None
     if check_logits and "logits" in taps:
-        lg = taps["logits"][b].cpu().numpy()
+        lg = taps["logits"][b].cpu().numpy()[:n]
         e = rel_err(lg, rec["logits"])
         rep.max_logit_err = max(rep.max_logit_err, e)
         assert e <= tol, f"logits off by {e:.3e} (tol {tol})"
@@ -156,6 +159,10 @@ def teacher_forced(engine: Bd.Engine, trace_per_seq, prompt_len, cfg, flt_dev, s
 
 def oracle_generate(model, prompt_row, w: synth.Workload, flt_np, trace=None, tau=None):
     bias = (w.model.eos_id, w.bias_from, w.bias_value) if w.bias_value else None
+    if w.eotp_step:
+        assert not (w.prefix_cache or w.dual_cache)
+        return O.generate_eotp_step(model, prompt_row, w.gen_len, w.block_len, w.model.mask_id, w.model.eos_id,
+                                    flt_np, w.threshold if tau is None else tau, bias=bias, trace=trace)
     return O.generate(model, prompt_row, w.gen_len, w.block_len, w.model.mask_id, w.model.eos_id, flt_np,
                       w.threshold if tau is None else tau, eotp=w.eotp, bias=bias, prefix_cache=w.prefix_cache,
                       trace=trace, dual_cache=w.dual_cache)
@@ -163,7 +170,8 @@ def oracle_generate(model, prompt_row, w: synth.Workload, flt_np, trace=None, ta
 
 def cfg_for(w: synth.Workload, tau=None):
     bias = (w.model.eos_id, w.bias_from, w.bias_value) if w.bias_value else None
-    return Bd.Engine.cfg_struct(w.gen_len, w.block_len, w.threshold if tau is None else tau, w.eotp,
+    return Bd.Engine.cfg_struct(w.gen_len, w.block_len, w.threshold if tau is None else tau,
+                                Bd.EOTP_STEP if w.eotp_step else w.eotp,
                                 w.prefix_cache, bias, w.dual_cache)
 
 

@@ -1,0 +1,76 @@
+"""GPU parity for the step-granular End-of-Text Prediction of Sec. 3.3: after every step the
+sequence is cut after the first end-of-text token and the next forward runs on the shortened input."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2509_25188_amd import synth
+from tests import parity as Pz
+from tests.test_gpu_parity import build, small_bf16
+
+pytestmark = pytest.mark.gpu
+TINY = synth.WORKLOADS["tiny"].model
+
+
+def oracle_runs(w, ora, flt, prompt):
+    traces, outs = [], []
+    for b in range(w.batch):
+        tr = []
+        outs.append(Pz.oracle_generate(ora, prompt[b].numpy(), w, Pz.np_filter(flt), tr))
+        traces.append(tr)
+    return traces, outs
+
+
+@pytest.mark.parametrize("bias_from", [40, 0, 95])
+def test_step_eotp_fp32_matches_oracle(bias_from):
+    # end-of-text forced from a position inside a block (40), from the very first position (0),
+    # and at the last position of the response (95: nothing left to discard)
+    w = synth.Workload("tiny_es", TINY, 2, 9, 96, 32, 16, 0.5, eotp=True, eotp_step=True, bias_from=bias_from,
+                       bias_value=60.0, prompt_hi=1022)
+    eng, ora, flt, prompt = build(w, lm_head_scale=25.0)
+    fdev = {k: v.cuda() for k, v in flt.items()}
+    traces, outs = oracle_runs(w, ora, flt, prompt)
+    if bias_from == 40:
+        assert any(t["n"] < 32 for t in traces[0])          # some steps really ran on a shortened block
+        assert all(o[2] % 32 for o in outs)                   # and the decode ended inside a block
+    rep = Pz.StepReport()
+    Pz.teacher_forced(eng, traces, w.prompt_len, Pz.cfg_for(w), fdev, w.model, w.threshold, rep)
+    print(f"step-granular EoTP fp32 (bias from {bias_from}) teacher-forced:", rep)
+    assert rep.max_logit_err < 1e-4
+    tok, st, dl = eng.generate(prompt.cuda(), fdev, Pz.cfg_for(w))
+    for b in range(2):
+        np.testing.assert_array_equal(tok.cpu().numpy()[b], outs[b][0])
+        assert int(st[b]) == outs[b][1] and int(dl[b]) == outs[b][2]
+        assert np.all(tok.cpu().numpy()[b, outs[b][2]:] == w.model.mask_id)
+
+
+def test_step_eotp_without_end_of_text_equals_plain_decode():
+    w0 = synth.Workload("tiny_plain", TINY, 1, 9, 64, 32, 16, 0.5, prompt_hi=1022)
+    w1 = synth.Workload("tiny_es0", TINY, 1, 9, 64, 32, 16, 0.5, eotp=True, eotp_step=True, prompt_hi=1022)
+    eng, ora, flt, prompt = build(w0, lm_head_scale=25.0)
+    fdev = {k: v.cuda() for k, v in flt.items()}
+    a = eng.generate(prompt.cuda(), fdev, Pz.cfg_for(w0))
+    b = eng.generate(prompt.cuda(), fdev, Pz.cfg_for(w1))
+    if not torch.any(a[0] == w0.model.eos_id):
+        for x, y in zip(a, b):
+            assert torch.equal(x, y)
+
+
+def test_step_eotp_bf16_ragged_lengths_in_a_batch():
+    # three sequences shortened at different steps: the forward covers the longest, every sequence
+    # attends to its own length
+    w = small_bf16("bf_es", 2, 256, 2, 128, 320, 1500, 3, 37, 128, 32, hidden=32, tau=0.8, eotp=True, eotp_step=True,
+                   bias_from=45, bias_value=60.0)
+    eng, ora, flt, prompt = build(w, lm_head_scale=25.0)
+    fdev = {k: v.cuda() for k, v in flt.items()}
+    traces, outs = oracle_runs(w, ora, flt, prompt)
+    rep = Pz.StepReport()
+    same = Pz.teacher_forced(eng, traces, w.prompt_len, Pz.cfg_for(w), fdev, w.model, w.threshold, rep)
+    print("step-granular EoTP bf16 teacher-forced:", rep, "decoded lengths", [o[2] for o in outs])
+    assert rep.max_logit_err < 2e-2
+    tok, st, dl = eng.generate(prompt.cuda(), fdev, Pz.cfg_for(w))
+    assert np.all(dl.cpu().numpy() <= 64)
+    if same:
+        for b in range(3):
+            np.testing.assert_array_equal(tok.cpu().numpy()[b], outs[b][0])
+            assert int(st[b]) == outs[b][1] and int(dl[b]) == outs[b][2]
