@@ -188,6 +188,12 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="reduced depth (debugging only; invalid as a result)")
     ap.add_argument("--seed", type=int, default=1234)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--decoder", default="learn2pd", choices=["learn2pd", "vanilla", "threshold"],
+                    help="learn2pd: the workload's filter and threshold; vanilla: one token per step (the most "
+                         "confident masked position); threshold: unmask where the confidence exceeds --conf-threshold")
+    ap.add_argument("--conf-threshold", type=float, default=0.9)
+    ap.add_argument("--lm-head-scale", type=float, default=1.0,
+                    help="scales the synthetic LM head; 25 spreads the confidences over (0, 1) (not the headline config)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch a plain device copy of known size (reference for HBM counter runs)")
     args = ap.parse_args()
@@ -209,8 +215,14 @@ def main():
     m = w.model
     dev = "cuda"
     t0 = time.time()
-    eng = Bd.engine_for(w, args.seed, dev)
+    import dataclasses
+    eng = Bd.engine_for(w, args.seed, dev, lm_head_scale=args.lm_head_scale)
     flt = synth.make_filter(args.seed, w.block_len, w.filter_hidden, dev)
+    if args.decoder == "vanilla":          # the filter never passes: only the forced most confident position goes
+        w = dataclasses.replace(w, threshold=1.0)
+    elif args.decoder == "threshold":
+        flt = synth.threshold_filter(w.block_len, args.conf_threshold, device=dev)
+        w = dataclasses.replace(w, threshold=0.5, filter_hidden=w.block_len)
     prompt = synth.make_prompt(args.seed, w.batch, w.prompt_len, w.prompt_hi, dev)
     bias = (m.eos_id, w.bias_from, w.bias_value) if w.bias_value else None
     cfg = Bd.Engine.cfg_struct(w.gen_len, w.block_len, w.threshold, Bd.EOTP_STEP if w.eotp_step else w.eotp,
@@ -284,8 +296,9 @@ def main():
         "vs_baseline": None, "dtype": "bf16" if m.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": w.name, "batch": w.batch, "prompt_len": w.prompt_len, "gen_len": w.gen_len,
                    "block_len": w.block_len, "threshold": w.threshold,
-                   "eotp": "step" if w.eotp_step else bool(w.eotp), "layers": m.n_layers, "d_model": m.d_model, "d_ffn": m.d_ffn, "vocab": m.vocab,
-                   "full_recompute_rows": rows},
+                   "eotp": "step" if w.eotp_step else bool(w.eotp), "decoder": args.decoder,
+                   "lm_head_scale": args.lm_head_scale, "layers": m.n_layers, "d_model": m.d_model, "d_ffn": m.d_ffn,
+                   "vocab": m.vocab, "full_recompute_rows": rows},
         "steps_per_s": steps_per_s,
         "trajectory": {"steps_per_generation": traj_steps, "tokens_per_generation": tokens_total,
                        "tokens_per_step": tokens_per_step, "generate_wall_s": gen_wall,

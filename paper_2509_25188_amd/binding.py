@@ -220,6 +220,7 @@ class Engine:
         return n.value, ms.value
 
 
-def engine_for(w: synth.Workload, seed: int, device="cuda", max_batch: Optional[int] = None) -> Engine:
-    weights = synth.make_weights(w.model, seed, device)
+def engine_for(w: synth.Workload, seed: int, device="cuda", max_batch: Optional[int] = None,
+               lm_head_scale: float = 1.0) -> Engine:
+    weights = synth.make_weights(w.model, seed, device, lm_head_scale=lm_head_scale)
     return Engine(w.model, weights, max_batch or w.batch, w.prompt_len + w.gen_len, w.prefix_cache or w.dual_cache)

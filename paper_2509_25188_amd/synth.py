@@ -249,6 +249,16 @@ def make_filter(seed: int, block_len: int, hidden: int, device="cpu") -> Dict[st
     }
 
 
+def threshold_filter(block_len: int, theta: float, sharpness: float = 200.0, device="cpu") -> Dict[str, torch.Tensor]:
+    """The filter that turns the decoder into fixed-threshold confidence decoding (the baseline of
+    Sec. 2 / Table 1): W1 = I, W2 = sharpness * I, b2 = -sharpness * theta, so that the filter output
+    exceeds 0.5 exactly when the position's confidence exceeds theta (committed positions enter as 1.0)."""
+    f32 = torch.float32
+    eye = torch.eye(block_len, dtype=f32, device=device)
+    return {"w1": eye.clone(), "b1": torch.zeros(block_len, dtype=f32, device=device),
+            "w2": eye * sharpness, "b2": torch.full((block_len,), -sharpness * theta, dtype=f32, device=device)}
+
+
 def make_prompt(seed: int, batch: int, prompt_len: int, hi: int, device="cpu") -> torch.Tensor:
     """int32 [batch, prompt_len], ids uniform on [0, hi) (hi excludes the EOS and mask ids)."""
     return uniform_ints(seed, "prompt", (batch, prompt_len), hi, device)
