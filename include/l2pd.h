@@ -178,7 +178,8 @@ enum {
 /* Selects one kernel class (L2PD_K_NONE switches timing off) and clears the counters. */
 int32_t l2pd_profile_select(l2pd_ctx* ctx, int32_t kernel_class);
 /* Synchronises the recorded events and returns the number of timed launches of the selected class
- * since the last select and the sum of their durations in milliseconds. */
+ * since the last select and the sum of their durations in milliseconds (event-pair time minus the time
+ * of an event pair with nothing inside, which is sampled on the same stream next to the timed launches). */
 int32_t l2pd_profile_read(l2pd_ctx* ctx, int64_t* launches_out, double* total_ms_out);
 
 const char* l2pd_strerror(int32_t status);

@@ -46,8 +46,10 @@ static bf16* random_bf16(size_t n, unsigned seed, float scale) {
   return d;
 }
 
+static int g_iters = 300;   // tens of milliseconds per kernel; KERNEL_BENCH_ITERS overrides (sustained-load checks)
 template <typename F>
-static float time_us(F f, int iters = 300) {   // tens of milliseconds per kernel: long enough for the clocks to settle
+static float time_us(F f) {
+  const int iters = g_iters;
   hipEvent_t a, b;
   CK(hipEventCreate(&a));
   CK(hipEventCreate(&b));
@@ -232,6 +234,10 @@ static void run_stream(float* out, const char* name) {
 
 int main(int argc, char** argv) {
   const char* mode = argc > 1 ? argv[1] : "layer";
+  if (const char* it = getenv("KERNEL_BENCH_ITERS")) {
+    const int v = atoi(it);
+    if (v >= 1 && v <= 100000) g_iters = v;
+  }
   if (!strcmp(mode, "mfma")) {
     float* out;
     CK(hipMalloc(&out, 256 * 256 * 4));

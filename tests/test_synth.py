@@ -56,3 +56,13 @@ def test_numpy_and_torch_paths_agree():
         a = synth.normal(5, "k", (333, 1001), 0.3, dt)
         b = synth.normal(5, "k", (333, 1001), 0.3, dt, force_torch=True)
         assert torch.equal(a, b)
+
+
+def test_threshold_filter_is_a_confidence_threshold():
+    # the baseline decoder of bench.py: filter output > 0.5 exactly where the confidence exceeds theta
+    import numpy as np
+    from oracle import l2pd_oracle as O
+    flt = {k: v.numpy() for k, v in synth.threshold_filter(8, 0.9).items()}
+    conf = np.array([0.05, 0.5, 0.89, 0.899, 0.901, 0.95, 1.0, 0.0], dtype=np.float32)
+    p = O.filter_prob(conf, flt)
+    np.testing.assert_array_equal(p > 0.5, conf > 0.9)
