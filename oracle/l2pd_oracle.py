@@ -24,6 +24,10 @@ What it states, in the paper's order and notation:
   block-granular Alg. 3): after every step, once the response holds an
   end-of-text token, everything after its first occurrence is discarded and
   the next step runs on the shortened sequence;
+* the Extremely Greedy Parallel rollout that labels training data (Sec. 3.1.3,
+  Alg. 1 without its update line), the binary cross-entropy of Eq. 6 with its
+  gradient for the two-layer filter, and AdamW (Sec. 4.1 names the optimiser,
+  learning rate 1e-3 and 5,000 epochs; the update rule is the published one);
 * the prefix KV cache variant (Sec. 4.3 names the technique only): K/V of the
   prompt and finished blocks come from a forward over that prefix alone and
   are refreshed once per block; a step recomputes only the active block;
@@ -45,7 +49,12 @@ active block after the first end-of-text leave the mask set undecoded; the
 filter still takes block_len inputs and discarded positions enter as 1.0 like
 committed ones; the block's loop ends when no masked position is left up to the
 end-of-text; discarded positions come back as mask id, decoded_len counts the
-response up to and including the end-of-text.
+response up to and including the end-of-text.  EGP / training: every one of
+the block's positions is a training entry, committed ones as (1.0, label 1);
+when no masked position's prediction equals the reference, the most confident
+masked position takes the REFERENCE token with label 0 (Alg. 1 would not
+terminate); one epoch is one full-batch AdamW step over all collected rows;
+AdamW defaults beta = (0.9, 0.999), eps = 1e-8, weight decay 0.01.
 
 Parity pins: every function below is pinned by tests/test_oracle_*.py against
 brute-force loops, closed forms and invariants, except the whole trajectory on
@@ -417,3 +426,94 @@ def tail_all_eos(response, eos_id, decoded_len):
     r = np.asarray(response)[:decoded_len]
     hit = np.nonzero(r == eos_id)[0]
     return bool(len(hit) and np.all(r[hit[0]:] == eos_id))
+
+
+# --------------------------------------------------------------------------- Alg. 1: EGP rollout
+def egp_step(model, X, prompt_len, b, block_len, mask_id, reference, bias=None):
+    """One pass of Alg. 1's while-loop body without the parameter update: predict, compare with the
+    reference answer, unmask where they agree (X modified in place).  Returns the training row:
+    cin[s] (confidence of masked positions, 1.0 for committed ones) and y[s] (1 = may be unmasked)."""
+    lo = prompt_len + b * block_len
+    logits = apply_bias(model.forward(X, lo, block_len), b * block_len, bias)
+    conf, pre = conf_pre(logits, mask_id)
+    masked = np.asarray(X[lo:lo + block_len]) == mask_id
+    ref = np.asarray(reference[b * block_len:(b + 1) * block_len])
+    match = masked & (pre == ref)
+    cin = np.where(masked, conf, conf.dtype.type(1.0))
+    y = np.where(masked, match, True).astype(conf.dtype)
+    sel = match.copy()
+    if masked.any() and not match.any():
+        cm = np.where(masked, conf, -np.inf)
+        sel[int(np.argmax(cm))] = True            # progress: the reference token, labelled 0
+    for j in np.nonzero(sel)[0]:
+        X[lo + j] = ref[j]
+    return dict(cin=cin, y=y, sel=sel, conf=conf, pre=pre, masked=masked, logits=logits)
+
+
+def egp_rollout(model, prompt, reference, gen_len, block_len, mask_id, bias=None, trace=None):
+    """EGP decoding of one prompt against its reference answer.  Returns (C[n, s], Y[n, s], steps
+    per block); the decoded response equals the reference by construction."""
+    assert gen_len % block_len == 0 and len(reference) == gen_len
+    P = len(prompt)
+    X = np.concatenate([np.asarray(prompt, dtype=np.int64), np.full(gen_len, mask_id, dtype=np.int64)])
+    rows_c, rows_y, per_block = [], [], []
+    for b in range(gen_len // block_len):
+        lo = P + b * block_len
+        n = 0
+        while np.any(X[lo:lo + block_len] == mask_id):
+            before = X.copy() if trace is not None else None
+            d = egp_step(model, X, P, b, block_len, mask_id, reference, bias)
+            rows_c.append(d["cin"])
+            rows_y.append(d["y"])
+            n += 1
+            if trace is not None:
+                d.update(X_before=before, block=b)
+                trace.append(d)
+        per_block.append(n)
+    assert np.array_equal(X[P:], np.asarray(reference))
+    return np.array(rows_c), np.array(rows_y), per_block
+
+
+# --------------------------------------------------------------------------- Eq. 6 and the optimiser
+def bce_loss_and_grad(flt, C, Y):
+    """Mean binary cross-entropy (Eq. 6) of sigmoid(f_theta(c)) against y over all entries of the
+    rows C[n, s], Y[n, s], and its gradient with respect to w1, b1, w2, b2."""
+    C = np.asarray(C, dtype=np.float64)
+    Y = np.asarray(Y, dtype=np.float64)
+    w1, b1, w2, b2 = (np.asarray(flt[k], dtype=np.float64) for k in ("w1", "b1", "w2", "b2"))
+    A = C @ w1.T + b1                       # [n, hidden]
+    H = np.maximum(A, 0.0)
+    Z = H @ w2.T + b2                       # [n, s]
+    m = Z.size
+    # -[y log sigma(z) + (1 - y) log(1 - sigma(z))] = softplus(z) - y z
+    loss = float(np.sum(np.maximum(Z, 0.0) + np.log1p(np.exp(-np.abs(Z))) - Y * Z) / m)
+    dZ = (sigmoid(Z) - Y) / m
+    g = {"w2": dZ.T @ H, "b2": dZ.sum(axis=0)}
+    dH = (dZ @ w2) * (A > 0.0)
+    g["w1"] = dH.T @ C
+    g["b1"] = dH.sum(axis=0)
+    return loss, g
+
+
+def adamw_step(param, grad, m, v, t, lr, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01):
+    """One AdamW update (decoupled weight decay) at step t >= 1.  Returns (param, m, v)."""
+    m = beta1 * m + (1.0 - beta1) * grad
+    v = beta2 * v + (1.0 - beta2) * grad * grad
+    mh = m / (1.0 - beta1 ** t)
+    vh = v / (1.0 - beta2 ** t)
+    param = param - lr * (mh / (np.sqrt(vh) + eps) + weight_decay * param)
+    return param, m, v
+
+
+def train_filter(flt, C, Y, epochs, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01):
+    """`epochs` full-batch AdamW steps on Eq. 6.  Returns (filter, losses[epochs]) in float64."""
+    th = {k: np.array(flt[k], dtype=np.float64) for k in ("w1", "b1", "w2", "b2")}
+    m = {k: np.zeros_like(x) for k, x in th.items()}
+    v = {k: np.zeros_like(x) for k, x in th.items()}
+    losses = []
+    for t in range(1, epochs + 1):
+        loss, g = bce_loss_and_grad(th, C, Y)
+        losses.append(loss)
+        for k in th:
+            th[k], m[k], v[k] = adamw_step(th[k], g[k], m[k], v[k], t, lr, beta1, beta2, eps, weight_decay)
+    return th, np.array(losses)

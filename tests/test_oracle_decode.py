@@ -394,3 +394,95 @@ def test_step_eotp_discarded_positions_feed_the_filter_one():
     # step 2: sequence is P+2 long, positions 2, 3 discarded and enter as 1.0 -> p_0 = sigmoid(25) > tau
     assert trace[1]["n"] == 2 and trace[1]["p"][0] > 0.99
     assert steps == 2 and dl == 2 and resp[1] == eos and resp[0] == 3
+
+
+# ----------------------------------------------------------------- Alg. 1 (EGP), Eq. 6, AdamW
+def test_egp_with_greedy_reference_is_one_step_per_block_all_labels_one():
+    P, G, s, V = 3, 32, 8, 20
+    mask = V - 1
+    table = rand_table(G, V, 41)
+    table[:, mask] = -50.0
+    ref = np.argmax(table, axis=1)
+    C, Y, per_block = O.egp_rollout(ScriptedModel(table, P), np.arange(P), ref, G, s, mask)
+    assert per_block == [1] * (G // s) and C.shape == (G // s, s)
+    assert np.all(Y == 1.0)
+    p = np.exp(table - table.max(1, keepdims=True))
+    p[:, mask] = 0.0
+    np.testing.assert_allclose(C.reshape(-1), (p / p.sum(1, keepdims=True)).max(1), rtol=1e-12)
+
+
+def test_egp_mismatching_positions_are_forced_one_at_a_time_with_label_zero():
+    # reference differs from the (position-only) greedy prediction at 3 positions of block 0:
+    # step 1 unmasks the 5 agreeing ones; the 3 others can never agree, so they are taken one per
+    # step in order of confidence, with the reference token and label 0
+    P, G, s, V = 2, 8, 8, 12
+    mask = V - 1
+    table = np.zeros((G, V))
+    greedy = [3, 1, 4, 1, 5, 9, 2, 6]
+    for g, tok in enumerate(greedy):
+        table[g, tok] = 2.0 + 0.1 * g                 # confidence grows with the position
+    ref = np.array(greedy)
+    ref[[1, 4, 6]] = [0, 0, 0]
+    trace = []
+    C, Y, per_block = O.egp_rollout(ScriptedModel(table, P), np.arange(P), ref, G, s, mask, trace=trace)
+    assert per_block == [4]
+    assert Y[0].tolist() == [1, 0, 1, 1, 0, 1, 0, 1]
+    assert [t["sel"].nonzero()[0].tolist() for t in trace] == [[0, 2, 3, 5, 7], [6], [4], [1]]
+    assert Y[1].tolist() == [1, 0, 1, 1, 0, 1, 0, 1] and Y[3].tolist() == [1, 0, 1, 1, 1, 1, 1, 1]
+    assert np.all(C[1][[0, 2, 3, 5, 7]] == 1.0) and C[1][6] < 1.0    # committed positions enter as 1.0
+
+
+def tiny_filter(s, h, seed):
+    r = np.random.default_rng(seed)
+    return dict(w1=r.normal(size=(h, s)), b1=r.normal(size=h), w2=r.normal(size=(s, h)), b2=r.normal(size=s))
+
+
+def test_bce_gradient_matches_central_differences():
+    s, h, n = 5, 4, 7
+    flt = tiny_filter(s, h, 51)
+    r = np.random.default_rng(52)
+    C, Y = r.uniform(size=(n, s)), (r.uniform(size=(n, s)) > 0.4).astype(float)
+    loss, g = O.bce_loss_and_grad(flt, C, Y)
+    # the definition of Eq. 6 written out entry by entry
+    tot = 0.0
+    for i in range(n):
+        p = O.filter_prob(C[i], flt)
+        tot -= np.sum(Y[i] * np.log(p) + (1 - Y[i]) * np.log(1 - p))
+    assert abs(loss - tot / (n * s)) < 1e-12
+    eps = 1e-6
+    for k in ("w1", "b1", "w2", "b2"):
+        num = np.zeros_like(flt[k])
+        it = np.nditer(flt[k], flags=["multi_index"])
+        for _ in it:
+            idx = it.multi_index
+            for sign in (+1, -1):
+                f2 = {kk: np.array(vv, copy=True) for kk, vv in flt.items()}
+                f2[k][idx] += sign * eps
+                num[idx] += sign * O.bce_loss_and_grad(f2, C, Y)[0]
+        np.testing.assert_allclose(g[k], num / (2 * eps), rtol=1e-5, atol=1e-8)
+
+
+def test_adamw_first_step_closed_form_and_library_agreement():
+    # t = 1: m_hat = g, v_hat = g^2, so the step is -lr (g / (|g| + eps) + wd theta)
+    th, g = np.array([0.5, -2.0, 3.0]), np.array([0.1, -4.0, 1e-12])
+    new, _, _ = O.adamw_step(th, g, np.zeros(3), np.zeros(3), 1, 1e-3)
+    np.testing.assert_allclose(new, th - 1e-3 * (g / (np.abs(g) + 1e-8) + 0.01 * th), rtol=1e-12)
+    # 60 epochs against the library's optimiser and automatic differentiation
+    import torch
+    s, h, n = 6, 5, 9
+    flt = tiny_filter(s, h, 53)
+    r = np.random.default_rng(54)
+    C, Y = r.uniform(size=(n, s)), (r.uniform(size=(n, s)) > 0.5).astype(float)
+    mine, losses = O.train_filter(flt, C, Y, 60, lr=1e-2)
+    tp = {k: torch.tensor(v, dtype=torch.float64, requires_grad=True) for k, v in flt.items()}
+    opt = torch.optim.AdamW(list(tp.values()), lr=1e-2, betas=(0.9, 0.999), eps=1e-8, weight_decay=0.01)
+    Ct, Yt = torch.tensor(C), torch.tensor(Y)
+    for _ in range(60):
+        opt.zero_grad()
+        z = torch.relu(Ct @ tp["w1"].T + tp["b1"]) @ tp["w2"].T + tp["b2"]
+        loss = torch.nn.functional.binary_cross_entropy_with_logits(z, Yt)
+        loss.backward()
+        opt.step()
+    for k in mine:
+        np.testing.assert_allclose(mine[k], tp[k].detach().numpy(), rtol=1e-8, atol=1e-10)
+    assert losses[-1] < losses[0]
