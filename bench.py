@@ -155,6 +155,42 @@ def cached_workload(args, w, eng, flt, prompt, cfg, f, X0, state0, traj_steps, t
     }
 
 
+def pipeline(w, eng, prompt, cfg, seed, dev):
+    """Alg. 1 end to end on the synthetic model: the model's own one-token-per-step answer is the
+    reference (Sec. 3.1.2), an EGP rollout labels the confidences, the filter is trained on them
+    (AdamW, lr 1e-3, 5,000 epochs as in Sec. 4.1), and the prompt is decoded again with it."""
+    import torch
+    from paper_2509_25188_amd import binding as Bd
+    from paper_2509_25188_amd import synth
+    flt = synth.make_filter(seed, w.block_len, w.filter_hidden, dev)
+    vcfg = Bd.Engine.cfg_struct(w.gen_len, w.block_len, 1.0)           # tau = 1: only the forced position goes
+    t0 = time.perf_counter()
+    ref, st_v, _ = eng.generate(prompt, flt, vcfg)
+    torch.cuda.synchronize()
+    t_van = time.perf_counter() - t0
+    rcfg = Bd.Engine.cfg_struct(w.gen_len, w.block_len, 0.5)
+    t0 = time.perf_counter()
+    C, Y, steps = eng.egp_rollout(prompt, ref, rcfg)
+    torch.cuda.synchronize()
+    t_roll = time.perf_counter() - t0
+    rows_c = torch.cat([C[b, :int(steps[b])] for b in range(prompt.shape[0])]).contiguous()
+    rows_y = torch.cat([Y[b, :int(steps[b])] for b in range(prompt.shape[0])]).contiguous()
+    t0 = time.perf_counter()
+    losses = Bd.train_filter(flt, rows_c, rows_y, 5000, lr=1e-3)
+    torch.cuda.synchronize()
+    t_train = time.perf_counter() - t0
+    dcfg = Bd.Engine.cfg_struct(w.gen_len, w.block_len, 0.5)
+    t0 = time.perf_counter()
+    tok, st_f, _ = eng.generate(prompt, flt, dcfg)
+    torch.cuda.synchronize()
+    t_dec = time.perf_counter() - t0
+    return {"vanilla_steps": int(st_v.max()), "vanilla_s": t_van, "egp_steps": int(steps.max()), "egp_rollout_s": t_roll,
+            "training_rows": int(rows_c.shape[0]), "training_epochs": 5000, "training_s": t_train,
+            "bce_first": float(losses[0]), "bce_last": float(losses[-1]),
+            "trained_filter_steps": int(st_f.max()), "trained_filter_s": t_dec,
+            "trained_filter_tokens_equal_to_reference": float((tok == ref).float().mean())}
+
+
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "gate_up_gemm_hbm_traffic.txt")
 GEMM_SOURCE = os.path.join(ROOT, "paper_2509_25188_amd", "csrc", "gemm_bf16.hip")
 
@@ -194,6 +230,9 @@ def main():
     ap.add_argument("--conf-threshold", type=float, default=0.9)
     ap.add_argument("--lm-head-scale", type=float, default=1.0,
                     help="scales the synthetic LM head; 25 spreads the confidences over (0, 1) (not the headline config)")
+    ap.add_argument("--pipeline", action="store_true",
+                    help="also run the whole Learn2PD pipeline on the synthetic model: vanilla answer as reference, "
+                         "EGP rollout, filter training, decode with the trained filter (adds a 'pipeline' object)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch a plain device copy of known size (reference for HBM counter runs)")
     args = ap.parse_args()
@@ -313,6 +352,8 @@ def main():
                      "launches": n_launch, "avg_launch_ms": avg_kern_ms, "flop_per_launch": gu_flops},
         "setup_s": setup_s,
     }
+    if args.pipeline:
+        result["pipeline"] = pipeline(w, eng, prompt, cfg, args.seed, dev)
     if args.copy_calibration:
         n = 1 << 28
         src = torch.empty(n, dtype=torch.uint8, device=dev).fill_(1)

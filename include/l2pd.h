@@ -170,6 +170,36 @@ int32_t l2pd_generate(l2pd_ctx* ctx, const int32_t* prompt_dev, int32_t B, int32
                       const l2pd_decode_cfg* cfg, const l2pd_filter* filter, int32_t* tokens_out_dev,
                       int32_t* steps_out_dev, int32_t* decoded_len_out_dev, void* stream);
 
+/* Extremely Greedy Parallel rollout (Sec. 3.1.3; Alg. 1 without its update line): decodes the prompts
+ * [B, P] with the rule "unmask position j exactly when the greedy prediction equals the reference answer"
+ * reference_dev [B, gen_len], and records one training row per sequence and step:
+ *   conf_rows_dev  [B, gen_len, s] fp32: the block's confidences as the filter sees them (1.0 at committed
+ *                  positions); row index = step index of that sequence;
+ *   label_rows_dev [B, gen_len, s] fp32: 1 where the position may be unmasked (committed, or prediction ==
+ *                  reference), else 0;
+ *   steps_out_dev  [B]: rows written per sequence (rows beyond stay untouched).
+ * When no masked position agrees with the reference, the most confident masked one takes the reference
+ * token (label 0), so the rollout ends with X == reference.  Full recompute, no EoTP (cfg.kv_cache and
+ * cfg.eotp must be 0; cfg.threshold is ignored); the batch advances in lock step as in l2pd_generate. */
+int32_t l2pd_egp_rollout(l2pd_ctx* ctx, const int32_t* prompt_dev, const int32_t* reference_dev, int32_t B,
+                         int32_t P, const l2pd_decode_cfg* cfg, float* conf_rows_dev, float* label_rows_dev,
+                         int32_t* steps_out_dev, void* stream);
+
+/* Filter training (Sec. 3.2, Eq. 6; Sec. 4.1 names AdamW, learning rate 1e-3, 5,000 epochs): `epochs`
+ * full-batch AdamW steps (decoupled weight decay, bias-corrected moments) on the mean binary cross-entropy
+ * of sigmoid(f(conf_row)) against label_row over all n_rows * in_dim entries.  The filter's parameters are
+ * UPDATED IN PLACE through the pointers of `filter` (device memory, fp32).  opt_state_dev: 2 * n_params
+ * floats of device scratch (n_params = 2 * in_dim * hidden + in_dim + hidden), zeroed by the call;
+ * loss_out_dev [epochs] (optional) receives the loss of every epoch before its update.  Runs as one
+ * workgroup; returns L2PD_ENOTIMPL for filters too large for it (more than 20480 parameters). */
+typedef struct {
+  float lr, beta1, beta2, eps, weight_decay;
+  int32_t epochs;
+} l2pd_train_cfg;
+int32_t l2pd_filter_train(const l2pd_filter* filter, const float* conf_rows_dev, const float* label_rows_dev,
+                          int64_t n_rows, const l2pd_train_cfg* train_cfg, float* opt_state_dev,
+                          float* loss_out_dev, void* stream);
+
 /* Timing aid: kernel classes whose launches can be bracketed with HIP events on the launch stream. */
 enum {
   L2PD_K_NONE = 0, L2PD_K_GEMM_QKV = 1, L2PD_K_GEMM_O = 2, L2PD_K_GEMM_GATEUP = 3,

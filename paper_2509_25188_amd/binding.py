@@ -50,8 +50,13 @@ class DecodeCfg(C.Structure):
                 ("kv_cache", C.c_int32), ("keep_kv", C.c_int32), ("bias", LogitBias)]
 
 
+class TrainCfg(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("weight_decay", C.c_float), ("epochs", C.c_int32)]
+
+
 EXPORTS = ("l2pd_workspace_bytes", "l2pd_create", "l2pd_destroy", "l2pd_forward", "l2pd_denoise_step",
-           "l2pd_generate", "l2pd_profile_select", "l2pd_profile_read", "l2pd_strerror")
+           "l2pd_generate", "l2pd_egp_rollout", "l2pd_filter_train", "l2pd_profile_select", "l2pd_profile_read", "l2pd_strerror")
 
 
 def load_library() -> C.CDLL:
@@ -73,6 +78,10 @@ def load_library() -> C.CDLL:
                                       vp, vp, vp, vp, vp, vp]
     lib.l2pd_generate.restype = i32
     lib.l2pd_generate.argtypes = [vp, vp, i32, i32, C.POINTER(DecodeCfg), C.POINTER(Filter), vp, vp, vp, vp]
+    lib.l2pd_egp_rollout.restype = i32
+    lib.l2pd_egp_rollout.argtypes = [vp, vp, vp, i32, i32, C.POINTER(DecodeCfg), vp, vp, vp, vp]
+    lib.l2pd_filter_train.restype = i32
+    lib.l2pd_filter_train.argtypes = [C.POINTER(Filter), vp, vp, C.c_int64, C.POINTER(TrainCfg), vp, vp, vp]
     lib.l2pd_profile_select.restype = i32
     lib.l2pd_profile_select.argtypes = [vp, i32]
     lib.l2pd_profile_read.restype = i32
@@ -211,6 +220,19 @@ class Engine:
                "l2pd_generate")
         return tokens, steps, dlen
 
+    def egp_rollout(self, prompt: torch.Tensor, reference: torch.Tensor, cfg: DecodeCfg):
+        """EGP rollout against `reference` [B, gen_len] (int32).  Returns (conf_rows [B, gen_len, s],
+        label_rows [B, gen_len, s], steps [B]); rows beyond steps[b] are zero."""
+        B, P = prompt.shape
+        dev = prompt.device
+        conf = torch.zeros((B, cfg.gen_len, cfg.block_len), dtype=torch.float32, device=dev)
+        label = torch.zeros_like(conf)
+        steps = torch.empty((B,), dtype=torch.int32, device=dev)
+        _check(lib().l2pd_egp_rollout(self._ctx, prompt.data_ptr(), reference.data_ptr(), B, P, C.byref(cfg),
+                                      conf.data_ptr(), label.data_ptr(), steps.data_ptr(), _stream()),
+               "l2pd_egp_rollout")
+        return conf, label, steps
+
     def profile_select(self, kernel_class: int):
         _check(lib().l2pd_profile_select(self._ctx, kernel_class), "l2pd_profile_select")
 
@@ -218,6 +240,28 @@ class Engine:
         n, ms = C.c_int64(), C.c_double()
         _check(lib().l2pd_profile_read(self._ctx, C.byref(n), C.byref(ms)), "l2pd_profile_read")
         return n.value, ms.value
+
+
+def train_filter(flt: Dict[str, torch.Tensor], conf_rows: torch.Tensor, label_rows: torch.Tensor, epochs: int,
+                 lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01):
+    """Trains the filter IN PLACE (device fp32 tensors w1, b1, w2, b2) on rows [n, s]; returns the
+    per-epoch losses as a device tensor."""
+    w1, b1, w2, b2 = (flt[k] for k in ("w1", "b1", "w2", "b2"))
+    for t in (w1, b1, w2, b2, conf_rows, label_rows):
+        if t.dtype != torch.float32 or not t.is_contiguous() or not t.is_cuda:
+            raise ValueError("train_filter needs contiguous fp32 device tensors")
+    hidden, s = w1.shape
+    n = conf_rows.shape[0]
+    if conf_rows.shape != (n, s) or label_rows.shape != (n, s):
+        raise ValueError("rows must be [n, in_dim]")
+    f = Filter(s, hidden, w1.data_ptr(), b1.data_ptr(), w2.data_ptr(), b2.data_ptr())
+    tc = TrainCfg(lr, beta1, beta2, eps, weight_decay, epochs)
+    n_params = 2 * s * hidden + s + hidden
+    state = torch.empty(2 * n_params, dtype=torch.float32, device=w1.device)
+    losses = torch.empty(epochs, dtype=torch.float32, device=w1.device)
+    _check(lib().l2pd_filter_train(C.byref(f), conf_rows.data_ptr(), label_rows.data_ptr(), n, C.byref(tc),
+                                   state.data_ptr(), losses.data_ptr(), _stream()), "l2pd_filter_train")
+    return losses
 
 
 def engine_for(w: synth.Workload, seed: int, device="cuda", max_batch: Optional[int] = None,

@@ -65,10 +65,29 @@ struct UpdateArgs {
   uint8_t* unmask_out;
   int* ctl;
   const int* teff;       // step-granular EoTP: per-sequence length in force (else null)
+  // EGP rollout (Alg. 1): unmask where the prediction equals the reference answer; one training row per step
+  const int32_t* reference;   // [B, gen_len] or null
+  float* egp_conf;            // [B, gen_len, s]: row = step index of the sequence
+  float* egp_label;
+  int gen_len;
 };
 void launch_update(const UpdateArgs& a, Gate g, hipStream_t s);
 void launch_finalize(const int32_t* X, const int32_t* state, const int* teff, int B, int P, int G, int s_len,
                      int mask_id, int32_t* tokens_out, int32_t* steps_out, int32_t* dlen_out, hipStream_t s);
+// `epochs` full-batch AdamW steps on the binary cross-entropy of Eq. 6 for the two-layer filter, in place.
+struct TrainArgs {
+  float *w1, *b1, *w2, *b2;   // device, updated in place
+  int s, hidden;
+  const float* conf;          // [n, s]
+  const float* label;         // [n, s]
+  long long n;
+  int epochs;
+  float lr, beta1, beta2, eps, weight_decay;
+  float* opt_state;           // [2 * n_params], zeroed by the kernel
+  float* loss_out;            // [epochs] or null
+};
+int filter_train_supported(int s, int hidden);
+void launch_filter_train(const TrainArgs& a, hipStream_t s);
 void launch_seq_len(const int32_t* X, int B, int P, int G, int eos_id, int* teff, int* ctl, hipStream_t s);
 
 // ---- vocabulary reduction over materialised logits (fp32 path and the logits tap) ----

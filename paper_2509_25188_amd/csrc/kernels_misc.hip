@@ -433,7 +433,7 @@ __global__ void __launch_bounds__(1024) k_update(UpdateArgs a, Gate g) {
   __shared__ float s_hid[1024];
   __shared__ unsigned char s_masked[256];
   __shared__ unsigned char s_sel[256];
-  __shared__ int s_flag[6];   // masked, committed, end-of-text seen, still masked afterwards, first end-of-text
+  __shared__ int s_flag[6];   // masked, committed, end-of-text seen, still masked afterwards, first end-of-text, EGP hits
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int s = a.s;
   const int gb = a.ctl[CTL_GB];
@@ -484,7 +484,7 @@ __global__ void __launch_bounds__(1024) k_update(UpdateArgs a, Gate g) {
     }
     if (lane == 0) { s_conf[j] = 1.f / sum; s_pred[j] = idx; }
   }
-  if (tid < 4) s_flag[tid] = 0;
+  if (tid < 4 || tid == 5) s_flag[tid] = 0;
   if (tid == 4) s_flag[4] = 0x7fffffff;
   // step-granular EoTP (Sec. 3.3): the sequence is teff tokens long; block positions at or after
   // teff are discarded: never decoded, and they enter the filter as 1.0 like committed ones
@@ -499,7 +499,8 @@ __global__ void __launch_bounds__(1024) k_update(UpdateArgs a, Gate g) {
     if (mk) atomicAdd(&s_flag[0], 1);   // integer count of masked positions
   }
   __syncthreads();
-  for (int t = tid; t < a.hidden; t += blockDim.x) {
+  const int32_t* ref = a.reference ? a.reference + (size_t)b * a.gen_len + gb * s : nullptr;
+  for (int t = tid; t < (ref ? 0 : a.hidden); t += blockDim.x) {
     float acc = a.b1[t];
     const float* w = a.w1 + (size_t)t * s;
     for (int j = 0; j < s; ++j) acc += w[j] * s_cin[j];
@@ -507,17 +508,33 @@ __global__ void __launch_bounds__(1024) k_update(UpdateArgs a, Gate g) {
   }
   __syncthreads();
   if (tid < s) {
-    float z = a.b2[tid];
-    const float* w = a.w2 + (size_t)tid * a.hidden;
-    for (int t = 0; t < a.hidden; ++t) z += w[t] * s_hid[t];
-    float p = 1.f / (1.f + expf(-z));
-    if (a.filt_out) a.filt_out[b * s + tid] = p;
-    s_sel[tid] = s_masked[tid] && (p > a.tau);
+    if (ref) {
+      // EGP (Alg. 1): a masked position is unmasked exactly when its prediction is the reference token
+      const bool hit = s_masked[tid] && s_pred[tid] == ref[tid];
+      s_sel[tid] = hit;
+      if (hit) atomicAdd(&s_flag[5], 1);
+    } else {
+      float z = a.b2[tid];
+      const float* w = a.w2 + (size_t)tid * a.hidden;
+      for (int t = 0; t < a.hidden; ++t) z += w[t] * s_hid[t];
+      float p = 1.f / (1.f + expf(-z));
+      if (a.filt_out) a.filt_out[b * s + tid] = p;
+      s_sel[tid] = s_masked[tid] && (p > a.tau);
+    }
   }
   __syncthreads();
   const int n_masked = s_flag[0];
   const bool mine = !st[2] && st[0] == gb;
-  if (tid == 0 && n_masked > 0) {
+  if (ref && mine && n_masked > 0 && tid < s) {
+    // the step's training row: confidences as the filter would see them, labels 1 = may be unmasked
+    const size_t row = ((size_t)b * a.gen_len + st[1]) * s + tid;
+    a.egp_conf[row] = s_cin[tid];
+    a.egp_label[row] = (!s_masked[tid] || s_sel[tid]) ? 1.f : 0.f;
+  }
+  __syncthreads();   // labels are read before the forced position is added to the selection
+  // the most confident masked position always goes (in an EGP rollout only when nothing agreed,
+  // and then with the reference token)
+  if (tid == 0 && n_masked > 0 && !(ref && s_flag[5] > 0)) {
     float best = -INFINITY;
     int bj = -1;
     for (int j = 0; j < s; ++j)
@@ -529,7 +546,7 @@ __global__ void __launch_bounds__(1024) k_update(UpdateArgs a, Gate g) {
     bool sel = mine && s_sel[tid];
     if (a.unmask_out) a.unmask_out[b * s + tid] = sel ? 1 : 0;
     if (sel) {
-      X[lo + tid] = s_pred[tid];
+      X[lo + tid] = ref ? ref[tid] : s_pred[tid];
       atomicAdd(&s_flag[1], 1);
     }
   }
@@ -571,7 +588,7 @@ void launch_update(const UpdateArgs& a, Gate g, hipStream_t s) {
 __global__ void k_finalize(const int32_t* X, const int32_t* state, const int* teff, int B, int P, int G, int s_len,
                            int mask_id, int32_t* tokens_out, int32_t* steps_out, int32_t* dlen_out) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < B * G) {
+  if (tokens_out && i < B * G) {
     int b = i / G, t = i % G;
     int v = X[(size_t)b * (P + G) + P + t];
     if (teff && P + t >= teff[b]) v = mask_id;
@@ -614,6 +631,152 @@ __global__ void __launch_bounds__(256) k_seq_len(const int32_t* X, int B, int P,
 }
 void launch_seq_len(const int32_t* X, int B, int P, int G, int eos_id, int* teff, int* ctl, hipStream_t s) {
   hipLaunchKernelGGL(k_seq_len, dim3(1), dim3(256), 0, s, X, B, P, G, eos_id, teff, ctl);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Filter training (Sec. 3.2, Eq. 6; Sec. 4.1: AdamW): full-batch epochs on the mean binary
+// cross-entropy of sigmoid(W2 relu(W1 c + b1) + b2) against the EGP labels.  One workgroup: the
+// model has a few thousand parameters and a data set of a few thousand rows, so the whole of it is
+// a latency-bound loop that wants no grid synchronisation.  Parameters and the chunk's
+// intermediates live in LDS; every thread owns a few parameters, accumulates their gradient over
+// the rows in ascending order (deterministic) and applies the AdamW update.
+constexpr int kTrainThreads = 1024;
+constexpr int kTrainMaxOwn = 20;                 // parameters per thread
+constexpr int kTrainLdsFloats = 36 * 1024;       // 144 KB
+static int train_chunk_rows(int s, int hidden) {
+  const int n_params = 2 * s * hidden + s + hidden;
+  const int left = kTrainLdsFloats - n_params - 64;
+  int ch = left / (2 * s + 2 * hidden);
+  return ch > 64 ? 64 : ch;
+}
+int filter_train_supported(int s, int hidden) {
+  const int n_params = 2 * s * hidden + s + hidden;
+  return s >= 1 && hidden >= 1 && n_params <= kTrainThreads * kTrainMaxOwn && train_chunk_rows(s, hidden) >= 8;
+}
+__global__ void __launch_bounds__(kTrainThreads) k_filter_train(TrainArgs a, int chunk) {
+  extern __shared__ float lds[];
+  const int s = a.s, h = a.hidden, tid = threadIdx.x;
+  const int n_w1 = h * s, n_w2 = s * h, n_params = n_w1 + h + n_w2 + s;
+  // LDS: parameters (w1 | b1 | w2 | b2), chunk rows C, hidden H, dZ, dH, reduction scratch
+  float* th = lds;
+  float* Cc = th + n_params;
+  float* Hc = Cc + chunk * s;
+  float* dZ = Hc + chunk * h;
+  float* dH = dZ + chunk * s;
+  float* red = dH + chunk * h;    // 64 floats
+  const float* W1 = th;
+  const float* B1 = th + n_w1;
+  const float* W2 = B1 + h;
+  const float* B2 = W2 + n_w2;
+  float* gl[4] = {a.w1, a.b1, a.w2, a.b2};
+  const int seg[5] = {0, n_w1, n_w1 + h, n_w1 + h + n_w2, n_params};
+  for (int p = tid; p < n_params; p += kTrainThreads) {
+    int k = p < seg[1] ? 0 : (p < seg[2] ? 1 : (p < seg[3] ? 2 : 3));
+    th[p] = gl[k][p - seg[k]];
+    a.opt_state[p] = 0.f;
+    a.opt_state[n_params + p] = 0.f;
+  }
+  __syncthreads();
+  const float inv_m = 1.f / ((float)a.n * (float)s);
+  float b1t = 1.f, b2t = 1.f;     // beta^t
+  for (int ep = 0; ep < a.epochs; ++ep) {
+    float g[kTrainMaxOwn];
+#pragma unroll
+    for (int o = 0; o < kTrainMaxOwn; ++o) g[o] = 0.f;
+    float loss = 0.f;
+    for (long long c0 = 0; c0 < a.n; c0 += chunk) {
+      const int rows = (int)min((long long)chunk, a.n - c0);
+      for (int i = tid; i < rows * s; i += kTrainThreads) Cc[i] = a.conf[c0 * s + i];
+      __syncthreads();
+      for (int i = tid; i < rows * h; i += kTrainThreads) {      // hidden activations
+        const int r = i / h, t = i % h;
+        float acc = B1[t];
+        for (int j = 0; j < s; ++j) acc += W1[t * s + j] * Cc[r * s + j];
+        Hc[i] = fmaxf(acc, 0.f);
+      }
+      __syncthreads();
+      for (int i = tid; i < rows * s; i += kTrainThreads) {      // logits, loss, dL/dz
+        const int r = i / s, j = i % s;
+        float z = B2[j];
+        for (int t = 0; t < h; ++t) z += W2[j * h + t] * Hc[r * h + t];
+        const float y = a.label[c0 * s + i];
+        loss += fmaxf(z, 0.f) + log1pf(expf(-fabsf(z))) - y * z;   // softplus(z) - y z
+        dZ[i] = (1.f / (1.f + expf(-z)) - y) * inv_m;
+      }
+      __syncthreads();
+      for (int i = tid; i < rows * h; i += kTrainThreads) {      // dL/dh through the ReLU
+        const int r = i / h, t = i % h;
+        float acc = 0.f;
+        for (int j = 0; j < s; ++j) acc += dZ[r * s + j] * W2[j * h + t];
+        dH[i] = Hc[i] > 0.f ? acc : 0.f;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int o = 0; o < kTrainMaxOwn; ++o) {                     // gradient of the owned parameters
+        const int p = tid + o * kTrainThreads;
+        if (p >= n_params) break;
+        float acc = 0.f;
+        if (p < seg[1]) {
+          const int t = p / s, j = p % s;
+          for (int r = 0; r < rows; ++r) acc += dH[r * h + t] * Cc[r * s + j];
+        } else if (p < seg[2]) {
+          const int t = p - seg[1];
+          for (int r = 0; r < rows; ++r) acc += dH[r * h + t];
+        } else if (p < seg[3]) {
+          const int q = p - seg[2], j = q / h, t = q % h;
+          for (int r = 0; r < rows; ++r) acc += dZ[r * s + j] * Hc[r * h + t];
+        } else {
+          const int j = p - seg[3];
+          for (int r = 0; r < rows; ++r) acc += dZ[r * s + j];
+        }
+        g[o] += acc;
+      }
+      __syncthreads();
+    }
+    // loss of the epoch (before its update)
+    if (a.loss_out) {
+#pragma unroll
+      for (int of = 32; of > 0; of >>= 1) loss += __shfl_xor(loss, of, 64);
+      if ((tid & 63) == 0) red[tid >> 6] = loss;
+      __syncthreads();
+      if (tid == 0) {
+        float tot = 0.f;
+        for (int w = 0; w < kTrainThreads / 64; ++w) tot += red[w];
+        a.loss_out[ep] = tot * inv_m;
+      }
+    }
+    // AdamW, decoupled weight decay
+    b1t *= a.beta1;
+    b2t *= a.beta2;
+#pragma unroll
+    for (int o = 0; o < kTrainMaxOwn; ++o) {
+      const int p = tid + o * kTrainThreads;
+      if (p >= n_params) break;
+      const float m = a.beta1 * a.opt_state[p] + (1.f - a.beta1) * g[o];
+      const float v = a.beta2 * a.opt_state[n_params + p] + (1.f - a.beta2) * g[o] * g[o];
+      a.opt_state[p] = m;
+      a.opt_state[n_params + p] = v;
+      const float mh = m / (1.f - b1t), vh = v / (1.f - b2t);
+      th[p] = th[p] - a.lr * (mh / (sqrtf(vh) + a.eps) + a.weight_decay * th[p]);
+    }
+    __syncthreads();
+  }
+  for (int p = tid; p < n_params; p += kTrainThreads) {
+    int k = p < seg[1] ? 0 : (p < seg[2] ? 1 : (p < seg[3] ? 2 : 3));
+    gl[k][p - seg[k]] = th[p];
+  }
+}
+void launch_filter_train(const TrainArgs& a, hipStream_t s) {
+  const int chunk = train_chunk_rows(a.s, a.hidden);
+  const int n_params = 2 * a.s * a.hidden + a.s + a.hidden;
+  const size_t smem = (size_t)(n_params + chunk * (2 * a.s + 2 * a.hidden) + 64) * sizeof(float);
+  static bool attr_done = false;
+  if (!attr_done) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_filter_train), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              kTrainLdsFloats * (int)sizeof(float));
+    attr_done = true;
+  }
+  hipLaunchKernelGGL(k_filter_train, dim3(1), dim3(kTrainThreads), smem, s, a, chunk);
 }
 
 }  // namespace l2pd

@@ -385,6 +385,12 @@ int check_decode_args(const l2pd_ctx* c, int B, int P, const l2pd_decode_cfg* cf
   return L2PD_OK;
 }
 
+struct EgpArgs {             // Alg. 1 rollout: reference answers in, training rows out
+  const int32_t* reference;  // [B, gen_len]
+  float* conf;               // [B, gen_len, s]
+  float* label;
+};
+
 struct StepTaps {
   float* logits;
   float* conf;
@@ -407,7 +413,8 @@ void run_refresh(l2pd_ctx* c, const int32_t* X, int B, int P, const l2pd_decode_
 // t_run > 0 (step-granular EoTP): the forward runs over the first t_run positions of every sequence,
 // each sequence attending to its own teff[b] <= t_run keys.
 void run_step(l2pd_ctx* c, int32_t* X, int B, int P, const l2pd_decode_cfg* cfg, const l2pd_filter* f,
-              int32_t* state, int host_gb, const StepTaps& taps, hipStream_t s, int t_run = 0) {
+              int32_t* state, int host_gb, const StepTaps& taps, hipStream_t s, int t_run = 0,
+              const EgpArgs* egp = nullptr) {
   const Layout& L = c->L;
   const int sl = cfg->block_len, T = P + cfg->gen_len, nb = cfg->gen_len / sl;
   int* ctl = c->at<int>(L.ctl);
@@ -437,7 +444,9 @@ void run_step(l2pd_ctx* c, int32_t* X, int B, int P, const l2pd_decode_cfg* cfg,
   u.mask_id = c->m.mask_id; u.eos_id = c->m.eos_id; u.eotp = cfg->eotp;
   u.part_max = c->at<float>(L.part_max); u.part_sum = c->at<float>(L.part_sum);
   u.part_idx = c->at<int32_t>(L.part_idx); u.n_part = L.n_part;
-  u.w1 = f->w1_dev; u.b1 = f->b1_dev; u.w2 = f->w2_dev; u.b2 = f->b2_dev; u.hidden = f->hidden;
+  if (f) { u.w1 = f->w1_dev; u.b1 = f->b1_dev; u.w2 = f->w2_dev; u.b2 = f->b2_dev; u.hidden = f->hidden; }
+  if (egp) { u.reference = egp->reference; u.egp_conf = egp->conf; u.egp_label = egp->label; }
+  u.gen_len = cfg->gen_len;
   u.tau = cfg->threshold;
   u.conf_out = taps.conf; u.pred_out = taps.pred; u.filt_out = taps.filt; u.unmask_out = taps.unmask;
   u.ctl = ctl;
@@ -678,6 +687,65 @@ int32_t l2pd_generate(l2pd_ctx* c, const int32_t* prompt_dev, int32_t B, int32_t
                   steps_out_dev, decoded_len_out_dev, s);
   HIP_TRY(c, hipGetLastError());
   return L2PD_OK;
+}
+
+int32_t l2pd_egp_rollout(l2pd_ctx* c, const int32_t* prompt_dev, const int32_t* reference_dev, int32_t B, int32_t P,
+                         const l2pd_decode_cfg* cfg, float* conf_rows_dev, float* label_rows_dev,
+                         int32_t* steps_out_dev, void* stream) {
+  if (!c || !cfg || !prompt_dev || !reference_dev || !conf_rows_dev || !label_rows_dev) return L2PD_EINVAL;
+  if (B < 1 || B > c->max_batch || P < 1) return L2PD_EINVAL;
+  if (cfg->gen_len < 1 || cfg->block_len < 1 || cfg->block_len > 256 || cfg->gen_len % cfg->block_len) return L2PD_EINVAL;
+  if ((long long)P + cfg->gen_len > c->max_seq) return L2PD_EINVAL;
+  if (cfg->kv_cache != L2PD_CACHE_NONE || cfg->eotp != L2PD_EOTP_OFF) return L2PD_ENOTIMPL;
+  if (isnan(cfg->bias.value) ||
+      (cfg->bias.value != 0.f && (cfg->bias.token_id < 0 || cfg->bias.token_id >= c->m.vocab)))
+    return L2PD_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int st = ensure_device(c, s);
+  if (st) return st;
+  st = ensure_pinned(c);
+  if (st) return st;
+  const Layout& L = c->L;
+  int32_t* X = c->at<int32_t>(L.X);
+  int32_t* state = c->at<int32_t>(L.state);
+  int* ctl = c->at<int>(L.ctl);
+  const int sl = cfg->block_len, G = cfg->gen_len, nb = G / sl;
+  launch_init_decode(X, prompt_dev, B, P, G, c->m.mask_id, state, ctl, s);
+  const StepTaps no_taps = {nullptr, nullptr, nullptr, nullptr, nullptr};
+  const EgpArgs egp = {reference_dev, conf_rows_dev, label_rows_dev};
+  // every step commits at least one position per unfinished sequence: at most gen_len steps;
+  // the control block is looked at every few steps, as in l2pd_generate
+  for (int k = 0; k < G;) {
+    for (int i = 0; i < 4 && k < G; ++i, ++k) run_step(c, X, B, P, cfg, nullptr, state, -1, no_taps, s, 0, &egp);
+    launch_prepare(state, B, nb, ctl, s);
+    HIP_TRY(c, hipMemcpyAsync(c->pinned, ctl, CTL_WORDS * sizeof(int), hipMemcpyDeviceToHost, s));
+    HIP_TRY(c, hipStreamSynchronize(s));
+    if (c->pinned[CTL_ALL_DONE]) break;
+  }
+  launch_finalize(X, state, nullptr, B, P, G, sl, c->m.mask_id, nullptr, steps_out_dev, nullptr, s);
+  HIP_TRY(c, hipGetLastError());
+  return L2PD_OK;
+}
+
+int32_t l2pd_filter_train(const l2pd_filter* f, const float* conf_rows_dev, const float* label_rows_dev,
+                          int64_t n_rows, const l2pd_train_cfg* tc, float* opt_state_dev, float* loss_out_dev,
+                          void* stream) {
+  if (!f || !tc || !conf_rows_dev || !label_rows_dev || !opt_state_dev) return L2PD_EINVAL;
+  if (!f->w1_dev || !f->b1_dev || !f->w2_dev || !f->b2_dev || f->in_dim < 1 || f->hidden < 1) return L2PD_EINVAL;
+  if (n_rows < 1 || n_rows > (1ll << 24) || tc->epochs < 1 || tc->epochs > 1000000) return L2PD_EINVAL;
+  if (!(tc->lr > 0.f) || !(tc->beta1 >= 0.f && tc->beta1 < 1.f) || !(tc->beta2 >= 0.f && tc->beta2 < 1.f) ||
+      !(tc->eps > 0.f) || !(tc->weight_decay >= 0.f))
+    return L2PD_EINVAL;
+  if (!filter_train_supported(f->in_dim, f->hidden)) return L2PD_ENOTIMPL;
+  TrainArgs a = {};
+  a.w1 = const_cast<float*>(f->w1_dev); a.b1 = const_cast<float*>(f->b1_dev);
+  a.w2 = const_cast<float*>(f->w2_dev); a.b2 = const_cast<float*>(f->b2_dev);
+  a.s = f->in_dim; a.hidden = f->hidden;
+  a.conf = conf_rows_dev; a.label = label_rows_dev; a.n = n_rows; a.epochs = tc->epochs;
+  a.lr = tc->lr; a.beta1 = tc->beta1; a.beta2 = tc->beta2; a.eps = tc->eps; a.weight_decay = tc->weight_decay;
+  a.opt_state = opt_state_dev; a.loss_out = loss_out_dev;
+  launch_filter_train(a, static_cast<hipStream_t>(stream));
+  return hipGetLastError() == hipSuccess ? L2PD_OK : L2PD_EHIP;
 }
 
 int32_t l2pd_profile_select(l2pd_ctx* c, int32_t cls) {
