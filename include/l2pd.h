@@ -116,6 +116,10 @@ typedef struct {
   int32_t keep_kv;                  /* l2pd_denoise_step in a cached mode: 0 rebuilds the K/V store from the
                                        tokens first; 1 uses the store as the previous call left it (stepping
                                        through a block after a call that rebuilt it).  l2pd_generate ignores it. */
+  int32_t ragged;                   /* batches: 0 = lock step (every sequence works on the smallest unfinished
+                                       block index, one that is ahead idles); 1 = per-sequence block pointers
+                                       (every sequence works on its own block; same tokens and per-sequence step
+                                       counts, fewer forwards).  Full recompute only. */
   l2pd_logit_bias bias;
 } l2pd_decode_cfg;
 
@@ -145,8 +149,9 @@ int32_t l2pd_forward(l2pd_ctx* ctx, const int32_t* tokens_dev, int32_t B, int32_
  * position of highest confidence, block advance, EoTP check (Alg. 3) when the block completes.
  *
  * tokens_dev [B, prompt_len + gen_len] and state_dev [B, 3] = (block_idx, steps, done) are updated
- * in place.  The batch advances in lock step: the active block is the smallest block_idx among
- * sequences that are not done; a sequence that has finished that block idles (state unchanged).
+ * in place.  By default the batch advances in lock step: the active block is the smallest block_idx among
+ * sequences that are not done; a sequence that has finished that block idles (state unchanged).  With
+ * cfg.ragged every sequence that is not done works on its own block_idx.
  * Optional taps (NULL to skip), all for the active block, written before the update:
  *   logits_dev [B, s, vocab] fp32 (bias applied), conf_dev [B, s], pred_dev [B, s],
  *   filt_dev [B, s] (filter output p), unmask_dev [B, s] (1 where unmasked by this step).

@@ -47,7 +47,7 @@ EOTP_OFF, EOTP_BLOCK, EOTP_STEP = 0, 1, 2
 
 class DecodeCfg(C.Structure):
     _fields_ = [("gen_len", C.c_int32), ("block_len", C.c_int32), ("threshold", C.c_float), ("eotp", C.c_int32),
-                ("kv_cache", C.c_int32), ("keep_kv", C.c_int32), ("bias", LogitBias)]
+                ("kv_cache", C.c_int32), ("keep_kv", C.c_int32), ("ragged", C.c_int32), ("bias", LogitBias)]
 
 
 class TrainCfg(C.Structure):
@@ -172,11 +172,11 @@ class Engine:
 
     @staticmethod
     def cfg_struct(gen_len, block_len, threshold, eotp=False, prefix_cache=False, bias=None,
-                   dual_cache=False) -> DecodeCfg:
+                   dual_cache=False, ragged=False) -> DecodeCfg:
         b = LogitBias(0, 0, 0.0) if bias is None else LogitBias(int(bias[0]), int(bias[1]), float(bias[2]))
         if prefix_cache and dual_cache:
             raise ValueError("prefix_cache and dual_cache are alternatives")
-        return DecodeCfg(gen_len, block_len, threshold, int(eotp), CACHE_DUAL if dual_cache else int(bool(prefix_cache)), 0, b)
+        return DecodeCfg(gen_len, block_len, threshold, int(eotp), CACHE_DUAL if dual_cache else int(bool(prefix_cache)), 0, int(bool(ragged)), b)
 
     # ---- entry points ----
     def forward(self, tokens: torch.Tensor, row_begin: int = 0, row_count: Optional[int] = None) -> torch.Tensor:

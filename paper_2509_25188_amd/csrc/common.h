@@ -10,8 +10,10 @@ namespace l2pd {
 
 typedef __hip_bfloat16 bf16;
 
-// Device control block (int32 words).  Written by k_prepare at the start of every step.
-enum { CTL_GB = 0, CTL_ALL_DONE = 1, CTL_ACTIVE = 2, CTL_TMAX = 3, CTL_WORDS = 8 };
+// Device control block (int32 words).  Written by k_prepare at the start of every step.  The words
+// from CTL_SEQ_GB on hold the active block of every sequence: the batch's common one in lock step,
+// the sequence's own with per-sequence block pointers.
+enum { CTL_GB = 0, CTL_ALL_DONE = 1, CTL_ACTIVE = 2, CTL_TMAX = 3, CTL_WORDS = 8, CTL_SEQ_GB = 8 };
 
 // Every kernel of a step is gated: once decoding has stopped (or, with the prefix cache, once the
 // block the host enqueued it for is finished) it returns at once, so steps that the host enqueued
@@ -27,12 +29,12 @@ __device__ __forceinline__ bool gate_skip(const Gate& g) {
 }
 
 // Maps a compact row index r (b * rows_per_seq + j) to a row of a [B, seq_stride] array:
-//   b * seq_stride + off_base + gb * off_per_gb + j,  gb read from the control block.
+//   b * seq_stride + off_base + gb_b * off_per_gb + j,  gb_b = sequence b's active block from the control block.
 struct RowMap {
   int rows_per_seq, seq_stride, off_base, off_per_gb;
 };
 __device__ __forceinline__ int map_row(const RowMap& m, int r, const int* ctl) {
-  int gb = (m.off_per_gb && ctl) ? ctl[CTL_GB] : 0;
+  int gb = (m.off_per_gb && ctl) ? ctl[CTL_SEQ_GB + r / m.rows_per_seq] : 0;
   return (r / m.rows_per_seq) * m.seq_stride + m.off_base + gb * m.off_per_gb + (r % m.rows_per_seq);
 }
 
@@ -41,7 +43,7 @@ void launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t s);
 void launch_rope_table(float* cos_t, float* sin_t, int max_pos, int head_dim, float base, hipStream_t s);
 void launch_init_decode(int32_t* X, const int32_t* prompt, int B, int P, int G, int mask_id, int32_t* state,
                         int* ctl, hipStream_t s);
-void launch_prepare(const int32_t* state, int B, int n_blocks, int* ctl, hipStream_t s);
+void launch_prepare(const int32_t* state, int B, int n_blocks, int ragged, int* ctl, hipStream_t s);
 void launch_embed(float* h, const void* emb, int dtype, const int32_t* tokens, RowMap tokmap, int rows, int d,
                   Gate g, hipStream_t s);
 // h (+= part[0] + ... + part[n_parts-1] in that order when given; written back) -> y = rmsnorm(h) * gain,

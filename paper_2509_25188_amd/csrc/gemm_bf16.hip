@@ -445,7 +445,7 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
     float* s_s = s_m + WN * BM;
     int* s_i = reinterpret_cast<int*>(s_s + WN * BM);
     __syncthreads();
-    const int gb = (e.bias.value != 0.f && a.gate.ctl) ? a.gate.ctl[CTL_GB] : 0;
+    const bool biased = e.bias.value != 0.f && a.gate.ctl;
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -459,8 +459,9 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
         for (int j = 0; j < FN; ++j) {
           int col = n0 + wn * (BN / WN) + j * 32 + lj;
           float v = acc[i][j][r];
-          if (e.bias.value != 0.f && col == e.bias.token_id &&
-              gb * e.bias.block_len + (row % e.bias.block_len) >= e.bias.gen_pos_from)
+          if (biased && col == e.bias.token_id && row < a.M &&
+              a.gate.ctl[CTL_SEQ_GB + row / e.bias.block_len] * e.bias.block_len + (row % e.bias.block_len) >=
+                  e.bias.gen_pos_from)
             v += e.bias.value;
           if (e.logits && row < a.M && col < a.N) e.logits[(size_t)row * a.N + col] = v;
           if (col == e.mask_id || col >= a.N) v = -INFINITY;

@@ -54,7 +54,9 @@ void launch_init_decode(int32_t* X, const int32_t* prompt, int B, int P, int G, 
 }
 
 // Active block of the lock-step batch = smallest block index among sequences that are not done.
-__global__ void k_prepare(const int32_t* state, int B, int n_blocks, int* ctl) {
+// With `ragged` every sequence works on its own block (per-sequence block pointers): nobody idles
+// while another sequence finishes the common block.
+__global__ void k_prepare(const int32_t* state, int B, int n_blocks, int ragged, int* ctl) {
   if (threadIdx.x == 0 && blockIdx.x == 0) {
     int gb = n_blocks, all_done = 1;
     for (int b = 0; b < B; ++b) {
@@ -65,12 +67,17 @@ __global__ void k_prepare(const int32_t* state, int B, int n_blocks, int* ctl) {
       }
     }
     if (gb >= n_blocks) all_done = 1;
-    ctl[CTL_GB] = all_done ? (n_blocks > 0 ? n_blocks - 1 : 0) : gb;
+    const int last = n_blocks > 0 ? n_blocks - 1 : 0;
+    ctl[CTL_GB] = all_done ? last : gb;
     ctl[CTL_ALL_DONE] = all_done;
+    for (int b = 0; b < B; ++b) {
+      const int own = state[b * 3 + 0] < last ? state[b * 3 + 0] : last;
+      ctl[CTL_SEQ_GB + b] = ragged ? own : ctl[CTL_GB];
+    }
   }
 }
-void launch_prepare(const int32_t* state, int B, int n_blocks, int* ctl, hipStream_t s) {
-  hipLaunchKernelGGL(k_prepare, dim3(1), dim3(64), 0, s, state, B, n_blocks, ctl);
+void launch_prepare(const int32_t* state, int B, int n_blocks, int ragged, int* ctl, hipStream_t s) {
+  hipLaunchKernelGGL(k_prepare, dim3(1), dim3(64), 0, s, state, B, n_blocks, ragged, ctl);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -378,7 +385,7 @@ __global__ void k_vocab_partials(float* logits, int rows, int V, int chunk, int 
   float* row = logits + (size_t)r * V;
   int c0 = p * chunk, c1 = min(V, c0 + chunk);
   if (bias.value != 0.f && bias.token_id >= c0 && bias.token_id < c1 && tid == 0) {
-    int gb = g.ctl ? g.ctl[CTL_GB] : 0;
+    int gb = g.ctl ? g.ctl[CTL_SEQ_GB + r / bias.block_len] : 0;
     int genpos = gb * bias.block_len + (r % bias.block_len);
     if (genpos >= bias.gen_pos_from) row[bias.token_id] += bias.value;
   }
@@ -436,7 +443,7 @@ __global__ void __launch_bounds__(1024) k_update(UpdateArgs a, Gate g) {
   __shared__ int s_flag[6];   // masked, committed, end-of-text seen, still masked afterwards, first end-of-text, EGP hits
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int s = a.s;
-  const int gb = a.ctl[CTL_GB];
+  const int gb = a.ctl[CTL_SEQ_GB + b];   // the batch's common block, or this sequence's own
   const int lo = a.P + gb * s;
   int32_t* X = a.X + (size_t)b * a.T;
   int32_t* st = a.state + b * 3;

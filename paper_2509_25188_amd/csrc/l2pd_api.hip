@@ -99,7 +99,7 @@ Layout make_layout(const l2pd_model_desc& m, int max_batch, int max_seq, int cac
   const size_t head_rows = (size_t)max_batch * 256;   // block_len <= 256
   L.cos_t = c.take((size_t)L.Tpad * (m.head_dim / 2) * 4);
   L.sin_t = c.take((size_t)L.Tpad * (m.head_dim / 2) * 4);
-  L.ctl = c.take(CTL_WORDS * 4);
+  L.ctl = c.take((size_t)(CTL_WORDS + max_batch) * 4);
   L.state = c.take((size_t)max_batch * 3 * 4);
   L.teff = c.take((size_t)max_batch * 4);
   L.X = c.take(rows * 4);
@@ -380,6 +380,8 @@ int check_decode_args(const l2pd_ctx* c, int B, int P, const l2pd_decode_cfg* cf
   if (cfg->kv_cache && !c->cache) return L2PD_EINVAL;
   if (cfg->eotp < 0 || cfg->eotp > L2PD_EOTP_STEP) return L2PD_EINVAL;
   if (cfg->eotp == L2PD_EOTP_STEP && cfg->kv_cache) return L2PD_ENOTIMPL;   // shortened sequences: full recompute only
+  if (cfg->ragged < 0 || cfg->ragged > 1) return L2PD_EINVAL;
+  if (cfg->ragged && cfg->kv_cache) return L2PD_ENOTIMPL;   // the K/V stores are rebuilt for one common block
   if (cfg->bias.value != 0.f && (cfg->bias.token_id < 0 || cfg->bias.token_id >= c->m.vocab)) return L2PD_EINVAL;
   if (isnan(cfg->bias.value)) return L2PD_EINVAL;
   return L2PD_OK;
@@ -418,7 +420,7 @@ void run_step(l2pd_ctx* c, int32_t* X, int B, int P, const l2pd_decode_cfg* cfg,
   const Layout& L = c->L;
   const int sl = cfg->block_len, T = P + cfg->gen_len, nb = cfg->gen_len / sl;
   int* ctl = c->at<int>(L.ctl);
-  launch_prepare(state, B, nb, ctl, s);
+  launch_prepare(state, B, nb, cfg->ragged, ctl, s);
   Gate g = {ctl, cfg->kv_cache ? host_gb : -1};
   BiasArgs bias = {cfg->bias.token_id, cfg->bias.gen_pos_from, sl, cfg->bias.value};
   if (cfg->kv_cache) {
@@ -471,7 +473,7 @@ int sync_seq_len(l2pd_ctx* c, const int32_t* X, const int32_t* state, int B, int
                  int* all_done, hipStream_t s) {
   const Layout& L = c->L;
   int* ctl = c->at<int>(L.ctl);
-  launch_prepare(state, B, cfg->gen_len / cfg->block_len, ctl, s);
+  launch_prepare(state, B, cfg->gen_len / cfg->block_len, cfg->ragged, ctl, s);
   launch_seq_len(X, B, P, cfg->gen_len, c->m.eos_id, c->at<int>(L.teff), ctl, s);
   if (hipMemcpyAsync(c->pinned, ctl, CTL_WORDS * sizeof(int), hipMemcpyDeviceToHost, s) != hipSuccess ||
       hipStreamSynchronize(s) != hipSuccess)
@@ -638,7 +640,7 @@ int32_t l2pd_generate(l2pd_ctx* c, const int32_t* prompt_dev, int32_t B, int32_t
     while (issued < max_steps) {
       for (int i = 0; i < CHUNK && issued < max_steps; ++i, ++issued)
         run_step(c, X, B, P, cfg, f, state, host_gb, no_taps, s);
-      launch_prepare(state, B, nb, ctl, s);
+      launch_prepare(state, B, nb, cfg->ragged, ctl, s);
       if (hipMemcpyAsync(c->pinned + slot * CTL_WORDS, ctl, CTL_WORDS * sizeof(int), hipMemcpyDeviceToHost, s) !=
               hipSuccess ||
           hipEventRecord(c->poll_ev[slot], s) != hipSuccess)
@@ -673,7 +675,7 @@ int32_t l2pd_generate(l2pd_ctx* c, const int32_t* prompt_dev, int32_t B, int32_t
     launch_seq_len(X, B, P, G, c->m.eos_id, c->at<int>(L.teff), ctl, s);
   } else if (cfg->kv_cache) {
     for (int gb = 0; gb < nb; ++gb) {
-      launch_prepare(state, B, nb, ctl, s);
+      launch_prepare(state, B, nb, cfg->ragged, ctl, s);
       run_refresh(c, X, B, P, cfg, gb, Gate{ctl, -1}, s);
       int r = run_until(gb, sl);   // a block needs at most block_len steps
       if (r < 0) { c->last_hip_error = (int)hipGetLastError(); return L2PD_EHIP; }
@@ -717,7 +719,7 @@ int32_t l2pd_egp_rollout(l2pd_ctx* c, const int32_t* prompt_dev, const int32_t* 
   // the control block is looked at every few steps, as in l2pd_generate
   for (int k = 0; k < G;) {
     for (int i = 0; i < 4 && k < G; ++i, ++k) run_step(c, X, B, P, cfg, nullptr, state, -1, no_taps, s, 0, &egp);
-    launch_prepare(state, B, nb, ctl, s);
+    launch_prepare(state, B, nb, cfg->ragged, ctl, s);
     HIP_TRY(c, hipMemcpyAsync(c->pinned, ctl, CTL_WORDS * sizeof(int), hipMemcpyDeviceToHost, s));
     HIP_TRY(c, hipStreamSynchronize(s));
     if (c->pinned[CTL_ALL_DONE]) break;

@@ -1,0 +1,113 @@
+"""GPU tests for per-sequence block pointers: every sequence of a batch works on its own block instead
+of idling until the others finish the common one.  Tokens and per-sequence step counts must be what the
+lock-step batch (and the oracle, sequence by sequence) gives; only the number of forwards falls."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2509_25188_amd import binding as Bd
+from paper_2509_25188_amd import synth
+from tests import parity as Pz
+from tests.test_gpu_parity import build, small_bf16
+
+pytestmark = pytest.mark.gpu
+TINY = synth.WORKLOADS["tiny"].model
+
+
+def cfg_of(w, ragged):
+    bias = (w.model.eos_id, w.bias_from, w.bias_value) if w.bias_value else None
+    return Bd.Engine.cfg_struct(w.gen_len, w.block_len, w.threshold, Bd.EOTP_STEP if w.eotp_step else w.eotp,
+                                False, bias, False, ragged)
+
+
+def forwards(eng, prompt, fdev, cfg):
+    eng.profile_select(Bd.K_UPDATE)
+    out = eng.generate(prompt, fdev, cfg)
+    torch.cuda.synchronize()
+    n, _ = eng.profile_read()
+    eng.profile_select(Bd.K_NONE)
+    return out, n
+
+
+@pytest.mark.parametrize("eotp,eotp_step", [(False, False), (True, False), (True, True)])
+def test_ragged_batch_equals_lock_step_and_oracle_fp32(eotp, eotp_step):
+    w = synth.Workload("tiny_rag", TINY, 4, 13, 128, 32, 32, 0.5, eotp=eotp, eotp_step=eotp_step,
+                       bias_from=70 if eotp else -1, bias_value=60.0 if eotp else 0.0, prompt_hi=1022)
+    eng, ora, flt, prompt = build(w, lm_head_scale=25.0)
+    fdev = {k: v.cuda() for k, v in flt.items()}
+    (t0, s0, d0), n_lock = forwards(eng, prompt.cuda(), fdev, cfg_of(w, False))
+    (t1, s1, d1), n_rag = forwards(eng, prompt.cuda(), fdev, cfg_of(w, True))
+    assert torch.equal(t0, t1) and torch.equal(s0, s1) and torch.equal(d0, d1)
+    for b in range(w.batch):
+        resp, steps, dlen = Pz.oracle_generate(ora, prompt[b].numpy(), w, Pz.np_filter(flt))
+        np.testing.assert_array_equal(t1.cpu().numpy()[b], resp)
+        assert int(s1[b]) == steps and int(d1[b]) == dlen
+    steps = s1.cpu().numpy()
+    print(f"eotp={eotp} step={eotp_step}: steps per sequence {steps.tolist()}, forwards enqueued lock step {n_lock}, ragged {n_rag}")
+    # the host enqueues steps in chunks of 4 until the device reports completion
+    assert steps.max() <= n_rag <= steps.max() + 8
+    assert n_rag <= n_lock
+
+
+def test_ragged_denoise_step_sequences_at_different_blocks():
+    # two sequences imposed at different blocks in one call: each must get its own block's step
+    w = synth.Workload("tiny_rag2", TINY, 2, 13, 128, 32, 32, 0.5, bias_from=40, bias_value=5.0, prompt_hi=1022)
+    eng, ora, flt, prompt = build(w, lm_head_scale=25.0)
+    fdev = {k: v.cuda() for k, v in flt.items()}
+    blocks = [1, 3]
+    X = np.stack([Pz.random_state(w, 5 + b, blocks[b], 7 + 3 * b, b) for b in range(2)])
+    recs = [Pz.oracle_step_record(ora, X[b], w, Pz.np_filter(flt), blocks[b]) for b in range(2)]
+    Xd = torch.tensor(X, dtype=torch.int32, device="cuda")
+    state = torch.tensor([[blocks[0], 4, 0], [blocks[1], 9, 0]], dtype=torch.int32, device="cuda")
+    taps = eng.denoise_step(Xd, w.prompt_len, state, fdev, cfg_of(w, True), want_logits=True)
+    torch.cuda.synchronize()
+    rep = Pz.StepReport()
+    for b in range(2):
+        assert Pz.check_step(recs[b], taps, b, w.model, w.threshold, 1e-4, rep)
+        lo = w.prompt_len + blocks[b] * w.block_len
+        after = X[b].copy()
+        idx = np.nonzero(recs[b]["sel"])[0]
+        after[lo + idx] = recs[b]["pre"][idx]
+        np.testing.assert_array_equal(Xd.cpu().numpy()[b], after)
+    assert state.cpu().numpy()[:, 1].tolist() == [5, 10]
+    print("ragged denoise_step:", rep)
+
+
+def test_ragged_bf16_batch_rows_equal_lock_step():
+    w = small_bf16("bf_rag", 2, 256, 4, 64, 448, 2000, 5, 40, 128, 32, tau=0.7)
+    eng, ora, flt, prompt = build(w, lm_head_scale=25.0)
+    fdev = {k: v.cuda() for k, v in flt.items()}
+    (t0, s0, d0), n_lock = forwards(eng, prompt.cuda(), fdev, cfg_of(w, False))
+    (t1, s1, d1), n_rag = forwards(eng, prompt.cuda(), fdev, cfg_of(w, True))
+    # same kernels on the same rows: the sequences do not interact, so the bits agree
+    assert torch.equal(t0, t1) and torch.equal(s0, s1) and torch.equal(d0, d1)
+    print(f"bf16 batch of 5: steps {s1.tolist()}, forwards lock step {n_lock}, ragged {n_rag}")
+    assert n_rag <= n_lock
+
+
+def test_ragged_forward_count_matches_the_oracle_traces():
+    # fixed-threshold decoding spreads the per-block step counts of the sequences; the oracle's traces give
+    # the forwards each schedule needs: lock step = sum over blocks of the slowest sequence's steps in that
+    # block, own-block pointers = the slowest sequence's total
+    w = synth.Workload("tiny_rag3", TINY, 6, 13, 128, 16, 16, 0.5, prompt_hi=1022)
+    eng, ora, _, prompt = build(w, lm_head_scale=120.0)
+    flt = synth.threshold_filter(w.block_len, 0.9)
+    fdev = {k: v.cuda() for k, v in flt.items()}
+    per_block = np.zeros((w.batch, w.gen_len // w.block_len), dtype=np.int64)
+    want = []
+    for b in range(w.batch):
+        tr = []
+        want.append(Pz.oracle_generate(ora, prompt[b].numpy(), w, Pz.np_filter(flt), trace=tr))
+        for d in tr:
+            per_block[b, d["block"]] += 1
+    need_lock, need_rag = int(per_block.max(axis=0).sum()), int(per_block.sum(axis=1).max())
+    (t0, s0, _), n_lock = forwards(eng, prompt.cuda(), fdev, cfg_of(w, False))
+    (t1, s1, _), n_rag = forwards(eng, prompt.cuda(), fdev, cfg_of(w, True))
+    for b in range(w.batch):
+        np.testing.assert_array_equal(t1.cpu().numpy()[b], want[b][0])
+        assert int(s1[b]) == want[b][1] == int(s0[b])
+    assert torch.equal(t0, t1)
+    print(f"threshold decoding, batch of 6: steps {s1.tolist()}; forwards needed lock step {need_lock}, own blocks "
+          f"{need_rag}; enqueued {n_lock}, {n_rag}")
+    assert need_lock <= n_lock <= need_lock + 8 and need_rag <= n_rag <= need_rag + 8
+    assert need_rag < need_lock
