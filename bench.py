@@ -191,6 +191,28 @@ def pipeline(w, eng, prompt, cfg, seed, dev):
             "trained_filter_tokens_equal_to_reference": float((tok == ref).float().mean())}
 
 
+def batch_schedules(w, eng, prompt, flt, cfg):
+    """Whole generations of one batch under the three batch schedules (lock step, per-sequence block
+    pointers, pointers + compaction of the live sequences): same tokens, different number and size
+    of forwards."""
+    import torch
+    from paper_2509_25188_amd import binding as Bd
+    out, ref = {}, None
+    for name, mode in (("lock_step", Bd.RAGGED_OFF), ("own_blocks", Bd.RAGGED_BLOCKS), ("compact", Bd.RAGGED_COMPACT)):
+        cfg.ragged = mode
+        eng.generate(prompt, flt, cfg)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        tok, st, dl = eng.generate(prompt, flt, cfg)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        ref = tok if ref is None else ref
+        out[name] = {"generate_wall_s": dt, "tokens_per_s": int(dl.sum()) / dt,
+                     "steps_per_sequence": st.cpu().tolist(), "tokens_equal_lock_step": bool(torch.equal(tok, ref))}
+    cfg.ragged = Bd.RAGGED_OFF
+    return out
+
+
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "gate_up_gemm_hbm_traffic.txt")
 GEMM_SOURCE = os.path.join(ROOT, "paper_2509_25188_amd", "csrc", "gemm_bf16.hip")
 
@@ -233,6 +255,9 @@ def main():
     ap.add_argument("--pipeline", action="store_true",
                     help="also run the whole Learn2PD pipeline on the synthetic model: vanilla answer as reference, "
                          "EGP rollout, filter training, decode with the trained filter (adds a 'pipeline' object)")
+    ap.add_argument("--batch-schedules", action="store_true",
+                    help="also time whole generations of the batch in lock step, with per-sequence block "
+                         "pointers, and with batch compaction")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch a plain device copy of known size (reference for HBM counter runs)")
     args = ap.parse_args()
@@ -354,6 +379,8 @@ def main():
     }
     if args.pipeline:
         result["pipeline"] = pipeline(w, eng, prompt, cfg, args.seed, dev)
+    if args.batch_schedules:
+        result["batch_schedules"] = batch_schedules(w, eng, prompt, flt, cfg)
     if args.copy_calibration:
         n = 1 << 28
         src = torch.empty(n, dtype=torch.uint8, device=dev).fill_(1)

@@ -106,6 +106,18 @@ enum { L2PD_CACHE_NONE = 0, L2PD_CACHE_PREFIX = 1, L2PD_CACHE_DUAL = 2 };
  *     waits for the stream after every step, because the length sizes the next launches. */
 enum { L2PD_EOTP_OFF = 0, L2PD_EOTP_BLOCK = 1, L2PD_EOTP_STEP = 2 };
 
+/* Batches whose sequences finish blocks (or the decode) at different steps.  The paper decodes one
+ * sequence at a time; these are scheduling choices of a batched decoder and change no token.
+ *   L2PD_RAGGED_OFF     lock step: every sequence works on the smallest unfinished block index, one that is
+ *                       ahead idles until the others reach it.
+ *   L2PD_RAGGED_BLOCKS  every sequence works on its own block: same tokens and per-sequence step counts,
+ *                       fewer forwards.
+ *   L2PD_RAGGED_COMPACT as BLOCKS, and l2pd_generate moves the sequences that are still decoding to the
+ *                       leading rows whenever some have finished, so later forwards run over fewer rows
+ *                       (l2pd_denoise_step, and l2pd_generate with L2PD_EOTP_STEP, treat it as BLOCKS).
+ * Full recompute only (kv_cache must be L2PD_CACHE_NONE). */
+enum { L2PD_RAGGED_OFF = 0, L2PD_RAGGED_BLOCKS = 1, L2PD_RAGGED_COMPACT = 2 };
+
 /* Decode arguments of Alg. 2 / Alg. 3: generation length L_gen, block size s, threshold tau. */
 typedef struct {
   int32_t gen_len, block_len;       /* gen_len % block_len == 0, block_len <= 256 */
@@ -116,10 +128,7 @@ typedef struct {
   int32_t keep_kv;                  /* l2pd_denoise_step in a cached mode: 0 rebuilds the K/V store from the
                                        tokens first; 1 uses the store as the previous call left it (stepping
                                        through a block after a call that rebuilt it).  l2pd_generate ignores it. */
-  int32_t ragged;                   /* batches: 0 = lock step (every sequence works on the smallest unfinished
-                                       block index, one that is ahead idles); 1 = per-sequence block pointers
-                                       (every sequence works on its own block; same tokens and per-sequence step
-                                       counts, fewer forwards).  Full recompute only. */
+  int32_t ragged;                   /* L2PD_RAGGED_OFF, L2PD_RAGGED_BLOCKS or L2PD_RAGGED_COMPACT */
   l2pd_logit_bias bias;
 } l2pd_decode_cfg;
 

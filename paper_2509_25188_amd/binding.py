@@ -43,6 +43,7 @@ class LogitBias(C.Structure):
 
 CACHE_NONE, CACHE_PREFIX, CACHE_DUAL = 0, 1, 2
 EOTP_OFF, EOTP_BLOCK, EOTP_STEP = 0, 1, 2
+RAGGED_OFF, RAGGED_BLOCKS, RAGGED_COMPACT = 0, 1, 2
 
 
 class DecodeCfg(C.Structure):
@@ -176,7 +177,7 @@ class Engine:
         b = LogitBias(0, 0, 0.0) if bias is None else LogitBias(int(bias[0]), int(bias[1]), float(bias[2]))
         if prefix_cache and dual_cache:
             raise ValueError("prefix_cache and dual_cache are alternatives")
-        return DecodeCfg(gen_len, block_len, threshold, int(eotp), CACHE_DUAL if dual_cache else int(bool(prefix_cache)), 0, int(bool(ragged)), b)
+        return DecodeCfg(gen_len, block_len, threshold, int(eotp), CACHE_DUAL if dual_cache else int(bool(prefix_cache)), 0, int(ragged), b)
 
     # ---- entry points ----
     def forward(self, tokens: torch.Tensor, row_begin: int = 0, row_count: Optional[int] = None) -> torch.Tensor:

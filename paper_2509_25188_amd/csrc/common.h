@@ -74,8 +74,12 @@ struct UpdateArgs {
   int gen_len;
 };
 void launch_update(const UpdateArgs& a, Gate g, hipStream_t s);
-void launch_finalize(const int32_t* X, const int32_t* state, const int* teff, int B, int P, int G, int s_len,
-                     int mask_id, int32_t* tokens_out, int32_t* steps_out, int32_t* dlen_out, hipStream_t s);
+void launch_finalize(const int32_t* X, const int32_t* state, const int* teff, const int32_t* perm, int B, int P,
+                     int G, int s_len, int mask_id, int32_t* tokens_out, int32_t* steps_out, int32_t* dlen_out,
+                     hipStream_t s);
+// live sequences to the leading rows (stable), src copies -> dst copies; perm_src nullptr = identity
+void launch_compact(const int32_t* X_src, int32_t* X_dst, const int32_t* state_src, int32_t* state_dst,
+                    const int32_t* perm_src, int32_t* perm_dst, int B, int T, hipStream_t s);
 // `epochs` full-batch AdamW steps on the binary cross-entropy of Eq. 6 for the two-layer filter, in place.
 struct TrainArgs {
   float *w1, *b1, *w2, *b2;   // device, updated in place

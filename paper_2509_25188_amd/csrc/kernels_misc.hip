@@ -58,10 +58,11 @@ void launch_init_decode(int32_t* X, const int32_t* prompt, int B, int P, int G, 
 // while another sequence finishes the common block.
 __global__ void k_prepare(const int32_t* state, int B, int n_blocks, int ragged, int* ctl) {
   if (threadIdx.x == 0 && blockIdx.x == 0) {
-    int gb = n_blocks, all_done = 1;
+    int gb = n_blocks, all_done = 1, n_active = 0;
     for (int b = 0; b < B; ++b) {
       if (!state[b * 3 + 2]) {
         all_done = 0;
+        ++n_active;
         int bi = state[b * 3 + 0];
         gb = bi < gb ? bi : gb;
       }
@@ -70,6 +71,7 @@ __global__ void k_prepare(const int32_t* state, int B, int n_blocks, int ragged,
     const int last = n_blocks > 0 ? n_blocks - 1 : 0;
     ctl[CTL_GB] = all_done ? last : gb;
     ctl[CTL_ALL_DONE] = all_done;
+    ctl[CTL_ACTIVE] = all_done ? 0 : n_active;
     for (int b = 0; b < B; ++b) {
       const int own = state[b * 3 + 0] < last ? state[b * 3 + 0] : last;
       ctl[CTL_SEQ_GB + b] = ragged ? own : ctl[CTL_GB];
@@ -78,6 +80,44 @@ __global__ void k_prepare(const int32_t* state, int B, int n_blocks, int ragged,
 }
 void launch_prepare(const int32_t* state, int B, int n_blocks, int ragged, int* ctl, hipStream_t s) {
   hipLaunchKernelGGL(k_prepare, dim3(1), dim3(64), 0, s, state, B, n_blocks, ragged, ctl);
+}
+
+// Batch compaction: rows of sequences that are not done move to the front (order kept), finished
+// ones behind them (order kept), so that later steps run over the leading rows only.  Reads the
+// `src` copies of tokens / state / row->sequence map and writes the `dst` copies; perm_src == nullptr
+// stands for the identity map.  Every workgroup works out the source row of its own destination row.
+__global__ void __launch_bounds__(256) k_compact(const int32_t* X_src, int32_t* X_dst, const int32_t* state_src,
+                                                 int32_t* state_dst, const int32_t* perm_src, int32_t* perm_dst,
+                                                 int B, int T) {
+  __shared__ int s_from;
+  const int r = blockIdx.y;
+  if (threadIdx.x == 0) {
+    int n_live = 0;
+    for (int b = 0; b < B; ++b) n_live += state_src[b * 3 + 2] ? 0 : 1;
+    // destination rows [0, n_live) take the live rows in order, the rest the finished rows in order
+    const bool want_done = r >= n_live;
+    int k = want_done ? r - n_live : r, from = 0;
+    for (int b = 0; b < B; ++b) {
+      if ((state_src[b * 3 + 2] != 0) == want_done) {
+        if (k == 0) { from = b; break; }
+        --k;
+      }
+    }
+    s_from = from;
+  }
+  __syncthreads();
+  const int from = s_from;
+  for (int t = blockIdx.x * 256 + threadIdx.x; t < T; t += gridDim.x * 256)
+    X_dst[(size_t)r * T + t] = X_src[(size_t)from * T + t];
+  if (blockIdx.x == 0 && threadIdx.x < 3) state_dst[r * 3 + threadIdx.x] = state_src[from * 3 + threadIdx.x];
+  if (blockIdx.x == 0 && threadIdx.x == 3) perm_dst[r] = perm_src ? perm_src[from] : from;
+}
+void launch_compact(const int32_t* X_src, int32_t* X_dst, const int32_t* state_src, int32_t* state_dst,
+                    const int32_t* perm_src, int32_t* perm_dst, int B, int T, hipStream_t s) {
+  int gx = (T + 255) / 256;
+  if (gx > 8) gx = 8;
+  hipLaunchKernelGGL(k_compact, dim3(gx, B), dim3(256), 0, s, X_src, X_dst, state_src, state_dst, perm_src, perm_dst,
+                     B, T);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -591,26 +631,30 @@ void launch_update(const UpdateArgs& a, Gate g, hipStream_t s) {
 
 // response_i = X[P : P+G], steps, decoded length
 // With `teff` (step-granular EoTP) the decoded length is the shortened sequence's response part and
-// discarded positions come back as mask_id.
-__global__ void k_finalize(const int32_t* X, const int32_t* state, const int* teff, int B, int P, int G, int s_len,
-                           int mask_id, int32_t* tokens_out, int32_t* steps_out, int32_t* dlen_out) {
+// discarded positions come back as mask_id.  `perm` (after batch compaction; nullptr = identity) maps
+// a row of X / state to the sequence it holds: outputs go to that sequence's slot.
+__global__ void k_finalize(const int32_t* X, const int32_t* state, const int* teff, const int32_t* perm, int B, int P,
+                           int G, int s_len, int mask_id, int32_t* tokens_out, int32_t* steps_out,
+                           int32_t* dlen_out) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (tokens_out && i < B * G) {
     int b = i / G, t = i % G;
     int v = X[(size_t)b * (P + G) + P + t];
     if (teff && P + t >= teff[b]) v = mask_id;
-    tokens_out[i] = v;
+    tokens_out[(size_t)(perm ? perm[b] : b) * G + t] = v;
   }
   if (i < B) {
-    if (steps_out) steps_out[i] = state[i * 3 + 1];
-    if (dlen_out) dlen_out[i] = teff ? teff[i] - P : state[i * 3 + 0] * s_len;
+    const int o = perm ? perm[i] : i;
+    if (steps_out) steps_out[o] = state[i * 3 + 1];
+    if (dlen_out) dlen_out[o] = teff ? teff[i] - P : state[i * 3 + 0] * s_len;
   }
 }
-void launch_finalize(const int32_t* X, const int32_t* state, const int* teff, int B, int P, int G, int s_len,
-                     int mask_id, int32_t* tokens_out, int32_t* steps_out, int32_t* dlen_out, hipStream_t s) {
+void launch_finalize(const int32_t* X, const int32_t* state, const int* teff, const int32_t* perm, int B, int P,
+                     int G, int s_len, int mask_id, int32_t* tokens_out, int32_t* steps_out, int32_t* dlen_out,
+                     hipStream_t s) {
   int n = B * G;
-  hipLaunchKernelGGL(k_finalize, dim3((n + 255) / 256), dim3(256), 0, s, X, state, teff, B, P, G, s_len, mask_id,
-                     tokens_out, steps_out, dlen_out);
+  hipLaunchKernelGGL(k_finalize, dim3((n + 255) / 256), dim3(256), 0, s, X, state, teff, perm, B, P, G, s_len,
+                     mask_id, tokens_out, steps_out, dlen_out);
 }
 
 // Step-granular EoTP (Sec. 3.3): teff[b] = index after the first end-of-text token of sequence b's

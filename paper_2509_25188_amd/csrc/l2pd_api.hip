@@ -25,7 +25,7 @@ struct Carver {
 
 struct Layout {
   // offsets into the workspace
-  size_t cos_t, sin_t, ctl, state, teff, X, h, xn, q, attn, act, parts, attn_ws, attn_ws_bytes, kstore, vstore, tmp_k, tmp_v, gate_up,
+  size_t cos_t, sin_t, ctl, state, state2, perm, perm2, teff, X, X2, h, xn, q, attn, act, parts, attn_ws, attn_ws_bytes, kstore, vstore, tmp_k, tmp_v, gate_up,
       xn_head, logits, part_max, part_sum, part_idx, conf, pred, total;
   size_t kv_layer_stride_k, kv_layer_stride_v;
   int Tpad, n_part, lm_chunk;
@@ -101,8 +101,12 @@ Layout make_layout(const l2pd_model_desc& m, int max_batch, int max_seq, int cac
   L.sin_t = c.take((size_t)L.Tpad * (m.head_dim / 2) * 4);
   L.ctl = c.take((size_t)(CTL_WORDS + max_batch) * 4);
   L.state = c.take((size_t)max_batch * 3 * 4);
+  L.state2 = c.take((size_t)max_batch * 3 * 4);   // second copies for batch compaction
+  L.perm = c.take((size_t)max_batch * 4);
+  L.perm2 = c.take((size_t)max_batch * 4);
   L.teff = c.take((size_t)max_batch * 4);
   L.X = c.take(rows * 4);
+  L.X2 = c.take(rows * 4);
   L.h = c.take(rows * d * 4);
   L.xn = c.take(rows * d * es);
   L.q = c.take(rows * d * es);
@@ -380,7 +384,7 @@ int check_decode_args(const l2pd_ctx* c, int B, int P, const l2pd_decode_cfg* cf
   if (cfg->kv_cache && !c->cache) return L2PD_EINVAL;
   if (cfg->eotp < 0 || cfg->eotp > L2PD_EOTP_STEP) return L2PD_EINVAL;
   if (cfg->eotp == L2PD_EOTP_STEP && cfg->kv_cache) return L2PD_ENOTIMPL;   // shortened sequences: full recompute only
-  if (cfg->ragged < 0 || cfg->ragged > 1) return L2PD_EINVAL;
+  if (cfg->ragged < 0 || cfg->ragged > L2PD_RAGGED_COMPACT) return L2PD_EINVAL;
   if (cfg->ragged && cfg->kv_cache) return L2PD_ENOTIMPL;   // the K/V stores are rebuilt for one common block
   if (cfg->bias.value != 0.f && (cfg->bias.token_id < 0 || cfg->bias.token_id >= c->m.vocab)) return L2PD_EINVAL;
   if (isnan(cfg->bias.value)) return L2PD_EINVAL;
@@ -634,13 +638,21 @@ int32_t l2pd_generate(l2pd_ctx* c, const int32_t* prompt_dev, int32_t B, int32_t
 
   // Enqueue `CHUNK` steps, then a copy of the control block to pinned memory; look at the copy of
   // the chunk before, so the device always has a chunk queued while the host waits.
+  // Batch compaction (cfg->ragged == L2PD_RAGGED_COMPACT): when the control block shows fewer live
+  // sequences than rows in flight, they are moved to the leading rows and the following steps run
+  // over those rows only.  The count read is the state of a chunk ago; sequences only ever finish,
+  // so the leading `count` rows of a later compaction hold every sequence still live.
+  int Bc = B;
+  int32_t *X_alt = c->at<int32_t>(L.X2), *state_alt = c->at<int32_t>(L.state2);
+  int32_t *perm = nullptr, *perm_alt = c->at<int32_t>(L.perm);
+  const bool compacting = cfg->ragged == L2PD_RAGGED_COMPACT && B > 1;
   auto run_until = [&](int host_gb, int max_steps) -> int {   // returns 1 when everything is done
     int issued = 0, slot = 0;
     bool have_prev = false;
     while (issued < max_steps) {
       for (int i = 0; i < CHUNK && issued < max_steps; ++i, ++issued)
-        run_step(c, X, B, P, cfg, f, state, host_gb, no_taps, s);
-      launch_prepare(state, B, nb, cfg->ragged, ctl, s);
+        run_step(c, X, Bc, P, cfg, f, state, host_gb, no_taps, s);
+      launch_prepare(state, Bc, nb, cfg->ragged, ctl, s);
       if (hipMemcpyAsync(c->pinned + slot * CTL_WORDS, ctl, CTL_WORDS * sizeof(int), hipMemcpyDeviceToHost, s) !=
               hipSuccess ||
           hipEventRecord(c->poll_ev[slot], s) != hipSuccess)
@@ -651,6 +663,14 @@ int32_t l2pd_generate(l2pd_ctx* c, const int32_t* prompt_dev, int32_t B, int32_t
         const int* pc = c->pinned + prev * CTL_WORDS;
         if (pc[CTL_ALL_DONE]) return 1;
         if (host_gb >= 0 && pc[CTL_GB] != host_gb) return 0;
+        if (compacting && pc[CTL_ACTIVE] > 0 && pc[CTL_ACTIVE] < Bc) {
+          launch_compact(X, X_alt, state, state_alt, perm, perm_alt, B, P + G, s);
+          std::swap(X, X_alt);
+          std::swap(state, state_alt);
+          if (!perm) perm = c->at<int32_t>(L.perm2);   // first compaction: identity in, L.perm out
+          std::swap(perm, perm_alt);
+          Bc = pc[CTL_ACTIVE];
+        }
       }
       have_prev = true;
       slot ^= 1;
@@ -685,8 +705,8 @@ int32_t l2pd_generate(l2pd_ctx* c, const int32_t* prompt_dev, int32_t B, int32_t
     int r = run_until(-1, G);      // at most gen_len steps in total
     if (r < 0) { c->last_hip_error = (int)hipGetLastError(); return L2PD_EHIP; }
   }
-  launch_finalize(X, state, step_eotp ? c->at<int>(L.teff) : nullptr, B, P, G, sl, c->m.mask_id, tokens_out_dev,
-                  steps_out_dev, decoded_len_out_dev, s);
+  launch_finalize(X, state, step_eotp ? c->at<int>(L.teff) : nullptr, perm, B, P, G, sl, c->m.mask_id,
+                  tokens_out_dev, steps_out_dev, decoded_len_out_dev, s);
   HIP_TRY(c, hipGetLastError());
   return L2PD_OK;
 }
@@ -724,7 +744,7 @@ int32_t l2pd_egp_rollout(l2pd_ctx* c, const int32_t* prompt_dev, const int32_t* 
     HIP_TRY(c, hipStreamSynchronize(s));
     if (c->pinned[CTL_ALL_DONE]) break;
   }
-  launch_finalize(X, state, nullptr, B, P, G, sl, c->m.mask_id, nullptr, steps_out_dev, nullptr, s);
+  launch_finalize(X, state, nullptr, nullptr, B, P, G, sl, c->m.mask_id, nullptr, steps_out_dev, nullptr, s);
   HIP_TRY(c, hipGetLastError());
   return L2PD_OK;
 }

@@ -78,6 +78,7 @@ WORKLOADS: Dict[str, Workload] = {
     "tiny": Workload("tiny", _TINY, 1, 32, 64, 32, 64, 0.5, prompt_hi=1022),
     "mid": Workload("mid", _MID, 8, 128, 256, 32, 128, 0.7, prompt_hi=31998),
     "8b_g256": Workload("8b_g256", _8B, 1, 256, 256, 32, 128, 0.9, prompt_hi=126081),
+    "8b_b8_g256": Workload("8b_b8_g256", _8B, 8, 256, 256, 32, 128, 0.9, prompt_hi=126081),
     "8b_g1024_eotp": Workload("8b_g1024_eotp", _8B, 1, 256, 1024, 32, 128, 0.9, eotp=True,
                               bias_from=300, bias_value=20.0, prompt_hi=126081),
     "8b_g1024_eotp_step": Workload("8b_g1024_eotp_step", _8B, 1, 256, 1024, 32, 128, 0.9, eotp=True, eotp_step=True,

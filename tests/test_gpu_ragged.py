@@ -29,14 +29,15 @@ def forwards(eng, prompt, fdev, cfg):
     return out, n
 
 
+@pytest.mark.parametrize("mode", [Bd.RAGGED_BLOCKS, Bd.RAGGED_COMPACT])
 @pytest.mark.parametrize("eotp,eotp_step", [(False, False), (True, False), (True, True)])
-def test_ragged_batch_equals_lock_step_and_oracle_fp32(eotp, eotp_step):
+def test_ragged_batch_equals_lock_step_and_oracle_fp32(eotp, eotp_step, mode):
     w = synth.Workload("tiny_rag", TINY, 4, 13, 128, 32, 32, 0.5, eotp=eotp, eotp_step=eotp_step,
                        bias_from=70 if eotp else -1, bias_value=60.0 if eotp else 0.0, prompt_hi=1022)
     eng, ora, flt, prompt = build(w, lm_head_scale=25.0)
     fdev = {k: v.cuda() for k, v in flt.items()}
     (t0, s0, d0), n_lock = forwards(eng, prompt.cuda(), fdev, cfg_of(w, False))
-    (t1, s1, d1), n_rag = forwards(eng, prompt.cuda(), fdev, cfg_of(w, True))
+    (t1, s1, d1), n_rag = forwards(eng, prompt.cuda(), fdev, cfg_of(w, mode))
     assert torch.equal(t0, t1) and torch.equal(s0, s1) and torch.equal(d0, d1)
     for b in range(w.batch):
         resp, steps, dlen = Pz.oracle_generate(ora, prompt[b].numpy(), w, Pz.np_filter(flt))
@@ -73,12 +74,13 @@ def test_ragged_denoise_step_sequences_at_different_blocks():
     print("ragged denoise_step:", rep)
 
 
-def test_ragged_bf16_batch_rows_equal_lock_step():
+@pytest.mark.parametrize("mode", [Bd.RAGGED_BLOCKS, Bd.RAGGED_COMPACT])
+def test_ragged_bf16_batch_rows_equal_lock_step(mode):
     w = small_bf16("bf_rag", 2, 256, 4, 64, 448, 2000, 5, 40, 128, 32, tau=0.7)
     eng, ora, flt, prompt = build(w, lm_head_scale=25.0)
     fdev = {k: v.cuda() for k, v in flt.items()}
     (t0, s0, d0), n_lock = forwards(eng, prompt.cuda(), fdev, cfg_of(w, False))
-    (t1, s1, d1), n_rag = forwards(eng, prompt.cuda(), fdev, cfg_of(w, True))
+    (t1, s1, d1), n_rag = forwards(eng, prompt.cuda(), fdev, cfg_of(w, mode))
     # same kernels on the same rows: the sequences do not interact, so the bits agree
     assert torch.equal(t0, t1) and torch.equal(s0, s1) and torch.equal(d0, d1)
     print(f"bf16 batch of 5: steps {s1.tolist()}, forwards lock step {n_lock}, ragged {n_rag}")
@@ -102,11 +104,14 @@ def test_ragged_forward_count_matches_the_oracle_traces():
             per_block[b, d["block"]] += 1
     need_lock, need_rag = int(per_block.max(axis=0).sum()), int(per_block.sum(axis=1).max())
     (t0, s0, _), n_lock = forwards(eng, prompt.cuda(), fdev, cfg_of(w, False))
-    (t1, s1, _), n_rag = forwards(eng, prompt.cuda(), fdev, cfg_of(w, True))
+    (t1, s1, _), n_rag = forwards(eng, prompt.cuda(), fdev, cfg_of(w, Bd.RAGGED_BLOCKS))
+    (t2, s2, d2), n_cmp = forwards(eng, prompt.cuda(), fdev, cfg_of(w, Bd.RAGGED_COMPACT))
     for b in range(w.batch):
         np.testing.assert_array_equal(t1.cpu().numpy()[b], want[b][0])
-        assert int(s1[b]) == want[b][1] == int(s0[b])
-    assert torch.equal(t0, t1)
+        np.testing.assert_array_equal(t2.cpu().numpy()[b], want[b][0])
+        assert int(s1[b]) == want[b][1] == int(s0[b]) == int(s2[b])
+        assert int(d2[b]) == want[b][2]
+    assert torch.equal(t0, t1) and n_cmp == n_rag
     print(f"threshold decoding, batch of 6: steps {s1.tolist()}; forwards needed lock step {need_lock}, own blocks "
           f"{need_rag}; enqueued {n_lock}, {n_rag}")
     assert need_lock <= n_lock <= need_lock + 8 and need_rag <= n_rag <= need_rag + 8
