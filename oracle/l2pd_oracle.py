@@ -16,6 +16,8 @@ What it states, in the paper's order and notation:
 * confidence       conf_j = p_theta(pre_j | X)            (Eq. 4);
 * the filter       p = sigmoid(f_theta(conf)), f_theta a two-layer MLP on the
   block's confidence vector (Sec. 3.2; Sec. 4.1: 2,112 parameters at block 32);
+  the single- and four-layer filters of Table 3 are read as the same MLP with
+  no, resp. three, hidden layers (ReLU between layers; the paper gives no widths);
 * the inference loop: blocks left to right, `while M != {}` per block, unmask j
   when p_j > tau (Alg. 2);
 * End-of-Text Prediction: after a block's loop ends, stop if an end-of-text
@@ -26,7 +28,7 @@ What it states, in the paper's order and notation:
   the next step runs on the shortened sequence;
 * the Extremely Greedy Parallel rollout that labels training data (Sec. 3.1.3,
   Alg. 1 without its update line), the binary cross-entropy of Eq. 6 with its
-  gradient for the two-layer filter, and AdamW (Sec. 4.1 names the optimiser,
+  gradient for a filter of any depth, and AdamW (Sec. 4.1 names the optimiser,
   learning rate 1e-3 and 5,000 epochs; the update rule is the published one);
 * the prefix KV cache variant (Sec. 4.3 names the technique only): K/V of the
   prompt and finished blocks come from a forward over that prefix alone and
@@ -273,16 +275,31 @@ def conf_pre(logits, mask_id):
 
 
 # --------------------------------------------------------------------------- filter f_theta (Sec. 3.2)
+def filter_depth(flt):
+    """Number of layers of a filter given as {"w1", "b1", ..., "wN", "bN"}."""
+    n = 0
+    while f"w{n + 1}" in flt:
+        n += 1
+    assert n >= 1 and all(f"b{k}" in flt for k in range(1, n + 1))
+    return n
+
+
 def filter_prob(conf_in, flt):
-    """sigmoid(W2 relu(W1 c + b1) + b2) for the block's confidence vector c."""
+    """The filter's output for the block's confidence vector c: an MLP with ReLU between its layers
+    and a sigmoid at the end.  Two layers, sigmoid(W2 relu(W1 c + b1) + b2), is the paper's filter
+    (Sec. 3.2, Sec. 4.1); one layer, sigmoid(W1 c + b1), and four are the variants of Table 3."""
     dt = conf_in.dtype
-    h = np.maximum(widen(flt["w1"], dt) @ conf_in + widen(flt["b1"], dt), 0)
-    z = widen(flt["w2"], dt) @ h + widen(flt["b2"], dt)
+    n = filter_depth(flt)
+    a = conf_in
+    for k in range(1, n):
+        a = np.maximum(widen(flt[f"w{k}"], dt) @ a + widen(flt[f"b{k}"], dt), 0)
+    z = widen(flt[f"w{n}"], dt) @ a + widen(flt[f"b{n}"], dt)
     return sigmoid(z)
 
 
-def filter_param_count(block_len, hidden):
-    return hidden * block_len + hidden + block_len * hidden + block_len
+def filter_param_count(block_len, hidden, n_layers=2):
+    dims = [block_len] + [hidden] * (n_layers - 1) + [block_len]
+    return sum(dims[k + 1] * dims[k] + dims[k + 1] for k in range(n_layers))
 
 
 # --------------------------------------------------------------------------- one denoising step (Alg. 2 loop body)
@@ -477,21 +494,28 @@ def egp_rollout(model, prompt, reference, gen_len, block_len, mask_id, bias=None
 # --------------------------------------------------------------------------- Eq. 6 and the optimiser
 def bce_loss_and_grad(flt, C, Y):
     """Mean binary cross-entropy (Eq. 6) of sigmoid(f_theta(c)) against y over all entries of the
-    rows C[n, s], Y[n, s], and its gradient with respect to w1, b1, w2, b2."""
+    rows C[n, s], Y[n, s], and its gradient with respect to every w_k, b_k of the filter."""
     C = np.asarray(C, dtype=np.float64)
     Y = np.asarray(Y, dtype=np.float64)
-    w1, b1, w2, b2 = (np.asarray(flt[k], dtype=np.float64) for k in ("w1", "b1", "w2", "b2"))
-    A = C @ w1.T + b1                       # [n, hidden]
-    H = np.maximum(A, 0.0)
-    Z = H @ w2.T + b2                       # [n, s]
+    n = filter_depth(flt)
+    W = [None] + [np.asarray(flt[f"w{k}"], dtype=np.float64) for k in range(1, n + 1)]
+    Bv = [None] + [np.asarray(flt[f"b{k}"], dtype=np.float64) for k in range(1, n + 1)]
+    acts = [C]                               # acts[k] = input of layer k+1, rows [n, width]
+    pre = [None]                             # pre[k] = pre-activation of layer k
+    for k in range(1, n):
+        pre.append(acts[-1] @ W[k].T + Bv[k])
+        acts.append(np.maximum(pre[-1], 0.0))
+    Z = acts[-1] @ W[n].T + Bv[n]            # [n, s]
     m = Z.size
     # -[y log sigma(z) + (1 - y) log(1 - sigma(z))] = softplus(z) - y z
     loss = float(np.sum(np.maximum(Z, 0.0) + np.log1p(np.exp(-np.abs(Z))) - Y * Z) / m)
-    dZ = (sigmoid(Z) - Y) / m
-    g = {"w2": dZ.T @ H, "b2": dZ.sum(axis=0)}
-    dH = (dZ @ w2) * (A > 0.0)
-    g["w1"] = dH.T @ C
-    g["b1"] = dH.sum(axis=0)
+    d = (sigmoid(Z) - Y) / m                 # dL/d(pre-activation) of the layer at hand
+    g = {}
+    for k in range(n, 0, -1):
+        g[f"w{k}"] = d.T @ acts[k - 1]
+        g[f"b{k}"] = d.sum(axis=0)
+        if k > 1:
+            d = (d @ W[k]) * (pre[k - 1] > 0.0)
     return loss, g
 
 
@@ -507,7 +531,8 @@ def adamw_step(param, grad, m, v, t, lr, beta1=0.9, beta2=0.999, eps=1e-8, weigh
 
 def train_filter(flt, C, Y, epochs, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01):
     """`epochs` full-batch AdamW steps on Eq. 6.  Returns (filter, losses[epochs]) in float64."""
-    th = {k: np.array(flt[k], dtype=np.float64) for k in ("w1", "b1", "w2", "b2")}
+    n = filter_depth(flt)
+    th = {f"{c}{k}": np.array(flt[f"{c}{k}"], dtype=np.float64) for k in range(1, n + 1) for c in "wb"}
     m = {k: np.zeros_like(x) for k, x in th.items()}
     v = {k: np.zeros_like(x) for k, x in th.items()}
     losses = []

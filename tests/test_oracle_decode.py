@@ -85,6 +85,45 @@ def test_filter_hand_example():
 def test_filter_param_count_matches_paper():
     g = golden()
     assert O.filter_param_count(32, 32) == int(g["filter_params_block32"])
+    # the depth variants of Table 3 at the same widths: one 32x32 layer with its bias, and four
+    assert O.filter_param_count(32, 32, 1) == 32 * 32 + 32
+    assert O.filter_param_count(32, 32, 4) == 2 * int(g["filter_params_block32"])
+
+
+def deep_filter(s, h, n_layers, seed):
+    r = np.random.default_rng(seed)
+    dims = [s] + [h] * (n_layers - 1) + [s]
+    f = {}
+    for k in range(n_layers):
+        f[f"w{k + 1}"] = r.normal(size=(dims[k + 1], dims[k]))
+        f[f"b{k + 1}"] = r.normal(size=dims[k + 1])
+    return f
+
+
+def test_filter_depth_variants_reduce_to_the_two_layer_filter():
+    # confidences are >= 0, so a first layer (I, 0) passes them through its ReLU unchanged: the
+    # single-layer filter (W, b) equals the two-layer filter (I, 0, W, b)
+    r = np.random.default_rng(61)
+    s = 6
+    c = r.uniform(size=s)
+    one = deep_filter(s, s, 1, 62)
+    two = dict(w1=np.eye(s), b1=np.zeros(s), w2=one["w1"], b2=one["b1"])
+    np.testing.assert_allclose(O.filter_prob(c, one), O.filter_prob(c, two), rtol=1e-14)
+    # hidden activations are >= 0 as well: identity layers in the middle of a four-layer filter
+    # leave the two-layer filter around them
+    h = 5
+    base = deep_filter(s, h, 2, 63)
+    four = dict(w1=base["w1"], b1=base["b1"], w2=np.eye(h), b2=np.zeros(h), w3=np.eye(h), b3=np.zeros(h),
+                w4=base["w2"], b4=base["b2"])
+    np.testing.assert_allclose(O.filter_prob(c, four), O.filter_prob(c, base), rtol=1e-14)
+    # and a generic four-layer filter against scalar loops
+    f4 = deep_filter(s, h, 4, 64)
+    a = list(c)
+    for k in (1, 2, 3):
+        w, b = f4[f"w{k}"], f4[f"b{k}"]
+        a = [max(0.0, b[i] + sum(w[i][j] * a[j] for j in range(len(a)))) for i in range(len(b))]
+    z = [f4["b4"][i] + sum(f4["w4"][i][j] * a[j] for j in range(h)) for i in range(s)]
+    np.testing.assert_allclose(O.filter_prob(c, f4), [1 / (1 + math.exp(-v)) for v in z], rtol=1e-13)
 
 
 # ----------------------------------------------------------------- Alg. 2 invariants and special cases
@@ -437,9 +476,10 @@ def tiny_filter(s, h, seed):
     return dict(w1=r.normal(size=(h, s)), b1=r.normal(size=h), w2=r.normal(size=(s, h)), b2=r.normal(size=s))
 
 
-def test_bce_gradient_matches_central_differences():
+@pytest.mark.parametrize("n_layers", [1, 2, 4])
+def test_bce_gradient_matches_central_differences(n_layers):
     s, h, n = 5, 4, 7
-    flt = tiny_filter(s, h, 51)
+    flt = tiny_filter(s, h, 51) if n_layers == 2 else deep_filter(s, h, n_layers, 51)
     r = np.random.default_rng(52)
     C, Y = r.uniform(size=(n, s)), (r.uniform(size=(n, s)) > 0.4).astype(float)
     loss, g = O.bce_loss_and_grad(flt, C, Y)
@@ -450,7 +490,7 @@ def test_bce_gradient_matches_central_differences():
         tot -= np.sum(Y[i] * np.log(p) + (1 - Y[i]) * np.log(1 - p))
     assert abs(loss - tot / (n * s)) < 1e-12
     eps = 1e-6
-    for k in ("w1", "b1", "w2", "b2"):
+    for k in flt:
         num = np.zeros_like(flt[k])
         it = np.nditer(flt[k], flags=["multi_index"])
         for _ in it:
@@ -460,6 +500,50 @@ def test_bce_gradient_matches_central_differences():
                 f2[k][idx] += sign * eps
                 num[idx] += sign * O.bce_loss_and_grad(f2, C, Y)[0]
         np.testing.assert_allclose(g[k], num / (2 * eps), rtol=1e-5, atol=1e-8)
+
+
+def test_single_layer_bce_gradient_is_the_logistic_regression_gradient():
+    # one layer: z = W c + b, and the textbook gradient of the mean log loss is (sigma(z) - y) c^T / m
+    s, n = 4, 6
+    flt = deep_filter(s, s, 1, 57)
+    r = np.random.default_rng(58)
+    C, Y = r.uniform(size=(n, s)), (r.uniform(size=(n, s)) > 0.5).astype(float)
+    _, g = O.bce_loss_and_grad(flt, C, Y)
+    gw, gb = np.zeros((s, s)), np.zeros(s)
+    for i in range(n):
+        for j in range(s):
+            z = flt["b1"][j] + sum(flt["w1"][j][t] * C[i][t] for t in range(s))
+            e = 1 / (1 + math.exp(-z)) - Y[i][j]
+            gb[j] += e / (n * s)
+            for t in range(s):
+                gw[j][t] += e * C[i][t] / (n * s)
+    np.testing.assert_allclose(g["w1"], gw, rtol=1e-12)
+    np.testing.assert_allclose(g["b1"], gb, rtol=1e-12)
+
+
+@pytest.mark.parametrize("n_layers", [1, 4])
+def test_training_of_depth_variants_agrees_with_the_library(n_layers):
+    import torch
+    s, h, n = 6, 5, 9
+    flt = deep_filter(s, h, n_layers, 55)
+    r = np.random.default_rng(56)
+    C, Y = r.uniform(size=(n, s)), (r.uniform(size=(n, s)) > 0.5).astype(float)
+    mine, losses = O.train_filter(flt, C, Y, 60, lr=1e-2)
+    tp = {k: torch.tensor(v, dtype=torch.float64, requires_grad=True) for k, v in flt.items()}
+    opt = torch.optim.AdamW(list(tp.values()), lr=1e-2, betas=(0.9, 0.999), eps=1e-8, weight_decay=0.01)
+    Ct, Yt = torch.tensor(C), torch.tensor(Y)
+    for _ in range(60):
+        opt.zero_grad()
+        a = Ct
+        for k in range(1, n_layers):
+            a = torch.relu(a @ tp[f"w{k}"].T + tp[f"b{k}"])
+        z = a @ tp[f"w{n_layers}"].T + tp[f"b{n_layers}"]
+        torch.nn.functional.binary_cross_entropy_with_logits(z, Yt).backward()
+        opt.step()
+    assert set(mine) == set(tp)
+    for k in mine:
+        np.testing.assert_allclose(mine[k], tp[k].detach().numpy(), rtol=1e-8, atol=1e-10)
+    assert losses[-1] < losses[0]
 
 
 def test_adamw_first_step_closed_form_and_library_agreement():
