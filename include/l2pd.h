@@ -70,14 +70,18 @@ typedef struct {
   const void* const* w_down;        /* each [d_model, d_ffn] */
 } l2pd_weights;
 
-/* The filter f_theta (Sec. 3.2; Sec. 4.1 "two-layer MLP"): p = sigmoid(W2 relu(W1 c + b1) + b2),
- * c = the block's confidence vector.  All fp32, device memory.  in_dim must equal block_len. */
+/* The filter f_theta (Sec. 3.2; Sec. 4.1 "two-layer MLP"): an MLP on c, the block's confidence
+ * vector, with ReLU between its layers and a sigmoid on its output.  n_layers = 2 is the paper's filter,
+ * p = sigmoid(W2 relu(W1 c + b1) + b2); 1 (p = sigmoid(W1 c + b1)) and 4 are the variants of Table 3,
+ * any depth up to L2PD_FILTER_MAX_LAYERS is taken.  Layer k (0-based) maps width in_k to out_k, where
+ * in_0 = out_{n_layers-1} = in_dim and every other width is `hidden`.  All fp32, device memory.
+ * in_dim must equal block_len. */
+#define L2PD_FILTER_MAX_LAYERS 4
 typedef struct {
-  int32_t in_dim, hidden;           /* hidden <= 1024 */
-  const float* w1_dev;              /* [hidden, in_dim] */
-  const float* b1_dev;              /* [hidden] */
-  const float* w2_dev;              /* [in_dim, hidden] */
-  const float* b2_dev;              /* [in_dim] */
+  int32_t n_layers;                               /* 1 .. L2PD_FILTER_MAX_LAYERS */
+  int32_t in_dim, hidden;                         /* hidden <= 1024; unused when n_layers == 1 */
+  const float* w_dev[L2PD_FILTER_MAX_LAYERS];     /* layer k: [out_k, in_k] row-major */
+  const float* b_dev[L2PD_FILTER_MAX_LAYERS];     /* layer k: [out_k] */
 } l2pd_filter;
 
 /* Workload hook: add `value` to the logit of `token_id` at generation positions >= gen_pos_from
@@ -203,7 +207,8 @@ int32_t l2pd_egp_rollout(l2pd_ctx* ctx, const int32_t* prompt_dev, const int32_t
  * full-batch AdamW steps (decoupled weight decay, bias-corrected moments) on the mean binary cross-entropy
  * of sigmoid(f(conf_row)) against label_row over all n_rows * in_dim entries.  The filter's parameters are
  * UPDATED IN PLACE through the pointers of `filter` (device memory, fp32).  opt_state_dev: 2 * n_params
- * floats of device scratch (n_params = 2 * in_dim * hidden + in_dim + hidden), zeroed by the call;
+ * floats of device scratch (n_params = sum over the layers of out_k * in_k + out_k; layer after layer,
+ * weights before biases), zeroed by the call;
  * loss_out_dev [epochs] (optional) receives the loss of every epoch before its update.  Runs as one
  * workgroup; returns L2PD_ENOTIMPL for filters too large for it (more than 20480 parameters). */
 typedef struct {

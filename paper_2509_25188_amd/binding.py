@@ -32,9 +32,38 @@ class Weights(C.Structure):
                                                        "w_gate", "w_up", "w_down")]
 
 
+FILTER_MAX_LAYERS = 4
+
+
 class Filter(C.Structure):
-    _fields_ = [("in_dim", C.c_int32), ("hidden", C.c_int32), ("w1_dev", C.c_void_p), ("b1_dev", C.c_void_p),
-                ("w2_dev", C.c_void_p), ("b2_dev", C.c_void_p)]
+    _fields_ = [("n_layers", C.c_int32), ("in_dim", C.c_int32), ("hidden", C.c_int32),
+                ("w_dev", C.c_void_p * FILTER_MAX_LAYERS), ("b_dev", C.c_void_p * FILTER_MAX_LAYERS)]
+
+
+def filter_layers(flt: Dict[str, torch.Tensor]):
+    """[(w1, b1), ..., (wN, bN)] of a filter given as a dict with those keys."""
+    out = []
+    while f"w{len(out) + 1}" in flt:
+        k = len(out) + 1
+        out.append((flt[f"w{k}"], flt[f"b{k}"]))
+    if not 1 <= len(out) <= FILTER_MAX_LAYERS or len(flt) != 2 * len(out):
+        raise ValueError("a filter is {w1, b1, ..., wN, bN} with 1 <= N <= 4")
+    return out
+
+
+def _filter_struct(flt: Dict[str, torch.Tensor]) -> Filter:
+    layers = filter_layers(flt)
+    in_dim = layers[0][0].shape[1]
+    hidden = layers[0][0].shape[0] if len(layers) > 1 else 0
+    for k, (w, b) in enumerate(layers):
+        want = (in_dim if k == len(layers) - 1 else hidden, in_dim if k == 0 else hidden)
+        if tuple(w.shape) != want or tuple(b.shape) != want[:1]:
+            raise ValueError(f"filter layer {k + 1}: expected weight {want}, got {tuple(w.shape)} / {tuple(b.shape)}")
+    f = Filter(len(layers), in_dim, hidden)
+    for k, (w, b) in enumerate(layers):
+        f.w_dev[k] = w.data_ptr()
+        f.b_dev[k] = b.data_ptr()
+    return f
 
 
 class LogitBias(C.Structure):
@@ -167,9 +196,7 @@ class Engine:
     # ---- marshalling helpers ----
     @staticmethod
     def filter_struct(flt: Dict[str, torch.Tensor]) -> Filter:
-        hidden, in_dim = flt["w1"].shape
-        return Filter(in_dim, hidden, flt["w1"].data_ptr(), flt["b1"].data_ptr(), flt["w2"].data_ptr(),
-                      flt["b2"].data_ptr())
+        return _filter_struct(flt)
 
     @staticmethod
     def cfg_struct(gen_len, block_len, threshold, eotp=False, prefix_cache=False, bias=None,
@@ -245,21 +272,20 @@ class Engine:
 
 def train_filter(flt: Dict[str, torch.Tensor], conf_rows: torch.Tensor, label_rows: torch.Tensor, epochs: int,
                  lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01):
-    """Trains the filter IN PLACE (device fp32 tensors w1, b1, w2, b2) on rows [n, s]; returns the
+    """Trains the filter IN PLACE (device fp32 tensors w1, b1, ..., wN, bN) on rows [n, s]; returns the
     per-epoch losses as a device tensor."""
-    w1, b1, w2, b2 = (flt[k] for k in ("w1", "b1", "w2", "b2"))
-    for t in (w1, b1, w2, b2, conf_rows, label_rows):
+    for t in list(flt.values()) + [conf_rows, label_rows]:
         if t.dtype != torch.float32 or not t.is_contiguous() or not t.is_cuda:
             raise ValueError("train_filter needs contiguous fp32 device tensors")
-    hidden, s = w1.shape
+    f = _filter_struct(flt)
+    s = f.in_dim
     n = conf_rows.shape[0]
     if conf_rows.shape != (n, s) or label_rows.shape != (n, s):
         raise ValueError("rows must be [n, in_dim]")
-    f = Filter(s, hidden, w1.data_ptr(), b1.data_ptr(), w2.data_ptr(), b2.data_ptr())
     tc = TrainCfg(lr, beta1, beta2, eps, weight_decay, epochs)
-    n_params = 2 * s * hidden + s + hidden
-    state = torch.empty(2 * n_params, dtype=torch.float32, device=w1.device)
-    losses = torch.empty(epochs, dtype=torch.float32, device=w1.device)
+    n_params = sum(t.numel() for t in flt.values())
+    state = torch.empty(2 * n_params, dtype=torch.float32, device=conf_rows.device)
+    losses = torch.empty(epochs, dtype=torch.float32, device=conf_rows.device)
     _check(lib().l2pd_filter_train(C.byref(f), conf_rows.data_ptr(), label_rows.data_ptr(), n, C.byref(tc),
                                    state.data_ptr(), losses.data_ptr(), _stream()), "l2pd_filter_train")
     return losses

@@ -50,6 +50,7 @@ void launch_embed(float* h, const void* emb, int dtype, const int32_t* tokens, R
 // rows taken through `src`.  part z is at parts + z * part_stride, laid out like h.
 void launch_rmsnorm(float* h, const float* parts, int n_parts, size_t part_stride, RowMap src, const void* gain,
                     int dtype, void* y, int rows, int d, float eps, Gate g, hipStream_t s);
+constexpr int kFilterMaxLayers = 4;
 struct UpdateArgs {
   int32_t* X;            // [B, T]
   int32_t* state;        // [B, 3]
@@ -58,8 +59,10 @@ struct UpdateArgs {
   const float* part_sum;
   const int32_t* part_idx;
   int n_part;
-  const float *w1, *b1, *w2, *b2;
-  int hidden;
+  // filter: n_layers layers of widths s -> hidden -> ... -> hidden -> s (layer k: fw[k] [out, in], fb[k] [out])
+  const float* fw[kFilterMaxLayers];
+  const float* fb[kFilterMaxLayers];
+  int n_layers, hidden;
   float tau;
   float* conf_out;       // optional taps [B, s]
   int32_t* pred_out;
@@ -80,10 +83,12 @@ void launch_finalize(const int32_t* X, const int32_t* state, const int* teff, co
 // live sequences to the leading rows (stable), src copies -> dst copies; perm_src nullptr = identity
 void launch_compact(const int32_t* X_src, int32_t* X_dst, const int32_t* state_src, int32_t* state_dst,
                     const int32_t* perm_src, int32_t* perm_dst, int B, int T, hipStream_t s);
-// `epochs` full-batch AdamW steps on the binary cross-entropy of Eq. 6 for the two-layer filter, in place.
+// `epochs` full-batch AdamW steps on the binary cross-entropy of Eq. 6 for a filter of n_layers layers
+// (widths s -> hidden -> ... -> hidden -> s), in place.
 struct TrainArgs {
-  float *w1, *b1, *w2, *b2;   // device, updated in place
-  int s, hidden;
+  float* w[kFilterMaxLayers];   // device, updated in place; layer k: [out, in]
+  float* b[kFilterMaxLayers];
+  int n_layers, s, hidden;
   const float* conf;          // [n, s]
   const float* label;         // [n, s]
   long long n;
@@ -92,7 +97,8 @@ struct TrainArgs {
   float* opt_state;           // [2 * n_params], zeroed by the kernel
   float* loss_out;            // [epochs] or null
 };
-int filter_train_supported(int s, int hidden);
+int filter_param_count(int s, int hidden, int n_layers);
+int filter_train_supported(int s, int hidden, int n_layers);
 void launch_filter_train(const TrainArgs& a, hipStream_t s);
 void launch_seq_len(const int32_t* X, int B, int P, int G, int eos_id, int* teff, int* ctl, hipStream_t s);
 

@@ -477,7 +477,7 @@ __global__ void __launch_bounds__(1024) k_update(UpdateArgs a, Gate g) {
   __shared__ float s_conf[256];
   __shared__ int s_pred[256];
   __shared__ float s_cin[256];
-  __shared__ float s_hid[1024];
+  __shared__ float s_hid[2][1024];
   __shared__ unsigned char s_masked[256];
   __shared__ unsigned char s_sel[256];
   __shared__ int s_flag[6];   // masked, committed, end-of-text seen, still masked afterwards, first end-of-text, EGP hits
@@ -547,13 +547,22 @@ __global__ void __launch_bounds__(1024) k_update(UpdateArgs a, Gate g) {
   }
   __syncthreads();
   const int32_t* ref = a.reference ? a.reference + (size_t)b * a.gen_len + gb * s : nullptr;
-  for (int t = tid; t < (ref ? 0 : a.hidden); t += blockDim.x) {
-    float acc = a.b1[t];
-    const float* w = a.w1 + (size_t)t * s;
-    for (int j = 0; j < s; ++j) acc += w[j] * s_cin[j];
-    s_hid[t] = fmaxf(acc, 0.f);
+  // hidden layers of the filter (none for the single-layer variant), activations alternating
+  // between two LDS vectors
+  const float* act = s_cin;
+  int width = s;
+  for (int k = 0; !ref && k + 1 < a.n_layers; ++k) {
+    float* nxt = s_hid[k & 1];
+    for (int t = tid; t < a.hidden; t += blockDim.x) {
+      float acc = a.fb[k][t];
+      const float* w = a.fw[k] + (size_t)t * width;
+      for (int j = 0; j < width; ++j) acc += w[j] * act[j];
+      nxt[t] = fmaxf(acc, 0.f);
+    }
+    __syncthreads();
+    act = nxt;
+    width = a.hidden;
   }
-  __syncthreads();
   if (tid < s) {
     if (ref) {
       // EGP (Alg. 1): a masked position is unmasked exactly when its prediction is the reference token
@@ -561,9 +570,9 @@ __global__ void __launch_bounds__(1024) k_update(UpdateArgs a, Gate g) {
       s_sel[tid] = hit;
       if (hit) atomicAdd(&s_flag[5], 1);
     } else {
-      float z = a.b2[tid];
-      const float* w = a.w2 + (size_t)tid * a.hidden;
-      for (int t = 0; t < a.hidden; ++t) z += w[t] * s_hid[t];
+      float z = a.fb[a.n_layers - 1][tid];
+      const float* w = a.fw[a.n_layers - 1] + (size_t)tid * width;
+      for (int t = 0; t < width; ++t) z += w[t] * act[t];
       float p = 1.f / (1.f + expf(-z));
       if (a.filt_out) a.filt_out[b * s + tid] = p;
       s_sel[tid] = s_masked[tid] && (p > a.tau);
@@ -694,36 +703,50 @@ void launch_seq_len(const int32_t* X, int B, int P, int G, int eos_id, int* teff
 constexpr int kTrainThreads = 1024;
 constexpr int kTrainMaxOwn = 20;                 // parameters per thread
 constexpr int kTrainLdsFloats = 36 * 1024;       // 144 KB
-static int train_chunk_rows(int s, int hidden) {
-  const int n_params = 2 * s * hidden + s + hidden;
-  const int left = kTrainLdsFloats - n_params - 64;
-  int ch = left / (2 * s + 2 * hidden);
+int filter_param_count(int s, int hidden, int n_layers) {
+  int n = 0;
+  for (int k = 0; k < n_layers; ++k) {
+    const int in = k == 0 ? s : hidden, out = k == n_layers - 1 ? s : hidden;
+    n += out * in + out;
+  }
+  return n;
+}
+static int train_chunk_rows(int s, int hidden, int n_layers) {
+  const int left = kTrainLdsFloats - filter_param_count(s, hidden, n_layers) - 64;
+  int ch = left / (2 * (s + (n_layers - 1) * hidden));
   return ch > 64 ? 64 : ch;
 }
-int filter_train_supported(int s, int hidden) {
-  const int n_params = 2 * s * hidden + s + hidden;
-  return s >= 1 && hidden >= 1 && n_params <= kTrainThreads * kTrainMaxOwn && train_chunk_rows(s, hidden) >= 8;
+int filter_train_supported(int s, int hidden, int n_layers) {
+  return n_layers >= 1 && n_layers <= kFilterMaxLayers && s >= 1 && (n_layers == 1 || hidden >= 1) &&
+         filter_param_count(s, hidden, n_layers) <= kTrainThreads * kTrainMaxOwn &&
+         train_chunk_rows(s, hidden, n_layers) >= 8;
 }
 __global__ void __launch_bounds__(kTrainThreads) k_filter_train(TrainArgs a, int chunk) {
   extern __shared__ float lds[];
-  const int s = a.s, h = a.hidden, tid = threadIdx.x;
-  const int n_w1 = h * s, n_w2 = s * h, n_params = n_w1 + h + n_w2 + s;
-  // LDS: parameters (w1 | b1 | w2 | b2), chunk rows C, hidden H, dZ, dH, reduction scratch
+  const int s = a.s, h = a.hidden, L = a.n_layers, tid = threadIdx.x;
+  // layer k maps width in(k) to width out(k); its parameters sit at off(k) (weights, then biases).
+  // Closed forms rather than tables, so nothing here is indexed dynamically out of registers.
+  auto in = [&](int k) { return k == 0 ? s : h; };
+  auto out = [&](int k) { return k == L - 1 ? s : h; };
+  const int first = h * s + h, mid = h * h + h;            // parameters of layer 0 / of a hidden->hidden layer
+  auto off = [&](int k) { return k == 0 ? 0 : first + (k - 1) * mid; };
+  const int n_params = off(L - 1) + s * in(L - 1) + s;
+  auto layer_of = [&](int p) {
+    if (L == 1 || p < first) return 0;
+    const int k = 1 + (p - first) / mid;
+    return k < L - 1 ? k : L - 1;
+  };
+  // LDS: parameters, then per chunk the input of every layer (A(0) = the confidence rows) and the
+  // loss gradient at every layer's pre-activation (D), then reduction scratch
   float* th = lds;
-  float* Cc = th + n_params;
-  float* Hc = Cc + chunk * s;
-  float* dZ = Hc + chunk * h;
-  float* dH = dZ + chunk * s;
-  float* red = dH + chunk * h;    // 64 floats
-  const float* W1 = th;
-  const float* B1 = th + n_w1;
-  const float* W2 = B1 + h;
-  const float* B2 = W2 + n_w2;
-  float* gl[4] = {a.w1, a.b1, a.w2, a.b2};
-  const int seg[5] = {0, n_w1, n_w1 + h, n_w1 + h + n_w2, n_params};
+  float* const baseA = th + n_params;
+  float* const baseD = baseA + chunk * (s + (L - 1) * h);
+  auto A = [&](int k) { return baseA + (k == 0 ? 0 : chunk * s + (k - 1) * chunk * h); };
+  auto D = [&](int k) { return baseD + k * chunk * h; };
+  float* red = baseD + chunk * ((L - 1) * h + s);          // 64 floats
   for (int p = tid; p < n_params; p += kTrainThreads) {
-    int k = p < seg[1] ? 0 : (p < seg[2] ? 1 : (p < seg[3] ? 2 : 3));
-    th[p] = gl[k][p - seg[k]];
+    const int k = layer_of(p), q = p - off(k), nw = out(k) * in(k);
+    th[p] = q < nw ? a.w[k][q] : a.b[k][q - nw];
     a.opt_state[p] = 0.f;
     a.opt_state[n_params + p] = 0.f;
   }
@@ -737,48 +760,55 @@ __global__ void __launch_bounds__(kTrainThreads) k_filter_train(TrainArgs a, int
     float loss = 0.f;
     for (long long c0 = 0; c0 < a.n; c0 += chunk) {
       const int rows = (int)min((long long)chunk, a.n - c0);
-      for (int i = tid; i < rows * s; i += kTrainThreads) Cc[i] = a.conf[c0 * s + i];
+      for (int i = tid; i < rows * s; i += kTrainThreads) A(0)[i] = a.conf[c0 * s + i];
       __syncthreads();
-      for (int i = tid; i < rows * h; i += kTrainThreads) {      // hidden activations
-        const int r = i / h, t = i % h;
-        float acc = B1[t];
-        for (int j = 0; j < s; ++j) acc += W1[t * s + j] * Cc[r * s + j];
-        Hc[i] = fmaxf(acc, 0.f);
+      for (int k = 0; k + 1 < L; ++k) {                            // hidden activations
+        const float* W = th + off(k);
+        const float* Bv = W + out(k) * in(k);
+        for (int i = tid; i < rows * out(k); i += kTrainThreads) {
+          const int r = i / out(k), t = i % out(k);
+          float acc = Bv[t];
+          for (int j = 0; j < in(k); ++j) acc += W[t * in(k) + j] * A(k)[r * in(k) + j];
+          A(k + 1)[i] = fmaxf(acc, 0.f);
+        }
+        __syncthreads();
       }
-      __syncthreads();
-      for (int i = tid; i < rows * s; i += kTrainThreads) {      // logits, loss, dL/dz
-        const int r = i / s, j = i % s;
-        float z = B2[j];
-        for (int t = 0; t < h; ++t) z += W2[j * h + t] * Hc[r * h + t];
-        const float y = a.label[c0 * s + i];
-        loss += fmaxf(z, 0.f) + log1pf(expf(-fabsf(z))) - y * z;   // softplus(z) - y z
-        dZ[i] = (1.f / (1.f + expf(-z)) - y) * inv_m;
+      {                                                            // logits, loss, dL/dz
+        const int k = L - 1;
+        const float* W = th + off(k);
+        const float* Bv = W + s * in(k);
+        for (int i = tid; i < rows * s; i += kTrainThreads) {
+          const int r = i / s, j = i % s;
+          float z = Bv[j];
+          for (int t = 0; t < in(k); ++t) z += W[j * in(k) + t] * A(k)[r * in(k) + t];
+          const float y = a.label[c0 * s + i];
+          loss += fmaxf(z, 0.f) + log1pf(expf(-fabsf(z))) - y * z;   // softplus(z) - y z
+          D(k)[i] = (1.f / (1.f + expf(-z)) - y) * inv_m;
+        }
+        __syncthreads();
       }
-      __syncthreads();
-      for (int i = tid; i < rows * h; i += kTrainThreads) {      // dL/dh through the ReLU
-        const int r = i / h, t = i % h;
-        float acc = 0.f;
-        for (int j = 0; j < s; ++j) acc += dZ[r * s + j] * W2[j * h + t];
-        dH[i] = Hc[i] > 0.f ? acc : 0.f;
+      for (int k = L - 1; k > 0; --k) {                            // back through layer k and the ReLU before it
+        const float* W = th + off(k);
+        for (int i = tid; i < rows * in(k); i += kTrainThreads) {
+          const int r = i / in(k), t = i % in(k);
+          float acc = 0.f;
+          for (int j = 0; j < out(k); ++j) acc += D(k)[r * out(k) + j] * W[j * in(k) + t];
+          D(k - 1)[i] = A(k)[i] > 0.f ? acc : 0.f;
+        }
+        __syncthreads();
       }
-      __syncthreads();
 #pragma unroll
       for (int o = 0; o < kTrainMaxOwn; ++o) {                     // gradient of the owned parameters
         const int p = tid + o * kTrainThreads;
         if (p >= n_params) break;
+        const int k = layer_of(p), q = p - off(k), nw = out(k) * in(k);
         float acc = 0.f;
-        if (p < seg[1]) {
-          const int t = p / s, j = p % s;
-          for (int r = 0; r < rows; ++r) acc += dH[r * h + t] * Cc[r * s + j];
-        } else if (p < seg[2]) {
-          const int t = p - seg[1];
-          for (int r = 0; r < rows; ++r) acc += dH[r * h + t];
-        } else if (p < seg[3]) {
-          const int q = p - seg[2], j = q / h, t = q % h;
-          for (int r = 0; r < rows; ++r) acc += dZ[r * s + j] * Hc[r * h + t];
+        if (q < nw) {
+          const int t = q / in(k), j = q % in(k);
+          for (int r = 0; r < rows; ++r) acc += D(k)[r * out(k) + t] * A(k)[r * in(k) + j];
         } else {
-          const int j = p - seg[3];
-          for (int r = 0; r < rows; ++r) acc += dZ[r * s + j];
+          const int t = q - nw;
+          for (int r = 0; r < rows; ++r) acc += D(k)[r * out(k) + t];
         }
         g[o] += acc;
       }
@@ -813,14 +843,16 @@ __global__ void __launch_bounds__(kTrainThreads) k_filter_train(TrainArgs a, int
     __syncthreads();
   }
   for (int p = tid; p < n_params; p += kTrainThreads) {
-    int k = p < seg[1] ? 0 : (p < seg[2] ? 1 : (p < seg[3] ? 2 : 3));
-    gl[k][p - seg[k]] = th[p];
+    const int k = layer_of(p), q = p - off(k), nw = out(k) * in(k);
+    if (q < nw) a.w[k][q] = th[p];
+    else a.b[k][q - nw] = th[p];
   }
 }
 void launch_filter_train(const TrainArgs& a, hipStream_t s) {
-  const int chunk = train_chunk_rows(a.s, a.hidden);
-  const int n_params = 2 * a.s * a.hidden + a.s + a.hidden;
-  const size_t smem = (size_t)(n_params + chunk * (2 * a.s + 2 * a.hidden) + 64) * sizeof(float);
+  const int chunk = train_chunk_rows(a.s, a.hidden, a.n_layers);
+  const int n_params = filter_param_count(a.s, a.hidden, a.n_layers);
+  const size_t smem =
+      (size_t)(n_params + chunk * 2 * (a.s + (a.n_layers - 1) * a.hidden) + 64) * sizeof(float);
   static bool attr_done = false;
   if (!attr_done) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_filter_train), hipFuncAttributeMaxDynamicSharedMemorySize,

@@ -371,14 +371,22 @@ void run_head(l2pd_ctx* c, int B, int n_rows_per_seq, RowMap src, float* logits_
   }
 }
 
+static_assert(L2PD_FILTER_MAX_LAYERS == kFilterMaxLayers, "filter depth limit");
+bool filter_ok(const l2pd_filter* f) {
+  if (f->n_layers < 1 || f->n_layers > L2PD_FILTER_MAX_LAYERS || f->in_dim < 1) return false;
+  if (f->n_layers > 1 && (f->hidden < 1 || f->hidden > 1024)) return false;
+  for (int k = 0; k < f->n_layers; ++k)
+    if (!f->w_dev[k] || !f->b_dev[k]) return false;
+  return true;
+}
+
 int check_decode_args(const l2pd_ctx* c, int B, int P, const l2pd_decode_cfg* cfg, const l2pd_filter* f) {
   if (!c || !cfg || !f) return L2PD_EINVAL;
   if (B < 1 || B > c->max_batch || P < 1) return L2PD_EINVAL;
   if (cfg->gen_len < 1 || cfg->block_len < 1 || cfg->block_len > 256) return L2PD_EINVAL;
   if (cfg->gen_len % cfg->block_len) return L2PD_EINVAL;
   if ((long long)P + cfg->gen_len > c->max_seq) return L2PD_EINVAL;
-  if (f->in_dim != cfg->block_len || f->hidden < 1 || f->hidden > 1024) return L2PD_EINVAL;
-  if (!f->w1_dev || !f->b1_dev || !f->w2_dev || !f->b2_dev) return L2PD_EINVAL;
+  if (f->in_dim != cfg->block_len || !filter_ok(f)) return L2PD_EINVAL;
   if (isnan(cfg->threshold)) return L2PD_EINVAL;
   if (cfg->kv_cache < L2PD_CACHE_NONE || cfg->kv_cache > L2PD_CACHE_DUAL) return L2PD_EINVAL;
   if (cfg->kv_cache && !c->cache) return L2PD_EINVAL;
@@ -450,7 +458,11 @@ void run_step(l2pd_ctx* c, int32_t* X, int B, int P, const l2pd_decode_cfg* cfg,
   u.mask_id = c->m.mask_id; u.eos_id = c->m.eos_id; u.eotp = cfg->eotp;
   u.part_max = c->at<float>(L.part_max); u.part_sum = c->at<float>(L.part_sum);
   u.part_idx = c->at<int32_t>(L.part_idx); u.n_part = L.n_part;
-  if (f) { u.w1 = f->w1_dev; u.b1 = f->b1_dev; u.w2 = f->w2_dev; u.b2 = f->b2_dev; u.hidden = f->hidden; }
+  if (f) {
+    for (int k = 0; k < f->n_layers; ++k) { u.fw[k] = f->w_dev[k]; u.fb[k] = f->b_dev[k]; }
+    u.n_layers = f->n_layers;
+    u.hidden = f->hidden;
+  }
   if (egp) { u.reference = egp->reference; u.egp_conf = egp->conf; u.egp_label = egp->label; }
   u.gen_len = cfg->gen_len;
   u.tau = cfg->threshold;
@@ -753,16 +765,18 @@ int32_t l2pd_filter_train(const l2pd_filter* f, const float* conf_rows_dev, cons
                           int64_t n_rows, const l2pd_train_cfg* tc, float* opt_state_dev, float* loss_out_dev,
                           void* stream) {
   if (!f || !tc || !conf_rows_dev || !label_rows_dev || !opt_state_dev) return L2PD_EINVAL;
-  if (!f->w1_dev || !f->b1_dev || !f->w2_dev || !f->b2_dev || f->in_dim < 1 || f->hidden < 1) return L2PD_EINVAL;
+  if (!filter_ok(f)) return L2PD_EINVAL;
   if (n_rows < 1 || n_rows > (1ll << 24) || tc->epochs < 1 || tc->epochs > 1000000) return L2PD_EINVAL;
   if (!(tc->lr > 0.f) || !(tc->beta1 >= 0.f && tc->beta1 < 1.f) || !(tc->beta2 >= 0.f && tc->beta2 < 1.f) ||
       !(tc->eps > 0.f) || !(tc->weight_decay >= 0.f))
     return L2PD_EINVAL;
-  if (!filter_train_supported(f->in_dim, f->hidden)) return L2PD_ENOTIMPL;
+  if (!filter_train_supported(f->in_dim, f->hidden, f->n_layers)) return L2PD_ENOTIMPL;
   TrainArgs a = {};
-  a.w1 = const_cast<float*>(f->w1_dev); a.b1 = const_cast<float*>(f->b1_dev);
-  a.w2 = const_cast<float*>(f->w2_dev); a.b2 = const_cast<float*>(f->b2_dev);
-  a.s = f->in_dim; a.hidden = f->hidden;
+  for (int k = 0; k < f->n_layers; ++k) {
+    a.w[k] = const_cast<float*>(f->w_dev[k]);
+    a.b[k] = const_cast<float*>(f->b_dev[k]);
+  }
+  a.n_layers = f->n_layers; a.s = f->in_dim; a.hidden = f->n_layers > 1 ? f->hidden : 1;
   a.conf = conf_rows_dev; a.label = label_rows_dev; a.n = n_rows; a.epochs = tc->epochs;
   a.lr = tc->lr; a.beta1 = tc->beta1; a.beta2 = tc->beta2; a.eps = tc->eps; a.weight_decay = tc->weight_decay;
   a.opt_state = opt_state_dev; a.loss_out = loss_out_dev;

@@ -234,20 +234,22 @@ def make_weights(m: ModelShape, seed: int, device="cpu", init_std: float = 0.02,
             for name, shape, kind in weight_specs(m)}
 
 
-def make_filter(seed: int, block_len: int, hidden: int, device="cpu") -> Dict[str, torch.Tensor]:
-    """Two-layer MLP parameters, fp32: W ~ N(0, 1/fan_in), b ~ N(0, 1).
+def make_filter(seed: int, block_len: int, hidden: int, device="cpu", n_layers: int = 2) -> Dict[str, torch.Tensor]:
+    """MLP filter parameters {w1, b1, ..., wN, bN}, fp32: W ~ N(0, 1/fan_in), b ~ N(0, 1).  Two layers
+    is the paper's filter; one and four are the depth variants of Table 3 (hidden widths all `hidden`).
 
     Biases of order one spread the filter outputs over (0, 1); with a random-init
     language model every confidence is about 1e-3, so a small-weight filter would
     put every decision on top of the threshold.
     """
     f32 = torch.float32
-    return {
-        "w1": normal(seed, "filter.w1", (hidden, block_len), block_len ** -0.5, f32, device),
-        "b1": normal(seed, "filter.b1", (hidden,), 1.0, f32, device),
-        "w2": normal(seed, "filter.w2", (block_len, hidden), hidden ** -0.5, f32, device),
-        "b2": normal(seed, "filter.b2", (block_len,), 1.0, f32, device),
-    }
+    dims = [block_len] + [hidden] * (n_layers - 1) + [block_len]
+    out = {}
+    for k in range(1, n_layers + 1):
+        fan_in, fan_out = dims[k - 1], dims[k]
+        out[f"w{k}"] = normal(seed, f"filter.w{k}", (fan_out, fan_in), fan_in ** -0.5, f32, device)
+        out[f"b{k}"] = normal(seed, f"filter.b{k}", (fan_out,), 1.0, f32, device)
+    return out
 
 
 def threshold_filter(block_len: int, theta: float, sharpness: float = 200.0, device="cpu") -> Dict[str, torch.Tensor]:

@@ -75,7 +75,14 @@ def test_decode_argument_checks_return_before_any_launch():
     ctx = C.c_void_p()
     assert lib.l2pd_create(C.byref(d), C.byref(w), 2, 96, 0, 0x10000, n, C.byref(ctx)) == Bd.L2PD_OK
     try:
-        flt = Bd.Filter(32, 64, 0x1000, 0x1000, 0x1000, 0x1000)
+        def filt(n_layers, in_dim, hidden, first=0x1000):
+            f = Bd.Filter(n_layers, in_dim, hidden)
+            for k in range(min(n_layers, Bd.FILTER_MAX_LAYERS)):
+                f.w_dev[k] = first if k == 0 else 0x1000
+                f.b_dev[k] = 0x1000
+            return f
+
+        flt = filt(2, 32, 64)
 
         def gen(cfg, f=flt, B=1, P=32, prompt=0x1000, out=0x1000):
             return lib.l2pd_generate(ctx, prompt, B, P, C.byref(cfg), C.byref(f), out, None, None, None)
@@ -85,8 +92,11 @@ def test_decode_argument_checks_return_before_any_launch():
         assert gen(Bd.Engine.cfg_struct(64, 32, math.nan)) == Bd.L2PD_EINVAL       # NaN threshold
         assert gen(Bd.Engine.cfg_struct(128, 32, 0.5)) == Bd.L2PD_EINVAL           # P + gen_len > max_seq
         assert gen(ok, B=3) == Bd.L2PD_EINVAL                                      # B > max_batch
-        assert gen(ok, f=Bd.Filter(16, 64, 0x1000, 0x1000, 0x1000, 0x1000)) == Bd.L2PD_EINVAL  # in_dim != block
-        assert gen(ok, f=Bd.Filter(32, 64, None, 0x1000, 0x1000, 0x1000)) == Bd.L2PD_EINVAL
+        assert gen(ok, f=filt(2, 16, 64)) == Bd.L2PD_EINVAL                        # in_dim != block_len
+        assert gen(ok, f=filt(2, 32, 64, first=None)) == Bd.L2PD_EINVAL            # missing layer
+        assert gen(ok, f=filt(0, 32, 64)) == Bd.L2PD_EINVAL                        # depth out of range
+        assert gen(ok, f=filt(5, 32, 64)) == Bd.L2PD_EINVAL
+        assert gen(ok, f=filt(4, 32, 2048)) == Bd.L2PD_EINVAL                      # hidden too wide
         assert gen(Bd.Engine.cfg_struct(64, 32, 0.5, prefix_cache=True)) == Bd.L2PD_EINVAL  # ctx has no cache
         assert gen(Bd.Engine.cfg_struct(64, 32, 0.5, bias=(m.vocab, 0, 1.0))) == Bd.L2PD_EINVAL
         assert gen(ok, prompt=None) == Bd.L2PD_EINVAL
