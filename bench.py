@@ -155,14 +155,14 @@ def cached_workload(args, w, eng, flt, prompt, cfg, f, X0, state0, traj_steps, t
     }
 
 
-def pipeline(w, eng, prompt, cfg, seed, dev):
+def pipeline(w, eng, prompt, cfg, seed, dev, n_layers=2):
     """Alg. 1 end to end on the synthetic model: the model's own one-token-per-step answer is the
     reference (Sec. 3.1.2), an EGP rollout labels the confidences, the filter is trained on them
     (AdamW, lr 1e-3, 5,000 epochs as in Sec. 4.1), and the prompt is decoded again with it."""
     import torch
     from paper_2509_25188_amd import binding as Bd
     from paper_2509_25188_amd import synth
-    flt = synth.make_filter(seed, w.block_len, w.filter_hidden, dev)
+    flt = synth.make_filter(seed, w.block_len, w.filter_hidden, dev, n_layers=n_layers)
     vcfg = Bd.Engine.cfg_struct(w.gen_len, w.block_len, 1.0)           # tau = 1: only the forced position goes
     t0 = time.perf_counter()
     ref, st_v, _ = eng.generate(prompt, flt, vcfg)
@@ -185,6 +185,8 @@ def pipeline(w, eng, prompt, cfg, seed, dev):
     torch.cuda.synchronize()
     t_dec = time.perf_counter() - t0
     return {"vanilla_steps": int(st_v.max()), "vanilla_s": t_van, "egp_steps": int(steps.max()), "egp_rollout_s": t_roll,
+            "filter_layers": n_layers, "filter_hidden": w.filter_hidden,
+            "filter_params": sum(v.numel() for v in flt.values()),
             "training_rows": int(rows_c.shape[0]), "training_epochs": 5000, "training_s": t_train,
             "bce_first": float(losses[0]), "bce_last": float(losses[-1]),
             "trained_filter_steps": int(st_f.max()), "trained_filter_s": t_dec,
@@ -255,6 +257,9 @@ def main():
     ap.add_argument("--pipeline", action="store_true",
                     help="also run the whole Learn2PD pipeline on the synthetic model: vanilla answer as reference, "
                          "EGP rollout, filter training, decode with the trained filter (adds a 'pipeline' object)")
+    ap.add_argument("--filter-layers", type=int, default=2,
+                    help="depth of the filter MLP (2 = the paper's; 1 and 4 are the variants of Table 3)")
+    ap.add_argument("--filter-hidden", type=int, default=0, help="hidden width of the filter (0: the workload's)")
     ap.add_argument("--batch-schedules", action="store_true",
                     help="also time whole generations of the batch in lock step, with per-sequence block "
                          "pointers, and with batch compaction")
@@ -276,12 +281,14 @@ def main():
     w = synth.WORKLOADS[args.workload]
     if args.layers:
         w = synth.with_layers(w, args.layers)
+    import dataclasses
+    if args.filter_hidden:
+        w = dataclasses.replace(w, filter_hidden=args.filter_hidden)
     m = w.model
     dev = "cuda"
     t0 = time.time()
-    import dataclasses
     eng = Bd.engine_for(w, args.seed, dev, lm_head_scale=args.lm_head_scale)
-    flt = synth.make_filter(args.seed, w.block_len, w.filter_hidden, dev)
+    flt = synth.make_filter(args.seed, w.block_len, w.filter_hidden, dev, n_layers=args.filter_layers)
     if args.decoder == "vanilla":          # the filter never passes: only the forced most confident position goes
         w = dataclasses.replace(w, threshold=1.0)
     elif args.decoder == "threshold":
@@ -361,6 +368,7 @@ def main():
         "config": {"workload": w.name, "batch": w.batch, "prompt_len": w.prompt_len, "gen_len": w.gen_len,
                    "block_len": w.block_len, "threshold": w.threshold,
                    "eotp": "step" if w.eotp_step else bool(w.eotp), "decoder": args.decoder,
+                   "filter_layers": args.filter_layers, "filter_hidden": w.filter_hidden,
                    "lm_head_scale": args.lm_head_scale, "layers": m.n_layers, "d_model": m.d_model, "d_ffn": m.d_ffn,
                    "vocab": m.vocab, "full_recompute_rows": rows},
         "steps_per_s": steps_per_s,
@@ -378,7 +386,7 @@ def main():
         "setup_s": setup_s,
     }
     if args.pipeline:
-        result["pipeline"] = pipeline(w, eng, prompt, cfg, args.seed, dev)
+        result["pipeline"] = pipeline(w, eng, prompt, cfg, args.seed, dev, args.filter_layers)
     if args.batch_schedules:
         result["batch_schedules"] = batch_schedules(w, eng, prompt, flt, cfg)
     if args.copy_calibration:
