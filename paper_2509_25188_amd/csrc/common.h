@@ -150,7 +150,8 @@ void launch_skinny_qkv_finish(const float* parts, int n_parts, size_t part_strid
                               Gate g, hipStream_t s);
 void launch_skinny_swiglu_finish(const float* parts, int n_parts, size_t part_stride, int rows, int F, bf16* act,
                                  Gate g, hipStream_t s);
-// act[M, F] = silu(A Wg^T) * (A Wu^T)
+// act[M, F] = silu(A Wg^T) * (A Wu^T); few rows take the fused few-row tiles when swiglu_few_rows_fused says so
+bool swiglu_few_rows_fused(int M, int F);
 void launch_gemm_swiglu_bf16(const bf16* A, const bf16* wg, const bf16* wu, bf16* act, int M, int F, int K, Gate g,
                              hipStream_t s);
 struct LmHeadEpilogue {

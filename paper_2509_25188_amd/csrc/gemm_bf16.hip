@@ -597,11 +597,22 @@ void launch_gemm_skinny_bf16(const bf16* A, const bf16* w0, const bf16* w1, cons
   else launch<64, 128, 64, 2, 2, 4, EPI_PARTIAL>(a, s);
 }
 
+// Few rows and a wide FFN: 64 (32 gate + 32 up) columns per workgroup already make a few hundred
+// workgroups, so the weights stream once without splitting K and SwiGLU stays in the epilogue
+// (measured against split-K partials plus a finishing kernel, weights coming from HBM: 40.6 us
+// against 44.1 + 4.6 us at 32 rows, 43.5 against 51.4 + 4.6 us at 64 rows, d_model 4096, d_ffn 12288).
+bool swiglu_few_rows_fused(int M, int F) { return M <= kSkinnyRows && F % 64 == 0 && 2 * F / 64 >= 256; }
+
 void launch_gemm_swiglu_bf16(const bf16* A, const bf16* wg, const bf16* wu, bf16* act, int M, int F, int K, Gate g,
                              hipStream_t s) {
   GemmArgs a = {};
   a.A = A; a.B0 = wg; a.B1 = wu; a.M = M; a.N = 2 * F; a.K = K; a.splits = 1; a.gate = g;
   a.act = act; a.F = F;
+  if (swiglu_few_rows_fused(M, F)) {
+    if (M <= 32) launch<32, 64, 64, 1, 1, 6, EPI_SWIGLU>(a, s);   // one wavefront per workgroup, 72 KB ring
+    else launch<64, 128, 64, 2, 2, 4, EPI_SWIGLU>(a, s);
+    return;
+  }
   switch (pick_tile(M, a.N)) {
     case 4: launch<128, 192, 32, 4, 1, 4, EPI_SWIGLU>(a, s); break;
     case 3: launch<256, 192, 32, 4, 1, 4, EPI_SWIGLU>(a, s); break;

@@ -148,11 +148,16 @@ static int bench_layer(int rows, int d, int F, int H, int keys) {
   if (skinny) {
     t = time_us([&] { launch_gemm_skinny_bf16(ao, wo, nullptr, nullptr, 0, parts, stride_d, rows, d, d, so, g, 0); });
     line("output projection (split-K partials)", t, 0, wb * d * d);
-    t = time_us([&] {
-      launch_gemm_skinny_bf16(xn, wg, wu, nullptr, F, parts, (size_t)rows * 2 * F, rows, 2 * F, d, sg, g, 0);
-      launch_skinny_swiglu_finish(parts, sg, (size_t)rows * 2 * F, rows, F, act, g, 0);
-    });
-    line("gate / up projection (split-K) + SwiGLU kernel", t, 0, wb * 2 * F * d);
+    if (swiglu_few_rows_fused(rows, F)) {
+      t = time_us([&] { launch_gemm_swiglu_bf16(xn, wg, wu, act, rows, F, d, g, 0); });
+      line("gate / up projection + SwiGLU (few-row tiles)", t, 0, wb * 2 * F * d);
+    } else {
+      t = time_us([&] {
+        launch_gemm_skinny_bf16(xn, wg, wu, nullptr, F, parts, (size_t)rows * 2 * F, rows, 2 * F, d, sg, g, 0);
+        launch_skinny_swiglu_finish(parts, sg, (size_t)rows * 2 * F, rows, F, act, g, 0);
+      });
+      line("gate / up projection (split-K) + SwiGLU kernel", t, 0, wb * 2 * F * d);
+    }
     t = time_us([&] { launch_gemm_skinny_bf16(act_in, wd, nullptr, nullptr, 0, parts, stride_d, rows, d, F, sd, g, 0); });
     line("down projection (split-K partials)", t, 0, wb * d * F);
   } else {

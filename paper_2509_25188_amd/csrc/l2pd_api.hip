@@ -306,7 +306,7 @@ void run_layers(l2pd_ctx* c, const Pass& p, Gate g, hipStream_t s) {
         launch_rmsnorm(h, parts, so, stride_d, ident, c->ffn_g[l], m.dtype, xn, rows, d, m.rms_eps, g, s); }
       bf16* act = c->at<bf16>(L.act);
       { Timed t(c, L2PD_K_GEMM_GATEUP, s);
-        if (skinny) {
+        if (skinny && !swiglu_few_rows_fused(rows, F)) {
           const int S = skinny_splits(2 * F, d);
           const size_t stride = (size_t)rows * 2 * F;
           launch_gemm_skinny_bf16(xn, (const bf16*)c->wg[l], (const bf16*)c->wu[l], nullptr, F, parts, stride, rows,
