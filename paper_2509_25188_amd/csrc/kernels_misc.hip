@@ -267,24 +267,29 @@ __global__ void __launch_bounds__(256) k_rmsnorm_row(float* h, const float* part
     const int i = tid + 256 * k;
     v[k] = i < d4 ? x[i] : make_float4(0.f, 0.f, 0.f, 0.f);
   }
-  // partials two at a time: both groups of loads are in flight together, the adds stay in order
-  for (int z = 0; z < n_parts; z += 2) {
-    const bool two = z + 1 < n_parts;
-    const float4* a0 = reinterpret_cast<const float4*>(parts + z * part_stride + srow * d);
-    const float4* a1 = reinterpret_cast<const float4*>(parts + (two ? z + 1 : z) * part_stride + srow * d);
-    float4 t0[VPL], t1[VPL];
+  // partials four at a time (the few-row path folds eight or more): the loads of a group are in
+  // flight together, the adds stay in ascending order
+  constexpr int GRP = 4;
+  for (int z0 = 0; z0 < n_parts; z0 += GRP) {
+    float4 t[GRP][VPL];
 #pragma unroll
-    for (int k = 0; k < VPL; ++k) {
-      const int i = tid + 256 * k;
-      const bool in = i < d4;
-      t0[k] = in ? a0[i] : make_float4(0.f, 0.f, 0.f, 0.f);
-      t1[k] = (in && two) ? a1[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int z = 0; z < GRP; ++z) {
+      const bool have = z0 + z < n_parts;
+      const float4* a = reinterpret_cast<const float4*>(parts + (have ? z0 + z : z0) * part_stride + srow * d);
+#pragma unroll
+      for (int k = 0; k < VPL; ++k) {
+        const int i = tid + 256 * k;
+        t[z][k] = (have && i < d4) ? a[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
     }
 #pragma unroll
-    for (int k = 0; k < VPL; ++k) {
-      v[k].x += t0[k].x; v[k].y += t0[k].y; v[k].z += t0[k].z; v[k].w += t0[k].w;
-      if (two) { v[k].x += t1[k].x; v[k].y += t1[k].y; v[k].z += t1[k].z; v[k].w += t1[k].w; }
-    }
+    for (int z = 0; z < GRP; ++z)
+      if (z0 + z < n_parts) {
+#pragma unroll
+        for (int k = 0; k < VPL; ++k) {
+          v[k].x += t[z][k].x; v[k].y += t[z][k].y; v[k].z += t[z][k].z; v[k].w += t[z][k].w;
+        }
+      }
   }
   float ss = 0.f;
 #pragma unroll
