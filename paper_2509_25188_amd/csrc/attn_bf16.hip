@@ -29,15 +29,13 @@ __device__ __forceinline__ unsigned int pack_bf16x2(float lo, float hi) {   // v
   return __builtin_bit_cast(unsigned int, __builtin_convertvector(v, bf16x2_t));
 }
 
-template <int DH, int NQ, int NSPL>
+template <int DH, int NQ, int NSPL, int NST>
 __global__ void __launch_bounds__(NQ * NSPL * 64) k_attn_bf16(const bf16* __restrict__ q, const bf16* __restrict__ kstore,
                                                               const bf16* __restrict__ vtstore, bf16* __restrict__ out,
                                                               int B, int Tq, int Tk_all, int Tpad, int H, int n_chunks,
                                                               float* __restrict__ chunk_out,
                                                               const int* __restrict__ tk_dev, Gate g) {
   if (gate_skip(g)) return;
-  // per-sequence key count (sequences shortened by step-granular EoTP), else the launch's
-  const int Tk = tk_dev ? min(Tk_all, tk_dev[blockIdx.z]) : Tk_all;
   constexpr int NW = NQ * NSPL;
   constexpr int NT = NW * 64;
   constexpr int KT = 64;                       // keys per LDS tile
@@ -50,17 +48,33 @@ __global__ void __launch_bounds__(NQ * NSPL * 64) k_attn_bf16(const bf16* __rest
   constexpr int KK = DH / 16;                  // MFMA steps over the feature dim
   constexpr int FO = DH / 32;                  // output row fragments
   constexpr int XW = FO * 16 + 2;              // floats a wave hands over per lane: O^T fragments, m, l
-  static_assert((NSPL - 1) * NQ * XW * 64 * 4 <= 2 * NSPL * STAGE, "exchange area must fit in the tile buffers");
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // [2 stages][NSPL key ranges][K tile | V^T tile]
+  static_assert(NST == 1 || NST == 2, "tile buffers are single or double");
+  static_assert((NSPL - 1) * NQ * XW * 64 * 4 <= NST * NSPL * STAGE, "exchange area must fit in the tile buffers");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // [NST stages][NSPL key ranges][K tile | V^T tile]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5, lj = lane & 31;
   const int qg = wave % NQ, sp = wave / NQ;    // query group and key range of this wavefront
-  const int b = blockIdx.z, h = blockIdx.y;
+  // Workgroups are dealt to the 8 XCDs round-robin by their linear id.  All query tiles of one
+  // (sequence, head) read the same K / V^T, so they are given ids that land on one XCD and share
+  // its L2 (T = 512: 1 MB of K/V per XCD instead of all 8 MB through every L2).
+  const int per_head = gridDim.x / (H * B);     // query tiles x key chunks
+  int hb, inner;
+  if ((H * B) % 8 == 0) {
+    const int slot = blockIdx.x >> 3;
+    hb = (slot / per_head) * 8 + (blockIdx.x & 7);
+    inner = slot % per_head;
+  } else {
+    hb = blockIdx.x / per_head;
+    inner = blockIdx.x % per_head;
+  }
+  const int b = hb / H, h = hb % H;
+  // per-sequence key count (sequences shortened by step-granular EoTP), else the launch's
+  const int Tk = tk_dev ? min(Tk_all, tk_dev[b]) : Tk_all;
   const int d = H * DH;
   // With n_chunks > 1 the keys are also dealt to n_chunks workgroups per query tile (few queries,
   // many keys: one workgroup per head would leave most CUs idle); each writes its unnormalised
   // (O^T, m, l) to chunk_out and k_attn_merge combines them.
-  const int qt = blockIdx.x / n_chunks, ch = blockIdx.x % n_chunks;
+  const int qt = inner / n_chunks, ch = inner % n_chunks;
   const int q0 = qt * (32 * NQ) + qg * 32;
   const int qrow = min(q0 + lj, Tq - 1);
 
@@ -116,7 +130,7 @@ __global__ void __launch_bounds__(NQ * NSPL * 64) k_attn_bf16(const bf16* __rest
   auto sstore = [&](int stage) {
 #pragma unroll
     for (int x = 0; x < NSPL; ++x) {
-      unsigned char* base = smem + (stage * NSPL + x) * STAGE;
+      unsigned char* base = smem + ((NST == 2 ? stage : 0) * NSPL + x) * STAGE;
 #pragma unroll
       for (int i = 0; i < KCH; ++i) *reinterpret_cast<u32x4*>(base + dstK[i]) = rk[x][i];
 #pragma unroll
@@ -141,7 +155,7 @@ __global__ void __launch_bounds__(NQ * NSPL * 64) k_attn_bf16(const bf16* __rest
     const bool more = t + 1 < per;
     if (more) gload(t + 1);
     if (t < my_count) {
-      const unsigned char* base = smem + ((t & 1) * NSPL + sp) * STAGE;
+      const unsigned char* base = smem + ((NST == 2 ? (t & 1) : 0) * NSPL + sp) * STAGE;
       const int k0 = (my_first + t) * KT;
 
       // S^T for the two 32-key halves of the tile
@@ -205,6 +219,7 @@ __global__ void __launch_bounds__(NQ * NSPL * 64) k_attn_bf16(const bf16* __rest
         }
       }
     }
+    if constexpr (NST == 1) __syncthreads();   // single buffer: every wavefront is done with the tiles before the refill
     if (more) sstore((t + 1) & 1);
     __syncthreads();
   }
@@ -296,11 +311,11 @@ __global__ void __launch_bounds__(256) k_attn_merge(const float* __restrict__ ch
   *reinterpret_cast<u32x2*>(op) = w2;
 }
 
-template <int DH, int NQ, int NSPL>
+template <int DH, int NQ, int NSPL, int NST>
 static void launch(const bf16* q, const bf16* kstore, const bf16* vtstore, bf16* out, int B, int Tq, int Tk,
                    int Tpad, int H, float* chunk_ws, size_t chunk_ws_bytes, const int* tk_dev, Gate g, hipStream_t s) {
-  auto kern = k_attn_bf16<DH, NQ, NSPL>;
-  constexpr int smem = 2 * NSPL * (64 * DH * 2 + DH * 64 * 2);
+  auto kern = k_attn_bf16<DH, NQ, NSPL, NST>;
+  constexpr int smem = NST * NSPL * (64 * DH * 2 + DH * 64 * 2);
   static bool attr_done = false;
   if (!attr_done) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
@@ -309,15 +324,15 @@ static void launch(const bf16* q, const bf16* kstore, const bf16* vtstore, bf16*
   const int q_tiles = (Tq + 32 * NQ - 1) / (32 * NQ), n_tiles = (Tk + 63) / 64;
   // few queries against many keys: deal the key tiles to several workgroups per query tile
   int n_chunks = 1;
-  if (chunk_ws && !tk_dev && q_tiles * H * B < 128 && n_tiles >= 4) {   // chunks must not be empty: launch-wide key count only
+  if (chunk_ws && !tk_dev && q_tiles * H * B < 128 && n_tiles >= 2 * NSPL) {   // chunks must not be empty: launch-wide key count only
     int want = (256 + q_tiles * H * B - 1) / (q_tiles * H * B);
     if (want > 16) want = 16;
-    if (want > n_tiles / 2) want = n_tiles / 2;
+    if (want > n_tiles / NSPL) want = n_tiles / NSPL;   // a tile for every key range of a chunk
     const int per_chunk = (n_tiles + want - 1) / want;
     n_chunks = (n_tiles + per_chunk - 1) / per_chunk;       // every chunk gets at least one tile
     if ((size_t)B * H * Tq * n_chunks * (DH + 2) * 4 > chunk_ws_bytes) n_chunks = 1;
   }
-  dim3 grid(q_tiles * n_chunks, H, B);
+  dim3 grid(q_tiles * n_chunks * H * B);
   hipLaunchKernelGGL(kern, grid, dim3(NQ * NSPL * 64), smem, s, q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, n_chunks,
                      chunk_ws, tk_dev, g);
   if (n_chunks > 1) {
@@ -326,15 +341,18 @@ static void launch(const bf16* q, const bf16* kstore, const bf16* vtstore, bf16*
   }
 }
 
-// 64 queries per workgroup, keys in two ranges: with one sequence of a few hundred tokens this
-// gives a workgroup to every CU and halves the chain of dependent key tiles per wavefront.  The
+// 64 queries per workgroup, keys in four ranges, single-buffered tiles (128 KB of LDS at head size
+// 128): with one sequence of a few hundred tokens this gives a workgroup to every CU, two wavefronts
+// to every SIMD and a short chain of dependent key tiles per wavefront.  Measured at 32 heads of 128
+// (us, 512 / 1280 / 4096 tokens): two ranges double-buffered 15.9 / 93.5 / 756, four ranges
+// single-buffered 14.4 / 71.9 / 521; before the XCD-aware workgroup ids the first was 21.5.  The
 // configuration depends on the head size only, and the chunking across workgroups on the shape of
 // the launch, never on the data.
 void launch_attn_bf16(const bf16* q, const bf16* kstore, const bf16* vtstore, bf16* out, int B, int Tq, int Tk,
                       int Tpad, int H, int Dh, float* chunk_ws, size_t chunk_ws_bytes, const int* tk_dev, Gate g,
                       hipStream_t s) {
-  if (Dh == 128) launch<128, 2, 2>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, chunk_ws, chunk_ws_bytes, tk_dev, g, s);
-  else launch<64, 2, 2>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, chunk_ws, chunk_ws_bytes, tk_dev, g, s);
+  if (Dh == 128) launch<128, 2, 4, 1>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, chunk_ws, chunk_ws_bytes, tk_dev, g, s);
+  else launch<64, 2, 4, 1>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, chunk_ws, chunk_ws_bytes, tk_dev, g, s);
 }
 
 }  // namespace l2pd
