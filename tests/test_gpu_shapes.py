@@ -170,3 +170,30 @@ def test_8b_full_depth_step_against_both_oracle_precisions():
     rep = Pz.StepReport()
     Pz.check_step(rec16, taps, 0, w.model, w.threshold, 4e-2, rep)
     print("8b full depth decisions vs bf16-input oracle:", rep)
+
+
+def test_lm_head_wide_tile_batched_blocks():
+    # 17 sequences x 32 block rows = 544 rows reach the LM head's 256-row tiles (two full, one ragged);
+    # vocabulary 2000 leaves a ragged last 128-column tile.  Every sequence sits at its own state of block 1.
+    from tests.test_gpu_parity import small_bf16
+    w = small_bf16("lmwide", 2, 256, 4, 64, 448, 2000, 17, 24, 64, 32, tau=0.7)
+    w = dataclasses.replace(w, bias_from=40, bias_value=3.0)
+    eng, ora, flt = setup(w, max_batch=17)
+    fdev = {k: v.cuda() for k, v in flt.items()}
+    X = np.stack([Pz.random_state(w, 300 + b, 1, (5 * b) % 29, b) for b in range(w.batch)])
+    recs = [Pz.oracle_step_record(ora, X[b], w, Pz.np_filter(flt), 1) for b in range(w.batch)]
+    Xd = torch.tensor(X, dtype=torch.int32, device="cuda")
+    state = torch.tensor([[1, 3, 0]] * w.batch, dtype=torch.int32, device="cuda")
+    taps = eng.denoise_step(Xd, w.prompt_len, state, fdev, Pz.cfg_for(w), want_logits=True)
+    torch.cuda.synchronize()
+    rep = Pz.StepReport()
+    for b in range(w.batch):
+        Pz.check_step(recs[b], taps, b, w.model, w.threshold, Pz.tol_for(w.model), rep)
+    print("LM head, 544 rows:", rep)
+    assert rep.max_logit_err < 2e-2 and rep.steps == w.batch
+    # the fused reduction (no logits tap) must give the same confidences and tokens as the tapped call
+    Xd2 = torch.tensor(X, dtype=torch.int32, device="cuda")
+    state2 = torch.tensor([[1, 3, 0]] * w.batch, dtype=torch.int32, device="cuda")
+    taps2 = eng.denoise_step(Xd2, w.prompt_len, state2, fdev, Pz.cfg_for(w), want_logits=False)
+    assert torch.equal(taps["pred"], taps2["pred"]) and torch.equal(Xd, Xd2)
+    assert torch.allclose(taps["conf"], taps2["conf"], rtol=1e-5, atol=1e-7)
