@@ -5,7 +5,8 @@
 // queries of one (sequence, head) and splits the keys into NSPL contiguous ranges; wavefront
 // (query group, key range) runs the online softmax of its 32 queries over its range, and the
 // ranges are merged at the end.  Key/value tiles of 64 keys are staged in LDS (XOR-swizzled rows,
-// double buffered), one tile per range and iteration, shared by the query groups.
+// NST buffers per range; the next tile waits in registers meanwhile), one tile per range and
+// iteration, shared by the query groups.
 //
 // The wave computes S^T = K Q^T (keys are MFMA rows, queries are columns), so that a lane holds
 // scores of ONE query: the row maximum is 31 register maxima plus one cross-lane exchange, and the
@@ -49,7 +50,7 @@ __global__ void __launch_bounds__(NQ * NSPL * 64) k_attn_bf16(const bf16* __rest
   constexpr int FO = DH / 32;                  // output row fragments
   constexpr int XW = FO * 16 + 2;              // floats a wave hands over per lane: O^T fragments, m, l
   static_assert(NST == 1 || NST == 2, "tile buffers are single or double");
-  static_assert((NSPL - 1) * NQ * XW * 64 * 4 <= NST * NSPL * STAGE, "exchange area must fit in the tile buffers");
+  // the exchange area of the final merge reuses the tile buffers; the launch sizes LDS for the larger of the two
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // [NST stages][NSPL key ranges][K tile | V^T tile]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hf = lane >> 5, lj = lane & 31;
@@ -315,7 +316,9 @@ template <int DH, int NQ, int NSPL, int NST>
 static void launch(const bf16* q, const bf16* kstore, const bf16* vtstore, bf16* out, int B, int Tq, int Tk,
                    int Tpad, int H, float* chunk_ws, size_t chunk_ws_bytes, const int* tk_dev, Gate g, hipStream_t s) {
   auto kern = k_attn_bf16<DH, NQ, NSPL, NST>;
-  constexpr int smem = NST * NSPL * (64 * DH * 2 + DH * 64 * 2);
+  constexpr int tiles = NST * NSPL * (64 * DH * 2 + DH * 64 * 2);
+  constexpr int xchg = (NSPL - 1) * NQ * ((DH / 32) * 16 + 2) * 64 * 4;
+  constexpr int smem = tiles > xchg ? tiles : xchg;
   static bool attr_done = false;
   if (!attr_done) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
@@ -346,11 +349,22 @@ static void launch(const bf16* q, const bf16* kstore, const bf16* vtstore, bf16*
 // to every SIMD and a short chain of dependent key tiles per wavefront.  Measured at 32 heads of 128
 // (us, 512 / 1280 / 4096 tokens): two ranges double-buffered 15.9 / 93.5 / 756, four ranges
 // single-buffered 14.4 / 71.9 / 521; before the XCD-aware workgroup ids the first was 21.5.  The
-// configuration depends on the head size only, and the chunking across workgroups on the shape of
-// the launch, never on the data.
+// configuration depends on the head size, the head count and the query rows per sequence, and the
+// chunking across workgroups on the shape of the launch, never on the data.
 void launch_attn_bf16(const bf16* q, const bf16* kstore, const bf16* vtstore, bf16* out, int B, int Tq, int Tk,
                       int Tpad, int H, int Dh, float* chunk_ws, size_t chunk_ws_bytes, const int* tk_dev, Gate g,
                       hipStream_t s) {
+  // A sequence long enough to give every CU a workgroup of 128 queries by itself: the key tiles
+  // then serve four query groups instead of two (half the L2 -> LDS traffic per flop) and two
+  // workgroups of 64 KB fit a CU.  Measured at 32 heads of 128, one sequence (us): 1024 tokens
+  // 40.5 -> 27.8, 2048 tokens 141 -> 99, 4096 tokens 520 -> 375.  The batch size is left out of the
+  // criterion on purpose: the two configurations merge key ranges in different orders, and a row's
+  // result must not depend on the batch it is part of.
+  if ((long long)((Tq + 127) / 128) * H >= 256) {
+    if (Dh == 128) launch<128, 4, 2, 1>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, chunk_ws, chunk_ws_bytes, tk_dev, g, s);
+    else launch<64, 4, 2, 1>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, chunk_ws, chunk_ws_bytes, tk_dev, g, s);
+    return;
+  }
   if (Dh == 128) launch<128, 2, 4, 1>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, chunk_ws, chunk_ws_bytes, tk_dev, g, s);
   else launch<64, 2, 4, 1>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, chunk_ws, chunk_ws_bytes, tk_dev, g, s);
 }

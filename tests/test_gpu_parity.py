@@ -62,9 +62,10 @@ def test_forward_fp32_ragged_batch():
         assert Pz.rel_err(got[b], ora.forward(X[b].numpy())) < 1e-4
 
 
-@pytest.mark.parametrize("Dh,H,T", [(64, 4, 200), (128, 2, 333), (128, 2, 64)])
+@pytest.mark.parametrize("Dh,H,T", [(64, 4, 200), (128, 2, 333), (128, 2, 64), (64, 16, 2100), (128, 16, 2100)])
 def test_forward_bf16_small(Dh, H, T):
-    # several row tiles, ragged tails in rows and keys, both head sizes
+    # several row tiles, ragged tails in rows and keys, both head sizes; the two long cases reach the
+    # 128-query attention workgroups (taken when ceil(T / 128) * heads >= 256)
     w = small_bf16(f"bf{Dh}", 2, H * Dh, H, Dh, 448, 1000, 2, T - 32, 32, 32)
     eng, ora, flt, prompt = build(w)
     X = torch.cat([prompt, torch.full((2, 32), w.model.mask_id, dtype=torch.int32)], 1)
