@@ -99,6 +99,9 @@ def test_decode_argument_checks_return_before_any_launch():
         assert gen(ok, f=filt(4, 32, 2048)) == Bd.L2PD_EINVAL                      # hidden too wide
         assert gen(Bd.Engine.cfg_struct(64, 32, 0.5, prefix_cache=True)) == Bd.L2PD_EINVAL  # ctx has no cache
         assert gen(Bd.Engine.cfg_struct(64, 32, 0.5, bias=(m.vocab, 0, 1.0))) == Bd.L2PD_EINVAL
+        assert gen(Bd.Engine.cfg_struct(64, 32, 0.5, ragged=3)) == Bd.L2PD_EINVAL  # no such batch schedule
+        assert gen(Bd.Engine.cfg_struct(64, 32, 0.5, ragged=-1)) == Bd.L2PD_EINVAL
+        assert gen(Bd.Engine.cfg_struct(64, 32, 0.5, eotp=3)) == Bd.L2PD_EINVAL    # no such EoTP mode
         assert gen(ok, prompt=None) == Bd.L2PD_EINVAL
         assert gen(ok, out=None) == Bd.L2PD_EINVAL
         assert lib.l2pd_forward(ctx, 0x1000, 1, 97, 0, 1, 0x1000, None) == Bd.L2PD_EINVAL   # T > max_seq
