@@ -5,8 +5,9 @@
 //                                                               (keys > rows: a block-only step over a K/V store)
 //   kernel_bench mfma                                     register-resident MFMA stream + shader clock
 //
-// "layer" calls the same launchers the library calls (same tile choice), on random operands that
-// stay resident in HBM.  "mfma" shows what bounds them on a power-limited part: the same instruction
+// "layer" calls the same launchers the library calls (same tile choice), in the order of a layer, on
+// random weights and a random residual stream that stay resident in HBM (each kernel consumes what the
+// one before it produced).  "mfma" shows what bounds them on a power-limited part: the same instruction
 // stream runs at a lower shader clock when the operands are random instead of constant.
 #include "common.h"
 
@@ -90,7 +91,17 @@ static int bench_layer(int rows, int d, int F, int H, int keys) {
   CK(hipMalloc(&h, (size_t)rows * d * 4));
   CK(hipMalloc(&cs, (size_t)Tpad * (Dh / 2) * 4));
   CK(hipMalloc(&sn, (size_t)Tpad * (Dh / 2) * 4));
-  CK(hipMemset(h, 0, (size_t)rows * d * 4));
+  {
+    // a random residual stream: the RMSNorm timed first writes xn from it, and every later kernel works
+    // on what its predecessor left, so no kernel here sees constant (cheap to switch) operands
+    std::vector<float> hv((size_t)rows * d);
+    unsigned sd = 11;
+    for (auto& v : hv) {
+      sd = sd * 1664525u + 1013904223u;
+      v = ((int)(sd >> 9) % 2001 - 1000) * 0.001f;
+    }
+    CK(hipMemcpy(h, hv.data(), hv.size() * 4, hipMemcpyHostToDevice));
+  }
   CK(hipMemset(ks, 0, (size_t)Tpad * d * 2));
   CK(hipMemset(vts, 0, (size_t)Tpad * d * 2));
   {
