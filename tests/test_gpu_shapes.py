@@ -197,3 +197,46 @@ def test_lm_head_wide_tile_batched_blocks():
     taps2 = eng.denoise_step(Xd2, w.prompt_len, state2, fdev, Pz.cfg_for(w), want_logits=False)
     assert torch.equal(taps["pred"], taps2["pred"]) and torch.equal(Xd, Xd2)
     assert torch.allclose(taps["conf"], taps2["conf"], rtol=1e-5, atol=1e-7)
+
+
+def _full_size_decode(name, batch, rows_identical):
+    """Whole decode of a named workload at its full depth and batch, in the launch configuration that
+    bench.py times; checked through properties that hold at any size (the oracle would need hours)."""
+    w = synth.WORKLOADS[name]
+    if batch != w.batch:
+        w = dataclasses.replace(w, batch=batch)
+    eng = Bd.engine_for(w, SEED, "cuda")
+    flt = synth.make_filter(SEED, w.block_len, w.filter_hidden, "cuda")
+    prompt = synth.make_prompt(SEED, w.batch, w.prompt_len, w.prompt_hi, "cuda")
+    if rows_identical:
+        prompt = prompt[:1].repeat(w.batch, 1).contiguous()
+    tok, st, dl = eng.generate(prompt, flt, Pz.cfg_for(w))
+    torch.cuda.synchronize()
+    return w, tok.cpu().numpy(), st.cpu().numpy(), dl.cpu().numpy()
+
+
+def _check_eotp_properties(w, tok, steps, dlen):
+    m, s = w.model, w.block_len
+    stop_block = w.bias_from // s                      # the block that holds the first forced end-of-text
+    for b in range(tok.shape[0]):
+        n = int(dlen[b])
+        assert n % s == 0 and n == (stop_block + 1) * s, (b, n)
+        assert not np.any(tok[b, :n] == m.mask_id)     # everything up to the stop is decoded
+        assert np.all(tok[b, n:] == m.mask_id)         # nothing after it was touched (Alg. 3 breaks)
+        assert np.all(tok[b, w.bias_from:n] == m.eos_id)   # +20 on one logit of a random-init head decides
+        assert n // s <= steps[b] <= n                 # at least one step per block, at most one per token
+
+
+def test_full_size_eotp_workload_properties():
+    w, tok, steps, dlen = _full_size_decode("8b_g1024_eotp", 1, False)
+    _check_eotp_properties(w, tok, steps, dlen)
+    print(f"8b_g1024_eotp at full depth: {int(steps[0])} steps, {int(dlen[0])} tokens")
+
+
+def test_full_size_batched_prefix_cache_properties():
+    # 32 sequences, 32 layers, block 64, prefix cache: identical prompts must give identical rows
+    # (rows of a batch never interact and run through the same kernels), and every row obeys Alg. 3
+    w, tok, steps, dlen = _full_size_decode("8b_b32_prefix", 32, True)
+    _check_eotp_properties(w, tok, steps, dlen)
+    assert np.all(tok == tok[0]) and np.all(steps == steps[0]) and np.all(dlen == dlen[0])
+    print(f"8b_b32_prefix at full size: {int(steps[0])} steps per sequence, {int(dlen[0])} tokens each")
