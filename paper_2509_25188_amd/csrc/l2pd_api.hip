@@ -646,7 +646,12 @@ int32_t l2pd_generate(l2pd_ctx* c, const int32_t* prompt_dev, int32_t B, int32_t
   const int sl = cfg->block_len, G = cfg->gen_len, nb = G / sl;
   launch_init_decode(X, prompt_dev, B, P, G, c->m.mask_id, state, ctl, s);
   const StepTaps no_taps = {nullptr, nullptr, nullptr, nullptr, nullptr};
-  const int CHUNK = 4;   // steps enqueued between two looks at the control block
+  // Steps enqueued between two looks at the control block.  The host always looks at the chunk
+  // before the one it has just enqueued, so a finished block (or decode) is noticed one to two chunks
+  // late and the steps enqueued meanwhile run as gated launches (a few hundred launches of a
+  // microsecond or two each per step).  The cached modes pay that at the end of every block, so
+  // they look after every step; full recompute pays it once per decode.
+  const int CHUNK = cfg->kv_cache ? 1 : 4;
 
   // Enqueue `CHUNK` steps, then a copy of the control block to pinned memory; look at the copy of
   // the chunk before, so the device always has a chunk queued while the host waits.
