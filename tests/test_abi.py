@@ -113,3 +113,30 @@ def test_decode_argument_checks_return_before_any_launch():
         assert lib.l2pd_profile_select(ctx, Bd.K_GEMM_GATEUP) == Bd.L2PD_OK
     finally:
         lib.l2pd_destroy(ctx)
+
+
+def test_mode_combinations_that_are_not_built_are_refused():
+    # the cached modes rebuild their K/V store for one common block, and step-granular EoTP resizes the
+    # forward every step: per-sequence block pointers / step-granular EoTP with a cache must say so
+    lib = Bd.lib()
+    m = synth.WORKLOADS["tiny"].model
+    d = Bd.model_desc(m)
+    n = lib.l2pd_workspace_bytes(C.byref(d), 2, 96, 1)
+    w, keep = fake_weights(m.n_layers)
+    ctx = C.c_void_p()
+    assert lib.l2pd_create(C.byref(d), C.byref(w), 2, 96, 1, 0x10000, n, C.byref(ctx)) == Bd.L2PD_OK
+    try:
+        f = Bd.Filter(2, 32, 64)
+        for k in range(2):
+            f.w_dev[k] = 0x1000
+            f.b_dev[k] = 0x1000
+
+        def gen(cfg):
+            return lib.l2pd_generate(ctx, 0x1000, 1, 32, C.byref(cfg), C.byref(f), 0x1000, None, None, None)
+
+        for cache in ("prefix_cache", "dual_cache"):
+            assert gen(Bd.Engine.cfg_struct(64, 32, 0.5, ragged=Bd.RAGGED_BLOCKS, **{cache: True})) == Bd.L2PD_ENOTIMPL
+            assert gen(Bd.Engine.cfg_struct(64, 32, 0.5, ragged=Bd.RAGGED_COMPACT, **{cache: True})) == Bd.L2PD_ENOTIMPL
+            assert gen(Bd.Engine.cfg_struct(64, 32, 0.5, eotp=Bd.EOTP_STEP, **{cache: True})) == Bd.L2PD_ENOTIMPL
+    finally:
+        lib.l2pd_destroy(ctx)
