@@ -45,3 +45,46 @@ def test_random_bf16_shape_forward(seed):
     if B > 1:
         alone = eng.forward(X[B - 1:B].cuda()).cpu().numpy()[0]
         assert Pz.rel_err(alone, got[B - 1]) < 2e-2
+
+
+def draw_step(seed):
+    r = np.random.default_rng(3000 + seed)
+    Dh = int(r.choice([64, 128]))
+    H = int(r.choice([1, 2, 4]))
+    m = synth.ModelShape(2, H * Dh, H, Dh, 64 * int(r.integers(2, 12)), int(r.integers(200, 2500)), 0, 0, dtype="bf16")
+    m = synth.ModelShape(m.n_layers, m.d_model, H, Dh, m.d_ffn, m.vocab, m.vocab - 1, m.vocab - 2, dtype="bf16")
+    s = int(r.choice([8, 16, 32, 64]))
+    nb = int(r.integers(1, 5))
+    cache = int(r.integers(0, 3))
+    w = synth.Workload(f"rs{seed}", m, int(r.integers(1, 4)), int(r.integers(1, 200)), s * nb, s, int(r.choice([16, 64])),
+                       float(r.choice([0.3, 0.6])), prefix_cache=cache == 1, dual_cache=cache == 2,
+                       bias_from=int(r.integers(0, s * nb)), bias_value=float(r.choice([0.0, 4.0])),
+                       prompt_hi=m.vocab - 2)
+    return w, int(r.integers(0, nb)), int(r.integers(1, 5))
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_random_bf16_shape_denoise_step(seed):
+    # one teacher-forced step of every sequence of a batch, all in the same block (lock step), each with
+    # its own number of committed positions; cached modes rebuild their store from the given tokens first
+    w, block, depth = draw_step(seed)
+    weights = synth.make_weights(w.model, 90 + seed, "cpu", lm_head_scale=8.0)
+    ora = Pz.oracle_model(w.model, weights)
+    eng = Bd.Engine(w.model, Pz.to_dev(weights), w.batch, w.prompt_len + w.gen_len, w.prefix_cache or w.dual_cache)
+    flt = synth.make_filter(70 + seed, w.block_len, w.filter_hidden, "cpu", n_layers=depth)
+    fdev = {k: v.cuda() for k, v in flt.items()}
+    r = np.random.default_rng(4000 + seed)
+    X = np.stack([Pz.random_state(w, 100 * seed + b, block, int(r.integers(0, w.block_len)), b) for b in range(w.batch)])
+    recs = [Pz.oracle_step_record(ora, X[b], w, Pz.np_filter(flt), block) for b in range(w.batch)]
+    Xd = torch.tensor(X, dtype=torch.int32, device="cuda")
+    state = torch.tensor([[block, 3, 0]] * w.batch, dtype=torch.int32, device="cuda")
+    taps = eng.denoise_step(Xd, w.prompt_len, state, fdev, Pz.cfg_for(w), want_logits=True)
+    torch.cuda.synchronize()
+    rep = Pz.StepReport()
+    for b in range(w.batch):
+        Pz.check_step(recs[b], taps, b, w.model, w.threshold, Pz.tol_for(w.model), rep)
+    m = w.model
+    print(f"d={m.d_model} H={m.n_heads}x{m.head_dim} F={m.d_ffn} V={m.vocab} B={w.batch} P={w.prompt_len} G={w.gen_len} "
+          f"s={w.block_len} block={block} cache={'prefix' if w.prefix_cache else 'dual' if w.dual_cache else 'none'} "
+          f"depth={depth}: {rep}")
+    assert rep.steps == w.batch and rep.max_logit_err < 2e-2
