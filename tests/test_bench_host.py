@@ -27,7 +27,7 @@ def test_step_flops_of_the_benched_workload():
     assert lin == 2.0 * T * L * (4 * d * d + 3 * d * F)
     assert attn == 4.0 * T * T * d * L
     assert head == 2.0 * 32 * d * V
-    assert abs((lin + attn + head) / 1e12 - 7.317) < 1e-3        # the figure the design doc and the bench line quote
+    assert abs((lin + attn + head) / 1e12 - 7.317) < 1e-3        # the figure the bench line reports as step_tflop
 
 
 def test_hbm_counter_figure_follows_the_kernel_source(tmp_path, monkeypatch):
