@@ -142,7 +142,8 @@ def silu(x):
 
 
 def sigmoid(x):
-    return 1.0 / (1.0 + np.exp(-x))
+    with np.errstate(over="ignore"):        # exp(-x) may overflow to inf for very negative x: the result is then 0, as it should be
+        return 1.0 / (1.0 + np.exp(-x))
 
 
 # --------------------------------------------------------------------------- mask predictor M(X)
