@@ -54,3 +54,39 @@ def test_random_configuration_against_the_oracle(seed):
         resp, steps, dlen = Pz.oracle_generate(ora, prompt[b].numpy(), w, Pz.np_filter(flt))
         np.testing.assert_array_equal(tok[b], resp, err_msg=what)
         assert int(st[b]) == steps and int(dl[b]) == dlen, what
+
+
+def test_one_context_serves_changing_calls():
+    # one context (created with K/V stores) takes a run of calls that differ in batch, lengths, block,
+    # cache mode, EoTP mode and batch schedule, with forwards and single steps in between: nothing a call
+    # leaves behind (pending partials, stores, control block, compaction copies) may leak into the next
+    weights = synth.make_weights(TINY, 911, "cpu", lm_head_scale=25.0)
+    ora = Pz.oracle_model(TINY, weights)
+    eng = Bd.Engine(TINY, Pz.to_dev(weights), 3, 40 + 128, True)
+    for seed in (3, 7, 10, 12, 0, 17, 22, 9, 15, 1):
+        w, ragged, depth = draw(seed)
+        flt = synth.make_filter(500 + seed, w.block_len, w.filter_hidden, "cpu", n_layers=depth)
+        fdev = {k: v.cuda() for k, v in flt.items()}
+        prompt = synth.make_prompt(300 + seed, w.batch, w.prompt_len, w.prompt_hi, "cpu")
+        cfg = Pz.cfg_for(w)
+        cfg.ragged = ragged
+        tok, st, dl = eng.generate(prompt.cuda(), fdev, cfg)
+        tok, st, dl = tok.cpu().numpy(), st.cpu().numpy(), dl.cpu().numpy()
+        for b in range(w.batch):
+            resp, steps, dlen = Pz.oracle_generate(ora, prompt[b].numpy(), w, Pz.np_filter(flt))
+            np.testing.assert_array_equal(tok[b], resp, err_msg=f"seed {seed}")
+            assert int(st[b]) == steps and int(dl[b]) == dlen, seed
+        # a forward and a teacher-forced step of another shape in between
+        X = synth.make_prompt(seed, 2, 50 + seed, 1022, "cpu")
+        got = eng.forward(X.cuda()).cpu().numpy()
+        assert Pz.rel_err(got[1], ora.forward(X[1].numpy())) < 1e-4
+        w2 = synth.Workload("mid_call", TINY, 1, 9, 64, 16, 32, 0.5, dual_cache=seed % 2 == 0, prompt_hi=1022)
+        f2 = synth.make_filter(seed, 16, 32, "cpu")
+        Xs = Pz.random_state(w2, seed, 2, 5)
+        rec = Pz.oracle_step_record(ora, Xs, w2, Pz.np_filter(f2), 2)
+        Xd = torch.tensor(Xs, dtype=torch.int32, device="cuda").view(1, -1)
+        state = torch.tensor([[2, 1, 0]], dtype=torch.int32, device="cuda")
+        taps = eng.denoise_step(Xd, w2.prompt_len, state, {k: v.cuda() for k, v in f2.items()}, Pz.cfg_for(w2),
+                                want_logits=True)
+        rep = Pz.StepReport()
+        assert Pz.check_step(rec, taps, 0, TINY, w2.threshold, 1e-4, rep)
