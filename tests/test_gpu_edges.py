@@ -91,3 +91,27 @@ def test_refused_arguments_launch_nothing():
     # the engine still works afterwards
     tok, st, dl = eng.generate(prompt.cuda(), fdev, Pz.cfg_for(w))
     assert int(dl[0]) == w.gen_len
+
+
+def test_calls_follow_the_callers_stream():
+    # everything a call enqueues (and the host's own polling of the control block) goes to the stream
+    # it is given: a decode on a side stream gives the same result as on the default stream, and the
+    # default stream stays free to do unrelated work meanwhile
+    w = synth.Workload("tiny_stream", TINY, 2, 17, 64, 16, 32, 0.5, prompt_hi=1022)
+    eng, ora, flt, prompt = build(w, lm_head_scale=25.0)
+    fdev = {k: v.cuda() for k, v in flt.items()}
+    cfg = Pz.cfg_for(w)
+    pd = prompt.cuda()
+    ref = eng.generate(pd, fdev, cfg)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        got = eng.generate(pd, fdev, cfg)
+        lg = eng.forward(torch.cat([pd, torch.full((2, 64), w.model.mask_id, dtype=torch.int32, device="cuda")], 1))
+    busy = torch.ones(1 << 20, device="cuda").cumsum(0)          # the default stream does something else
+    side.synchronize()
+    torch.cuda.synchronize()
+    for a, b in zip(ref, got):
+        assert torch.equal(a, b)
+    assert torch.isfinite(lg).all() and float(busy[-1]) == float(1 << 20)
