@@ -170,7 +170,10 @@ int32_t l2pd_forward(l2pd_ctx* ctx, const int32_t* tokens_dev, int32_t B, int32_
  *   filt_dev [B, s] (filter output p), unmask_dev [B, s] (1 where unmasked by this step).
  * With a cached mode in cfg.kv_cache the call first reads state_dev back (it synchronises the
  * stream) and, unless cfg.keep_kv is set, rebuilds the K/V store for the active block from the
- * tokens as they are. */
+ * tokens as they are.
+ * In full recompute with L2PD_EOTP_OFF or L2PD_EOTP_BLOCK the call only enqueues kernels (no host
+ * synchronisation, no copies, no memset nodes), so after one eager call on a context it may be
+ * captured into a HIP graph and replayed: every replay is the next step on the same buffers. */
 int32_t l2pd_denoise_step(l2pd_ctx* ctx, int32_t* tokens_dev, int32_t B, int32_t prompt_len,
                           const l2pd_decode_cfg* cfg, const l2pd_filter* filter, int32_t* state_dev,
                           float* logits_dev, float* conf_dev, int32_t* pred_dev, float* filt_dev,

@@ -115,3 +115,45 @@ def test_calls_follow_the_callers_stream():
     for a, b in zip(ref, got):
         assert torch.equal(a, b)
     assert torch.isfinite(lg).all() and float(busy[-1]) == float(1 << 20)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_denoise_step_can_be_captured_in_a_hip_graph(bf16):
+    # a serving loop may capture the full-recompute step (no host synchronisation, no memset nodes: the
+    # library clears with fill kernels) and replay it; every replay must equal the eager step, with the
+    # program's own eager work and synchronisations between the replays
+    if bf16:
+        w = small_bf16("bf_graph", 2, 256, 4, 64, 448, 2000, 2, 40, 64, 32, tau=0.7)
+    else:
+        w = synth.Workload("tiny_graph", TINY, 2, 21, 64, 32, 32, 0.5, prompt_hi=1022)
+    eng, ora, flt, prompt = build(w, lm_head_scale=25.0)
+    fdev = {k: v.cuda() for k, v in flt.items()}
+    cfg = Pz.cfg_for(w)
+    X0 = torch.cat([prompt, torch.full((w.batch, w.gen_len), w.model.mask_id, dtype=torch.int32)], 1).cuda()
+    S0 = torch.zeros((w.batch, 3), dtype=torch.int32, device="cuda")
+    # eager reference: the state after each of six steps
+    Xe, Se = X0.clone(), S0.clone()
+    want = []
+    for _ in range(6):
+        eng.denoise_step(Xe, w.prompt_len, Se, fdev, cfg)
+        want.append((Xe.clone(), Se.clone()))
+    torch.cuda.synchronize()
+    Xg, Sg = X0.clone(), S0.clone()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        eng.denoise_step(Xg, w.prompt_len, Sg, fdev, cfg)          # warm-up on the capture stream, then rewind
+        Xg.copy_(X0)
+        Sg.copy_(S0)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            eng.denoise_step(Xg, w.prompt_len, Sg, fdev, cfg)
+    torch.cuda.synchronize()
+    for k in range(6):
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Xg, want[k][0]) and torch.equal(Sg, want[k][1]), f"replay {k}"
+        other = eng.forward(X0)                                     # eager work of the same context in between
+        torch.cuda.synchronize()
+        assert torch.isfinite(other).all()
