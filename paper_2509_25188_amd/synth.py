@@ -85,6 +85,8 @@ WORKLOADS: Dict[str, Workload] = {
                                    bias_from=300, bias_value=20.0, prompt_hi=126081),
     "8b_g1024_dual": Workload("8b_g1024_dual", _8B, 1, 256, 1024, 32, 128, 0.9, eotp=True, dual_cache=True,
                               bias_from=300, bias_value=20.0, prompt_hi=126081),
+    "8b_b8_g1024_dual": Workload("8b_b8_g1024_dual", _8B, 8, 256, 1024, 32, 128, 0.9, eotp=True, dual_cache=True,
+                                 bias_from=300, bias_value=20.0, prompt_hi=126081),
     "8b_b32_prefix": Workload("8b_b32_prefix", _8B, 32, 512, 512, 64, 128, 0.9, eotp=True,
                               prefix_cache=True, bias_from=400, bias_value=20.0, prompt_hi=126081),
 }
