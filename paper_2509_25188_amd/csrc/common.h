@@ -143,6 +143,7 @@ void launch_gemm_partial_bf16(const bf16* A, const bf16* W, float* parts, size_t
 constexpr int kSkinnyRows = 64;
 constexpr int kSkinnyRowsAttn = 64;   // B * Tq up to which attention may chunk the keys across workgroups
 int skinny_splits(int N, int K);
+int wide_splits(int M, int N, int K);   // split-K depth of the wide path's [d, d] / [d, F] projections, at most 8
 void launch_gemm_skinny_bf16(const bf16* A, const bf16* w0, const bf16* w1, const bf16* w2, int n_sub, float* parts,
                              size_t part_stride, int M, int N, int K, int splits, Gate g, hipStream_t s);
 // sums of the skinny GEMM's partials -> rotated q, K store, V^T store / SiLU(gate) * up

@@ -116,9 +116,8 @@ static int bench_layer(int rows, int d, int F, int H, int keys) {
   // routing and split counts as in the library: the few-row path up to kSkinnyRows rows, else the wide path,
   // which splits K in two on the [d, d] and [d, F] projections when there are few row tiles
   const bool skinny = rows <= kSkinnyRows;
-  const int tiles = ((rows + 127) / 128) * (d / 128);
-  const int so = skinny ? skinny_splits(d, d) : ((tiles < 256 && (d / 64) % 2 == 0) ? 2 : 1);
-  const int sd = skinny ? skinny_splits(d, F) : ((tiles < 256 && (F / 64) % 2 == 0) ? 2 : 1);
+  const int so = skinny ? skinny_splits(d, d) : wide_splits(rows, d, d);
+  const int sd = skinny ? skinny_splits(d, F) : wide_splits(rows, d, F);
   const int sq = skinny ? skinny_splits(3 * d, d) : 1, sg = skinny ? skinny_splits(2 * F, d) : 1;
   size_t pbytes = (size_t)2 * rows * d * 4;
   for (size_t b : {(size_t)sq * rows * 3 * d * 4, (size_t)sg * rows * 2 * F * 4, (size_t)so * rows * d * 4,

@@ -4,6 +4,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <algorithm>
 #include <vector>
 
 #include "common.h"
@@ -133,7 +134,15 @@ Layout make_layout(const l2pd_model_desc& m, int max_batch, int max_seq, int cac
       const size_t b = (size_t)skinny_splits(sh[0], sh[1]) * kSkinnyRows * sh[0] * 4;
       if (b > skinny) skinny = b;
     }
-    const size_t wide = 2 * rows * d * 4;
+    // wide path: the [d, d] and [d, F] projections split K as far as wide_splits says for the number of
+    // rows at hand (it depends on the count of 128-row tiles only, so the top of every bucket is the worst case)
+    size_t wide = 0;
+    for (size_t top = 128;; top += 128) {
+      const size_t M = top < rows ? top : rows;
+      const int S = std::max(wide_splits((int)M, m.d_model, m.d_model), wide_splits((int)M, m.d_model, m.d_ffn));
+      wide = std::max(wide, (size_t)S * M * d * 4);
+      if (top >= rows) break;
+    }
     L.parts = c.take(wide > skinny ? wide : skinny);
     L.attn_ws_bytes = attn_chunk_ws_bytes(m.n_heads, m.head_dim);
     L.attn_ws = c.take(L.attn_ws_bytes);
@@ -290,11 +299,10 @@ void run_layers(l2pd_ctx* c, const Pass& p, Gate g, hipStream_t s) {
       { Timed t(c, L2PD_K_ATTN, s);
         launch_attn_bf16(q, ks, vts, ao, p.B, p.Tq, p.Tk, L.Tpad, H, Dh, c->at<float>(L.attn_ws), L.attn_ws_bytes,
                          p.tk_dev, g, s); }
-      // Few row tiles leave half of the CUs idle on the [d, d] and [d, F] projections: split K in two
-      // (wide path), or as far as skinny_splits says (few-row path).
-      const int tiles = ((rows + 127) / 128) * (d / 128);
-      const int so = skinny ? skinny_splits(d, d) : ((tiles < 256 && (d / 64) % 2 == 0) ? 2 : 1);
-      const int sd = skinny ? skinny_splits(d, F) : ((tiles < 256 && (F / 64) % 2 == 0) ? 2 : 1);
+      // Few row tiles leave CUs idle on the [d, d] and [d, F] projections: split K as far as
+      // wide_splits (wide path) or skinny_splits (few-row path) says.
+      const int so = skinny ? skinny_splits(d, d) : wide_splits(rows, d, d);
+      const int sd = skinny ? skinny_splits(d, F) : wide_splits(rows, d, F);
       const size_t stride_d = (size_t)rows * d;
       { Timed t(c, L2PD_K_GEMM_O, s);
         if (skinny)
