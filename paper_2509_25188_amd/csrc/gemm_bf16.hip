@@ -646,10 +646,10 @@ void launch_gemm_lmhead_bf16(const bf16* A, const bf16* W, int M, int V, int K, 
   // 128 columns per tile in every configuration: the partial (max, sum, argmax) triples are per 128 logits
   if (M <= 32)
     launch<32, 128, 64, 1, 4, 4, EPI_LMHEAD>(a, s);
-  else if (M < 512)
+  else if (M <= 128)
     launch<128, 128, 64, 2, 2, 4, EPI_LMHEAD>(a, s);
   else
-    launch<256, 128, 32, 4, 2, 6, EPI_LMHEAD>(a, s);   // batched blocks (32 sequences x 64 rows): more reuse per weight byte
+    launch<256, 128, 32, 4, 2, 6, EPI_LMHEAD>(a, s);   // batched blocks: the 1 GB of weights is read once per 256 rows
 }
 
 }  // namespace l2pd
