@@ -6,7 +6,10 @@
  * bidirectional transformer forward (the paper's mask predictor M(X)), the
  * greedy estimate and confidence of the active block (Eq. 3, Eq. 4), the
  * learned filter f_theta on the block's confidences (Sec. 3.2), the unmask
- * update (Alg. 2) and End-of-Text Prediction (Sec. 3.3, Alg. 3 in App. A).
+ * update (Alg. 2) and End-of-Text Prediction (Sec. 3.3, Alg. 3 in App. A);
+ * and the training side of the method: the Extremely Greedy Parallel rollout
+ * that labels confidences (Sec. 3.1.3, Alg. 1) and the fit of the filter to
+ * those labels (Eq. 6, AdamW as in Sec. 4.1).
  *
  * Conventions for every entry point
  *   - Pointers named *_dev are device (HBM) memory owned by the caller; the
@@ -37,7 +40,7 @@ typedef enum {
   L2PD_EINVAL = -1,   /* bad argument (NULL pointer, inconsistent sizes, NaN threshold, ...) */
   L2PD_ENOMEM = -2,   /* workspace too small */
   L2PD_EHIP = -3,     /* a HIP runtime call failed */
-  L2PD_ENOTIMPL = -4  /* shape outside what the kernels support */
+  L2PD_ENOTIMPL = -4  /* shape outside what the kernels support, or a combination of modes that is not built */
 } l2pd_status;
 
 enum { L2PD_FP32 = 0, L2PD_BF16 = 1 };
