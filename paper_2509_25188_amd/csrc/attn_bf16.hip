@@ -319,11 +319,8 @@ static void launch(const bf16* q, const bf16* kstore, const bf16* vtstore, bf16*
   constexpr int tiles = NST * NSPL * (64 * DH * 2 + DH * 64 * 2);
   constexpr int xchg = (NSPL - 1) * NQ * ((DH / 32) * 16 + 2) * 64 * 4;
   constexpr int smem = tiles > xchg ? tiles : xchg;
-  static bool attr_done = false;
-  if (!attr_done) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    attr_done = true;
-  }
+  static DynLdsAttr attr;
+  attr.ensure(reinterpret_cast<const void*>(kern), smem);
   const int q_tiles = (Tq + 32 * NQ - 1) / (32 * NQ), n_tiles = (Tk + 63) / 64;
   // few queries against many keys: deal the key tiles to several workgroups per query tile
   int n_chunks = 1;

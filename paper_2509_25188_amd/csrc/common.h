@@ -4,6 +4,8 @@
 #include <hip/hip_bf16.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "../../include/l2pd.h"
 
 namespace l2pd {
@@ -38,6 +40,20 @@ __device__ __forceinline__ int map_row(const RowMap& m, int r, const int* ctl) {
   return (r / m.rows_per_seq) * m.seq_stride + m.off_base + gb * m.off_per_gb + (r % m.rows_per_seq);
 }
 
+// Raises a kernel's dynamic-LDS limit once per device: the attribute belongs to the device's copy of
+// the kernel, and launchers may be called from several host threads (setting it twice is harmless).
+struct DynLdsAttr {
+  std::atomic<unsigned long long> done{0};
+  void ensure(const void* kernel, int bytes) {
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    const unsigned long long bit = 1ull << (dev & 63);
+    if (done.load(std::memory_order_acquire) & bit) return;
+    (void)hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    done.fetch_or(bit, std::memory_order_release);
+  }
+};
+
 // ---- small kernels (kernels_misc.hip) ----
 void launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t s);
 void launch_rope_table(float* cos_t, float* sin_t, int max_pos, int head_dim, float base, hipStream_t s);
@@ -46,10 +62,12 @@ void launch_init_decode(int32_t* X, const int32_t* prompt, int B, int P, int G, 
 void launch_prepare(const int32_t* state, int B, int n_blocks, int ragged, int* ctl, hipStream_t s);
 void launch_embed(float* h, const void* emb, int dtype, const int32_t* tokens, RowMap tokmap, int rows, int d,
                   Gate g, hipStream_t s);
-// h (+= part[0] + ... + part[n_parts-1] in that order when given; written back) -> y = rmsnorm(h) * gain,
-// rows taken through `src`.  part z is at parts + z * part_stride, laid out like h.
+// h (+= part[0] + ... + part[n_parts-1] in that order when given) -> y = rmsnorm(h) * gain, rows taken
+// through `src`.  part z is at parts + z * part_stride, laid out like h.  The sum is written back to h
+// when `write_back` is set; the final norm before the LM head leaves h alone (h is dead after it, and
+// two head rows may map to one row of h, so a write-back would race).
 void launch_rmsnorm(float* h, const float* parts, int n_parts, size_t part_stride, RowMap src, const void* gain,
-                    int dtype, void* y, int rows, int d, float eps, Gate g, hipStream_t s);
+                    int dtype, void* y, int rows, int d, float eps, bool write_back, Gate g, hipStream_t s);
 constexpr int kFilterMaxLayers = 4;
 struct UpdateArgs {
   int32_t* X;            // [B, T]

@@ -516,11 +516,8 @@ template <int BM, int BN, int BK, int WM, int WN, int NS, int EPI>
 static void launch(GemmArgs& a, hipStream_t s) {
   auto kern = k_gemm_bf16<BM, BN, BK, WM, WN, NS, EPI>;
   constexpr int smem = NS * (BM + BN) * BK * 2;
-  static bool attr_done = false;
-  if (!attr_done) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    attr_done = true;
-  }
+  static DynLdsAttr attr;
+  attr.ensure(reinterpret_cast<const void*>(kern), smem);
   a.tiles_m = (a.M + BM - 1) / BM;
   a.tiles_n = (a.N + BN - 1) / BN;
   int total = a.tiles_m * a.tiles_n * a.splits;

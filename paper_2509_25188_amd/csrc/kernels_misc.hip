@@ -162,7 +162,7 @@ __device__ __forceinline__ float wave_sum(float v) {
 // folded in; part z is at parts + z * part_stride, laid out like h.
 template <typename T>
 __global__ void k_rmsnorm(float* h, const float* parts, int n_parts, size_t part_stride, RowMap src, const T* gain,
-                          T* y, int rows, int d, float eps, Gate g) {
+                          T* y, int rows, int d, float eps, int wb, Gate g) {
   if (gate_skip(g)) return;
   int lane = threadIdx.x & 63;
   int r = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
@@ -175,21 +175,26 @@ __global__ void k_rmsnorm(float* h, const float* parts, int n_parts, size_t part
     float v = x[i];
     if (n_parts > 0) {
       for (int z = 0; z < n_parts; ++z) v += a0[z * part_stride + i];
-      x[i] = v;
+      if (wb) x[i] = v;
     }
     ss += v * v;
   }
   ss = wave_sum(ss);
   float inv = rsqrtf(ss / (float)d + eps);
   T* o = y + (size_t)r * d;
-  for (int i = lane; i < d; i += 64) o[i] = from_f<T>(x[i] * inv * to_f<T>(gain[i]));
+  for (int i = lane; i < d; i += 64) {
+    float v = x[i];
+    if (n_parts > 0 && !wb)
+      for (int z = 0; z < n_parts; ++z) v += a0[z * part_stride + i];
+    o[i] = from_f<T>(v * inv * to_f<T>(gain[i]));
+  }
 }
 // Same, with the row held in registers: VPL float4 per lane, all loads of a row in flight at once,
 // one pass over memory.  Used when d is a multiple of 4 and d <= 1024 * VPL.
 template <typename T, int VPL>
 __global__ void __launch_bounds__(256) k_rmsnorm_vec(float* h, const float* parts, int n_parts, size_t part_stride,
                                                     RowMap src, const T* gain, T* y, int rows, int d, float eps,
-                                                    Gate g) {
+                                                    int wb, Gate g) {
   if (gate_skip(g)) return;
   const int lane = threadIdx.x & 63;
   const int r = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
@@ -218,7 +223,7 @@ __global__ void __launch_bounds__(256) k_rmsnorm_vec(float* h, const float* part
 #pragma unroll
     for (int k = 0; k < VPL; ++k) {
       const int i = lane + 64 * k;
-      if (i < d4) x[i] = v[k];
+      if (wb && i < d4) x[i] = v[k];
     }
   }
   float ss = 0.f;
@@ -253,7 +258,7 @@ __global__ void __launch_bounds__(256) k_rmsnorm_vec(float* h, const float* part
 template <typename T, int VPL>
 __global__ void __launch_bounds__(256) k_rmsnorm_row(float* h, const float* parts, int n_parts, size_t part_stride,
                                                     RowMap src, const T* gain, T* y, int rows, int d, float eps,
-                                                    Gate g) {
+                                                    int wb, Gate g) {
   if (gate_skip(g)) return;
   __shared__ float s_part[4];
   const int tid = threadIdx.x;
@@ -295,7 +300,7 @@ __global__ void __launch_bounds__(256) k_rmsnorm_row(float* h, const float* part
 #pragma unroll
   for (int k = 0; k < VPL; ++k) {
     const int i = tid + 256 * k;
-    if (n_parts > 0 && i < d4) x[i] = v[k];
+    if (wb && n_parts > 0 && i < d4) x[i] = v[k];
     ss += v[k].x * v[k].x + v[k].y * v[k].y + v[k].z * v[k].z + v[k].w * v[k].w;
   }
   ss = wave_sum(ss);
@@ -324,29 +329,30 @@ __global__ void __launch_bounds__(256) k_rmsnorm_row(float* h, const float* part
 
 template <typename T>
 static void launch_rmsnorm_t(float* h, const float* parts, int n_parts, size_t part_stride, RowMap src, const T* gain,
-                             T* y, int rows, int d, float eps, Gate g, hipStream_t s) {
+                             T* y, int rows, int d, float eps, bool write_back, Gate g, hipStream_t s) {
+  const int wb = write_back ? 1 : 0;
   dim3 grid((rows + 3) / 4), block(256);
   if (rows <= 4096) { grid = dim3(rows); block = dim3(64); }   // few rows: one wavefront per workgroup fills more CUs
   if (d % 4 == 0 && d >= 2048 && d <= 4096)
-    hipLaunchKernelGGL((k_rmsnorm_row<T, 4>), dim3(rows), dim3(256), 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, g);
+    hipLaunchKernelGGL((k_rmsnorm_row<T, 4>), dim3(rows), dim3(256), 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, wb, g);
   else if (d % 4 == 0 && d > 4096 && d <= 8192)
-    hipLaunchKernelGGL((k_rmsnorm_row<T, 8>), dim3(rows), dim3(256), 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, g);
+    hipLaunchKernelGGL((k_rmsnorm_row<T, 8>), dim3(rows), dim3(256), 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, wb, g);
   else if (d % 4 == 0 && d <= 1024)
-    hipLaunchKernelGGL((k_rmsnorm_vec<T, 4>), grid, block, 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, g);
+    hipLaunchKernelGGL((k_rmsnorm_vec<T, 4>), grid, block, 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, wb, g);
   else if (d % 4 == 0 && d <= 4096)
-    hipLaunchKernelGGL((k_rmsnorm_vec<T, 16>), grid, block, 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, g);
+    hipLaunchKernelGGL((k_rmsnorm_vec<T, 16>), grid, block, 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, wb, g);
   else if (d % 4 == 0 && d <= 8192)
-    hipLaunchKernelGGL((k_rmsnorm_vec<T, 32>), grid, block, 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, g);
+    hipLaunchKernelGGL((k_rmsnorm_vec<T, 32>), grid, block, 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, wb, g);
   else
-    hipLaunchKernelGGL(k_rmsnorm<T>, grid, block, 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, g);
+    hipLaunchKernelGGL(k_rmsnorm<T>, grid, block, 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, wb, g);
 }
 void launch_rmsnorm(float* h, const float* parts, int n_parts, size_t part_stride, RowMap src, const void* gain,
-                    int dtype, void* y, int rows, int d, float eps, Gate g, hipStream_t s) {
+                    int dtype, void* y, int rows, int d, float eps, bool write_back, Gate g, hipStream_t s) {
   if (!parts) n_parts = 0;
   if (dtype == L2PD_FP32)
-    launch_rmsnorm_t<float>(h, parts, n_parts, part_stride, src, (const float*)gain, (float*)y, rows, d, eps, g, s);
+    launch_rmsnorm_t<float>(h, parts, n_parts, part_stride, src, (const float*)gain, (float*)y, rows, d, eps, write_back, g, s);
   else
-    launch_rmsnorm_t<bf16>(h, parts, n_parts, part_stride, src, (const bf16*)gain, (bf16*)y, rows, d, eps, g, s);
+    launch_rmsnorm_t<bf16>(h, parts, n_parts, part_stride, src, (const bf16*)gain, (bf16*)y, rows, d, eps, write_back, g, s);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -858,12 +864,8 @@ void launch_filter_train(const TrainArgs& a, hipStream_t s) {
   const int n_params = filter_param_count(a.s, a.hidden, a.n_layers);
   const size_t smem =
       (size_t)(n_params + chunk * 2 * (a.s + (a.n_layers - 1) * a.hidden) + 64) * sizeof(float);
-  static bool attr_done = false;
-  if (!attr_done) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_filter_train), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              kTrainLdsFloats * (int)sizeof(float));
-    attr_done = true;
-  }
+  static DynLdsAttr attr;
+  attr.ensure(reinterpret_cast<const void*>(k_filter_train), kTrainLdsFloats * (int)sizeof(float));
   hipLaunchKernelGGL(k_filter_train, dim3(1), dim3(kTrainThreads), smem, s, a, chunk);
 }
 

@@ -249,7 +249,7 @@ void run_layers(l2pd_ctx* c, const Pass& p, Gate g, hipStream_t s) {
       float* ks = reinterpret_cast<float*>(c->ws + L.kstore + kvo_k);
       float* vs = reinterpret_cast<float*>(c->ws + L.vstore + kvo_v);
       { Timed t(c, L2PD_K_NORM, s);
-        launch_rmsnorm(h, nullptr, 0, 0, ident, c->attn_g[l], m.dtype, xn, rows, d, m.rms_eps, g, s); }
+        launch_rmsnorm(h, nullptr, 0, 0, ident, c->attn_g[l], m.dtype, xn, rows, d, m.rms_eps, true, g, s); }
       { Timed t(c, L2PD_K_GEMM_QKV, s);
         launch_gemm_f32(xn, (const float*)c->wq[l], q, rows, d, d, 0, g, s);
         launch_gemm_f32(xn, (const float*)c->wk[l], c->at<float>(L.tmp_k), rows, d, d, 0, g, s);
@@ -262,7 +262,7 @@ void run_layers(l2pd_ctx* c, const Pass& p, Gate g, hipStream_t s) {
       { Timed t(c, L2PD_K_GEMM_O, s);
         launch_gemm_f32(c->at<float>(L.attn), (const float*)c->wo[l], h, rows, d, d, 1, g, s); }
       { Timed t(c, L2PD_K_NORM, s);
-        launch_rmsnorm(h, nullptr, 0, 0, ident, c->ffn_g[l], m.dtype, xn, rows, d, m.rms_eps, g, s); }
+        launch_rmsnorm(h, nullptr, 0, 0, ident, c->ffn_g[l], m.dtype, xn, rows, d, m.rms_eps, true, g, s); }
       float* gt = c->at<float>(L.gate_up);
       float* up = gt + (size_t)rows * F;
       { Timed t(c, L2PD_K_GEMM_GATEUP, s);
@@ -280,7 +280,7 @@ void run_layers(l2pd_ctx* c, const Pass& p, Gate g, hipStream_t s) {
       const bool skinny = rows <= kSkinnyRows;
       { Timed t(c, L2PD_K_NORM, s);
         launch_rmsnorm(h, pending ? parts : nullptr, pend_splits, pend_stride, ident, c->attn_g[l], m.dtype, xn, rows,
-                       d, m.rms_eps, g, s); }
+                       d, m.rms_eps, true, g, s); }
       pending = false;
       QkvEpilogue e = {q, ks, vts, cos_t, sin_t, p.Tq, p.pos0, L.Tpad, H, Dh, d};
       { Timed t(c, L2PD_K_GEMM_QKV, s);
@@ -311,7 +311,7 @@ void run_layers(l2pd_ctx* c, const Pass& p, Gate g, hipStream_t s) {
         else
           launch_gemm_partial_bf16(ao, (const bf16*)c->wo[l], parts, stride_d, rows, d, d, so, g, s); }
       { Timed t(c, L2PD_K_NORM, s);
-        launch_rmsnorm(h, parts, so, stride_d, ident, c->ffn_g[l], m.dtype, xn, rows, d, m.rms_eps, g, s); }
+        launch_rmsnorm(h, parts, so, stride_d, ident, c->ffn_g[l], m.dtype, xn, rows, d, m.rms_eps, true, g, s); }
       bf16* act = c->at<bf16>(L.act);
       { Timed t(c, L2PD_K_GEMM_GATEUP, s);
         if (skinny && !swiglu_few_rows_fused(rows, F)) {
@@ -350,7 +350,7 @@ void run_head(l2pd_ctx* c, int B, int n_rows_per_seq, RowMap src, float* logits_
   if (m.dtype == L2PD_FP32) {
     float* xh = c->at<float>(L.xn_head);
     { Timed t(c, L2PD_K_NORM, s);
-      launch_rmsnorm(h, nullptr, 0, 0, src, c->final_g, m.dtype, xh, hr, d, m.rms_eps, g, s); }
+      launch_rmsnorm(h, nullptr, 0, 0, src, c->final_g, m.dtype, xh, hr, d, m.rms_eps, false, g, s); }
     float* lg = logits_out ? logits_out : c->at<float>(L.logits);
     Timed t(c, L2PD_K_LMHEAD, s);
     launch_gemm_f32(xh, (const float*)c->lm_head, lg, hr, V, d, 0, g, s);
@@ -358,12 +358,14 @@ void run_head(l2pd_ctx* c, int B, int n_rows_per_seq, RowMap src, float* logits_
       launch_vocab_partials(lg, hr, V, L.lm_chunk, m.mask_id, bias, c->at<float>(L.part_max),
                             c->at<float>(L.part_sum), c->at<int32_t>(L.part_idx), L.n_part, g, s);
   } else {
-    // fold the last down projection's split-K partials into every row of h first (fixed order)
+    // the last down projection's split-K partials are summed onto the selected rows in fixed order;
+    // h itself is left as it is (nothing reads it afterwards, and with shortened sequences two head
+    // rows may map to one row of h)
     bf16* xh = c->at<bf16>(L.xn_head);
     const int sd = c->pend_splits;
     { Timed t(c, L2PD_K_NORM, s);
       launch_rmsnorm(h, sd > 0 ? c->at<float>(L.parts) : nullptr, sd, c->pend_stride, src, c->final_g, m.dtype, xh, hr,
-                     d, m.rms_eps, g, s); }
+                     d, m.rms_eps, false, g, s); }
     LmHeadEpilogue e = {};
     e.logits = logits_out;
     if (want_parts) {
