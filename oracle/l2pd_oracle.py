@@ -130,11 +130,12 @@ def attention(q, k, v, rin=None):
     before they enter the product with v.
     """
     dh = q.shape[-1]
-    s = np.einsum("qhd,khd->hqk", q, k) / q.dtype.type(np.sqrt(dh))
+    qh, kh, vh = (np.transpose(a, (1, 0, 2)) for a in (q, k, v))                  # per head: [H, T, Dh]
+    s = np.matmul(qh, np.transpose(kh, (0, 2, 1))) / q.dtype.type(np.sqrt(dh))    # scores [H, Tq, Tk]
     p = softmax(s, axis=-1)
     if rin is not None:
         p = rin(p)
-    return np.einsum("hqk,khd->qhd", p, v)
+    return np.transpose(np.matmul(p, vh), (1, 0, 2))                              # [Tq, H, Dh]
 
 
 def silu(x):
