@@ -38,7 +38,7 @@ extern "C" {
 typedef enum {
   L2PD_OK = 0,
   L2PD_EINVAL = -1,   /* bad argument (NULL pointer, inconsistent sizes, NaN threshold, ...) */
-  L2PD_ENOMEM = -2,   /* workspace too small */
+  L2PD_ENOMEM = -2,   /* workspace too small (l2pd_filter_train_static: filter beyond the static scratch) */
   L2PD_EHIP = -3,     /* a HIP runtime call failed */
   L2PD_ENOTIMPL = -4  /* shape outside what the kernels support, or a combination of modes that is not built */
 } l2pd_status;
@@ -224,6 +224,21 @@ typedef struct {
 int32_t l2pd_filter_train(const l2pd_filter* filter, const float* conf_rows_dev, const float* label_rows_dev,
                           int64_t n_rows, const l2pd_train_cfg* train_cfg, float* opt_state_dev,
                           float* loss_out_dev, void* stream);
+
+/* l2pd_filter_train for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): the same training, with the optimiser moments kept in a
+ * device array that is part of the library image instead of opt_state_dev.  The call allocates and frees
+ * nothing, on the device or through any library.
+ *   - Limit: filters of at most 20480 parameters (160 KB of moments per GPU, resident until the process
+ *     ends); a larger filter returns L2PD_ENOMEM before anything is launched.  Every other argument and
+ *     every result is as for l2pd_filter_train (same kernel, bit-identical parameters and losses).
+ *   - The first call on a device looks the array's address up once (HIP loads the library's code object then
+ *     if nothing has yet): make one call outside a capture before capturing.
+ *   - All calls on one GPU share that GPU's array.  The kernel zeroes the moments before its first epoch, so
+ *     nothing survives from call to call; calls that overlap on one GPU (different streams) race. */
+int32_t l2pd_filter_train_static(const l2pd_filter* filter, const float* conf_rows_dev,
+                                 const float* label_rows_dev, int64_t n_rows, const l2pd_train_cfg* train_cfg,
+                                 float* loss_out_dev, void* stream);
 
 /* Timing aid: kernel classes whose launches can be bracketed with HIP events on the launch stream. */
 enum {

@@ -86,7 +86,7 @@ class TrainCfg(C.Structure):
 
 
 EXPORTS = ("l2pd_workspace_bytes", "l2pd_create", "l2pd_destroy", "l2pd_forward", "l2pd_denoise_step",
-           "l2pd_generate", "l2pd_egp_rollout", "l2pd_filter_train", "l2pd_profile_select", "l2pd_profile_read", "l2pd_strerror")
+           "l2pd_generate", "l2pd_egp_rollout", "l2pd_filter_train", "l2pd_filter_train_static", "l2pd_profile_select", "l2pd_profile_read", "l2pd_strerror")
 
 
 def load_library() -> C.CDLL:
@@ -112,6 +112,8 @@ def load_library() -> C.CDLL:
     lib.l2pd_egp_rollout.argtypes = [vp, vp, vp, i32, i32, C.POINTER(DecodeCfg), vp, vp, vp, vp]
     lib.l2pd_filter_train.restype = i32
     lib.l2pd_filter_train.argtypes = [C.POINTER(Filter), vp, vp, C.c_int64, C.POINTER(TrainCfg), vp, vp, vp]
+    lib.l2pd_filter_train_static.restype = i32
+    lib.l2pd_filter_train_static.argtypes = [C.POINTER(Filter), vp, vp, C.c_int64, C.POINTER(TrainCfg), vp, vp]
     lib.l2pd_profile_select.restype = i32
     lib.l2pd_profile_select.argtypes = [vp, i32]
     lib.l2pd_profile_read.restype = i32
@@ -271,9 +273,11 @@ class Engine:
 
 
 def train_filter(flt: Dict[str, torch.Tensor], conf_rows: torch.Tensor, label_rows: torch.Tensor, epochs: int,
-                 lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01):
+                 lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01, losses: Optional[torch.Tensor] = None,
+                 static_scratch: bool = False):
     """Trains the filter IN PLACE (device fp32 tensors w1, b1, ..., wN, bN) on rows [n, s]; returns the
-    per-epoch losses as a device tensor."""
+    per-epoch losses as a device tensor (`losses`, if given, receives them: [epochs] fp32 on the device).
+    `static_scratch` takes l2pd_filter_train_static: no buffer is allocated here either when `losses` is given."""
     for t in list(flt.values()) + [conf_rows, label_rows]:
         if t.dtype != torch.float32 or not t.is_contiguous() or not t.is_cuda:
             raise ValueError("train_filter needs contiguous fp32 device tensors")
@@ -283,9 +287,14 @@ def train_filter(flt: Dict[str, torch.Tensor], conf_rows: torch.Tensor, label_ro
     if conf_rows.shape != (n, s) or label_rows.shape != (n, s):
         raise ValueError("rows must be [n, in_dim]")
     tc = TrainCfg(lr, beta1, beta2, eps, weight_decay, epochs)
+    if losses is None:
+        losses = torch.empty(epochs, dtype=torch.float32, device=conf_rows.device)
+    if static_scratch:
+        _check(lib().l2pd_filter_train_static(C.byref(f), conf_rows.data_ptr(), label_rows.data_ptr(), n, C.byref(tc),
+                                              losses.data_ptr(), _stream()), "l2pd_filter_train_static")
+        return losses
     n_params = sum(t.numel() for t in flt.values())
     state = torch.empty(2 * n_params, dtype=torch.float32, device=conf_rows.device)
-    losses = torch.empty(epochs, dtype=torch.float32, device=conf_rows.device)
     _check(lib().l2pd_filter_train(C.byref(f), conf_rows.data_ptr(), label_rows.data_ptr(), n, C.byref(tc),
                                    state.data_ptr(), losses.data_ptr(), _stream()), "l2pd_filter_train")
     return losses

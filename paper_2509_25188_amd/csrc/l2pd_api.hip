@@ -5,6 +5,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <vector>
 
 #include "common.h"
@@ -507,6 +508,30 @@ int sync_seq_len(l2pd_ctx* c, const int32_t* X, const int32_t* state, int B, int
   *all_done = c->pinned[CTL_ALL_DONE];
   return c->pinned[CTL_TMAX];
 }
+// ---- filter training for callers that cannot allocate ----
+// The optimiser moments (first and second, one float each per parameter) live in a file-scope device
+// array instead of a caller buffer.  Every GPU holds its own copy at its own address: the address is
+// resolved once per device, with that device current, and only that pointer is ever handed to kernels
+// (the array's name in host code is a host-side stand-in, not a device address).
+constexpr int kStaticTrainParams = 20480;                 // the training kernel's own limit
+static __device__ __align__(256) float scratch[2 * kStaticTrainParams];   // 160 KB per GPU, held until the process ends
+constexpr int kMaxDevices = 64;
+float* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mu;
+
+// Device address of `scratch` on the current device, or nullptr (status in *st).
+float* static_scratch(int32_t* st) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { *st = L2PD_EHIP; return nullptr; }
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) { *st = L2PD_EHIP; return nullptr; }
+    g_scratch_ptr[dev] = static_cast<float*>(p);
+  }
+  *st = L2PD_OK;
+  return g_scratch_ptr[dev];
+}
 }  // namespace
 
 // =================================================================================================
@@ -516,7 +541,7 @@ const char* l2pd_strerror(int32_t st) {
   switch (st) {
     case L2PD_OK: return "ok";
     case L2PD_EINVAL: return "invalid argument";
-    case L2PD_ENOMEM: return "workspace too small";
+    case L2PD_ENOMEM: return "workspace (or the library's static scratch) too small";
     case L2PD_EHIP: return "HIP runtime error";
     case L2PD_ENOTIMPL: return "shape not supported by the kernels";
     default: return "unknown status";
@@ -797,6 +822,23 @@ int32_t l2pd_filter_train(const l2pd_filter* f, const float* conf_rows_dev, cons
   a.opt_state = opt_state_dev; a.loss_out = loss_out_dev;
   launch_filter_train(a, static_cast<hipStream_t>(stream));
   return hipGetLastError() == hipSuccess ? L2PD_OK : L2PD_EHIP;
+}
+
+int32_t l2pd_filter_train_static(const l2pd_filter* f, const float* conf_rows_dev, const float* label_rows_dev,
+                                 int64_t n_rows, const l2pd_train_cfg* tc, float* loss_out_dev, void* stream) {
+  if (!f || !filter_ok(f)) return L2PD_EINVAL;
+  // beyond the static array: refused here, whatever the training kernel itself could take
+  long long n_params = 0;
+  for (int k = 0; k < f->n_layers; ++k) {
+    const long long in = k == 0 ? f->in_dim : f->hidden, out = k == f->n_layers - 1 ? f->in_dim : f->hidden;
+    n_params += out * in + out;
+  }
+  if (n_params > kStaticTrainParams) return L2PD_ENOMEM;
+  int32_t st = L2PD_OK;
+  float* moments = static_scratch(&st);
+  if (!moments) return st;
+  // the kernel zeroes the moments before its first epoch, so what an earlier call left is never read
+  return l2pd_filter_train(f, conf_rows_dev, label_rows_dev, n_rows, tc, moments, loss_out_dev, stream);
 }
 
 int32_t l2pd_profile_select(l2pd_ctx* c, int32_t cls) {
