@@ -494,21 +494,22 @@ def egp_rollout(model, prompt, reference, gen_len, block_len, mask_id, bias=None
 
 
 # --------------------------------------------------------------------------- Eq. 6 and the optimiser
-def bce_loss_and_grad(flt, C, Y):
+def bce_loss_and_grad(flt, C, Y, dtype=np.float64):
     """Mean binary cross-entropy (Eq. 6) of sigmoid(f_theta(c)) against y over all entries of the
-    rows C[n, s], Y[n, s], and its gradient with respect to every w_k, b_k of the filter."""
-    C = np.asarray(C, dtype=np.float64)
-    Y = np.asarray(Y, dtype=np.float64)
+    rows C[n, s], Y[n, s], and its gradient with respect to every w_k, b_k of the filter.
+    `dtype` is the precision everything is evaluated in (float64 by default)."""
+    C = np.asarray(C, dtype=dtype)
+    Y = np.asarray(Y, dtype=dtype)
     n = filter_depth(flt)
-    W = [None] + [np.asarray(flt[f"w{k}"], dtype=np.float64) for k in range(1, n + 1)]
-    Bv = [None] + [np.asarray(flt[f"b{k}"], dtype=np.float64) for k in range(1, n + 1)]
+    W = [None] + [np.asarray(flt[f"w{k}"], dtype=dtype) for k in range(1, n + 1)]
+    Bv = [None] + [np.asarray(flt[f"b{k}"], dtype=dtype) for k in range(1, n + 1)]
     acts = [C]                               # acts[k] = input of layer k+1, rows [n, width]
     pre = [None]                             # pre[k] = pre-activation of layer k
     for k in range(1, n):
         pre.append(acts[-1] @ W[k].T + Bv[k])
         acts.append(np.maximum(pre[-1], 0.0))
     Z = acts[-1] @ W[n].T + Bv[n]            # [n, s]
-    m = Z.size
+    m = C.dtype.type(Z.size)
     # -[y log sigma(z) + (1 - y) log(1 - sigma(z))] = softplus(z) - y z
     loss = float(np.sum(np.maximum(Z, 0.0) + np.log1p(np.exp(-np.abs(Z))) - Y * Z) / m)
     d = (sigmoid(Z) - Y) / m                 # dL/d(pre-activation) of the layer at hand
@@ -531,15 +532,19 @@ def adamw_step(param, grad, m, v, t, lr, beta1=0.9, beta2=0.999, eps=1e-8, weigh
     return param, m, v
 
 
-def train_filter(flt, C, Y, epochs, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01):
-    """`epochs` full-batch AdamW steps on Eq. 6.  Returns (filter, losses[epochs]) in float64."""
+def train_filter(flt, C, Y, epochs, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01,
+                 dtype=np.float64):
+    """`epochs` full-batch AdamW steps on Eq. 6.  Returns (filter, losses[epochs]) in `dtype`
+    (float64 by default; float32 shows how far single precision alone moves the result)."""
     n = filter_depth(flt)
-    th = {f"{c}{k}": np.array(flt[f"{c}{k}"], dtype=np.float64) for k in range(1, n + 1) for c in "wb"}
+    ft = np.dtype(dtype).type
+    lr, beta1, beta2, eps, weight_decay = (ft(x) for x in (lr, beta1, beta2, eps, weight_decay))
+    th = {f"{c}{k}": np.array(flt[f"{c}{k}"], dtype=dtype) for k in range(1, n + 1) for c in "wb"}
     m = {k: np.zeros_like(x) for k, x in th.items()}
     v = {k: np.zeros_like(x) for k, x in th.items()}
     losses = []
     for t in range(1, epochs + 1):
-        loss, g = bce_loss_and_grad(th, C, Y)
+        loss, g = bce_loss_and_grad(th, C, Y, dtype)
         losses.append(loss)
         for k in th:
             th[k], m[k], v[k] = adamw_step(th[k], g[k], m[k], v[k], t, lr, beta1, beta2, eps, weight_decay)

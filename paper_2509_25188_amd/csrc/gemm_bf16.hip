@@ -573,17 +573,18 @@ void launch_gemm_partial_bf16(const bf16* A, const bf16* W, float* parts, size_t
 }
 
 // Wide path, [d, d] and [d, F] projections: 128 x 128 tiles of these narrow outputs do not fill the
-// chip until there are thousands of rows, so K is split until a launch has about 256 workgroups,
-// each K range staying a multiple of the 64-wide stage and at least 512 long: two ways as a rule,
-// and up to eight ways up to 256 rows (batched block-only steps of the cached modes, which are bound
-// by the weight stream: 256 rows of the 8B shape split 4 ways, 128 rows 8 ways).  The partials are
-// folded by the next RMSNorm in order.  Above 256 rows the depth is 1 or 2 whatever the row count, so
-// that full-recompute batches of different sizes sum in the same order as often as possible.
+// chip at a few hundred rows, so K is split, each K range staying a multiple of the 64-wide stage and
+// at least 512 long; the partials are folded by the next RMSNorm in order.  Above 256 rows the depth is
+// a function of K alone (two ways whenever K allows it), never of the row count: a sequence must sum
+// its projections in the same order whatever batch it is decoded in (full-recompute forwards of one
+// sequence and of a batch then give the same bits row by row).  Up to 256 rows (batched block-only steps
+// of the cached modes, bound by the weight stream) the split goes up to eight ways, until the launch
+// has about 256 workgroups: 256 rows of the 8B shape split 4 ways, 128 rows 8 ways.
 int wide_splits(int M, int N, int K) {
+  if (M > 256) return (K % 128 == 0 && K / 2 >= 512) ? 2 : 1;
   const int tiles = ((M + 127) / 128) * ((N + 127) / 128);
-  const int s_max = M <= 256 ? 8 : 2;
   int S = 1;
-  while (tiles * S < 256 && S < s_max && K % (S * 2 * 64) == 0 && K / (S * 2) >= 512) S *= 2;
+  while (tiles * S < 256 && S < 8 && K % (S * 2 * 64) == 0 && K / (S * 2) >= 512) S *= 2;
   return S;
 }
 

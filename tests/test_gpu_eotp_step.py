@@ -64,13 +64,15 @@ def test_step_eotp_bf16_ragged_lengths_in_a_batch():
     eng, ora, flt, prompt = build(w, lm_head_scale=25.0)
     fdev = {k: v.cuda() for k, v in flt.items()}
     traces, outs = oracle_runs(w, ora, flt, prompt)
+    Pz.annotate_fmt(traces, ora.alt, w)
     rep = Pz.StepReport()
-    same = Pz.teacher_forced(eng, traces, w.prompt_len, Pz.cfg_for(w), fdev, w.model, w.threshold, rep)
+    forced = Pz.teacher_forced(eng, traces, w.prompt_len, Pz.cfg_for(w), fdev, w.model, w.threshold, rep)
     print("step-granular EoTP bf16 teacher-forced:", rep, "decoded lengths", [o[2] for o in outs])
     assert rep.max_logit_err < 2e-2
+    # near-ties of this model that a bf16 path cannot resolve (rules in tests/parity.py); measured 2 to 6 %
+    assert rep.exempt_tokens + rep.exempt_decisions <= 0.08 * rep.positions
     tok, st, dl = eng.generate(prompt.cuda(), fdev, Pz.cfg_for(w))
     assert np.all(dl.cpu().numpy() <= 64)
-    if same:
-        for b in range(3):
-            np.testing.assert_array_equal(tok.cpu().numpy()[b], outs[b][0])
-            assert int(st[b]) == outs[b][1] and int(dl[b]) == outs[b][2]
+    for b in range(3):
+        Pz.check_generate(tok.cpu().numpy()[b], st[b], dl[b], traces[b], *outs[b], forced.first_exempt[b],
+                          w.prompt_len, w.block_len, f"step EoTP bf16 seq {b}")

@@ -24,13 +24,13 @@ def test_decode_with_filters_of_each_depth_fp32(n_layers, hidden):
     fdev = {k: v.cuda() for k, v in flt.items()}
     cfg = Pz.cfg_for(w)
     rep = Pz.StepReport()
-    same = Pz.teacher_forced(eng, [trace], w.prompt_len, cfg, fdev, w.model, w.threshold, rep)
+    forced = Pz.teacher_forced(eng, [trace], w.prompt_len, cfg, fdev, w.model, w.threshold, rep)
     print(f"{n_layers}-layer filter (hidden {hidden}): {rep}; oracle steps {steps}")
     assert rep.max_p_err < 1e-4
+    assert rep.exempt_tokens == 0 and rep.exempt_decisions <= 1
     tok, st, dl = eng.generate(prompt.cuda(), fdev, cfg)
-    if same:
-        np.testing.assert_array_equal(tok.cpu().numpy()[0], resp)
-        assert int(st[0]) == steps and int(dl[0]) == dlen
+    Pz.check_generate(tok.cpu().numpy()[0], st[0], dl[0], trace, resp, steps, dlen, forced.first_exempt[0],
+                      w.prompt_len, w.block_len, f"{n_layers}-layer filter")
 
 
 def test_single_layer_filter_equals_two_layer_with_identity_first_layer():
@@ -70,14 +70,17 @@ def test_training_filters_of_each_depth_matches_oracle(n_layers, s, h, n):
     ref, ref_losses = O.train_filter(Pz.np_filter(flt), Cn, Yn, 200, lr=3e-3)
     print(f"{n_layers} layers, s {s}, hidden {h}, rows {n}: loss {losses[0]:.5f} -> {losses[-1]:.5f} "
           f"(oracle {ref_losses[0]:.5f} -> {ref_losses[-1]:.5f})")
-    n_params = sum(v.numel() for v in flt.values())
-    if n * s >= n_params:
-        np.testing.assert_allclose(losses, ref_losses, rtol=1e-2, atol=1e-5)
-    else:
-        # more parameters than targets: the descent is ill-conditioned and the two precisions part ways
-        # after some tens of steps; the first stretch still agrees, and both fit the rows
-        np.testing.assert_allclose(losses[:40], ref_losses[:40], rtol=1e-2, atol=1e-5)
-        assert abs(losses[-1] - ref_losses[-1]) < 0.15 * ref_losses[-1]
+    # The kernel trains in float32, the reference above in float64.  How far float32 arithmetic alone moves
+    # the loss curve is measured on the oracle itself (same trainer in float32): the kernel may be that far
+    # from the float64 curve (times two: two float32 evaluations differ from each other by up to twice what
+    # each differs from the exact one), and never less than 1e-3 relative.  With more parameters than targets
+    # (4 layers, 64 wide, 70 rows) the descent is ill-conditioned and the two oracle precisions themselves
+    # part ways after some tens of steps; with enough rows they agree to 1e-4 and so must the kernel.
+    _, ref32_losses = O.train_filter(Pz.np_filter(flt), Cn, Yn, 200, lr=3e-3, dtype=np.float32)
+    spread = np.abs(ref32_losses - ref_losses)
+    print(f"  float32 oracle vs float64 oracle: max loss distance {spread.max():.3e}; kernel vs float64 oracle "
+          f"{np.abs(losses - ref_losses).max():.3e}")
+    assert np.all(np.abs(losses - ref_losses) <= 2 * np.maximum.accumulate(spread) + 1e-3 * ref_losses + 1e-5)
     assert losses[-1] < losses[0]
 
 

@@ -1,0 +1,91 @@
+"""GPU parity against the stored oracle trajectories of the named workloads (tests/golden/traj_*.npz,
+written by tests/golden/make_trajectories.py from the CPU oracle alone).
+
+Every stored step is imposed on l2pd_denoise_step (teacher forcing) and compared under the fixed rules of
+tests/parity.py; then l2pd_generate decodes the same prompt freely and its tokens, step count and decoded
+length are compared with the oracle's (identical when no position of the trajectory is exempt, else
+identical up to the first exempt step, and reported)."""
+import dataclasses
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2509_25188_amd import binding as Bd
+from paper_2509_25188_amd import synth
+from tests import parity as Pz
+
+pytestmark = pytest.mark.gpu
+SEED = 1234
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def path_of(case, seq):
+    return os.path.join(GOLDEN, f"traj_{case}_seq{seq}.npz")
+
+
+def engine(w, max_batch):
+    eng = Bd.engine_for(w, SEED, "cuda", max_batch=max_batch)
+    flt = synth.make_filter(SEED, w.block_len, w.filter_hidden, "cuda")
+    return eng, flt
+
+
+def forced_and_free(case, w, seqs, eng, flt, exempt_frac, batch_rows=None):
+    """Teacher-forces every stored step of the sequences `seqs`, then compares a free-running decode.
+    batch_rows: decode the workload's whole batch in one call and compare these rows (else one call per
+    sequence at B = 1).  Returns the report."""
+    cfg = Pz.cfg_for(w)
+    prompts = synth.make_prompt(SEED, max(w.batch, max(seqs) + 1), w.prompt_len, w.prompt_hi, "cuda")
+    rep = Pz.StepReport()
+    loaded = {}
+    for b in seqs:
+        meta, recs, result = Pz.load_trajectory(path_of(case, b))
+        assert meta["workload"] == (w.name.split("_L")[0]) and meta["layers"] == w.model.n_layers and meta["seq"] == b
+        np.testing.assert_array_equal(np.load(path_of(case, b))["prompt"], prompts[b].cpu().numpy())
+        # logits: the stated tolerance, or 1.5 x the stored noise floor where that is larger (deep random-init
+        # models: the same oracle accumulated in float64 instead of float32 already moves the logits that far)
+        lim = max(Pz.tol_for(w.model), 1.5 * meta["floor_rel_max"])
+        for r in recs:
+            r["logit_tol"] = lim
+        forced = Pz.teacher_forced(eng, [recs], w.prompt_len, cfg, flt, w.model, w.threshold, rep,
+                                   want_logits=lambda r: "lg_fixed" in r)
+        loaded[b] = (recs, result, forced.first_exempt[0])
+        print(f"{case} seq {b}: {len(recs)} stored steps, D = {meta['fmt_abs_max']:.3e} logit units, noise floor "
+              f"{meta['floor_rel_max']:.3e}, logit tolerance {lim:.3e}, first exempt step {forced.first_exempt[0]}")
+    print(f"{case} teacher-forced:", rep)
+    assert rep.exempt_tokens + rep.exempt_decisions <= exempt_frac * rep.positions, rep
+    if batch_rows is not None:
+        tok, st, dl = eng.generate(prompts[:w.batch].contiguous(), flt, cfg)
+        tok, st, dl = tok.cpu().numpy(), st.cpu().numpy(), dl.cpu().numpy()
+        rows = {b: (tok[b], st[b], dl[b]) for b in batch_rows}
+    else:
+        rows = {}
+        for b in seqs:
+            tok, st, dl = eng.generate(prompts[b:b + 1].contiguous(), flt, cfg)
+            rows[b] = (tok.cpu().numpy()[0], int(st[0]), int(dl[0]))
+    for b in seqs:
+        recs, result, first_exempt = loaded[b]
+        if result is None:
+            continue
+        Pz.check_generate(rows[b][0], rows[b][1], rows[b][2], recs, *result, first_exempt, w.prompt_len,
+                          w.block_len, f"{case} seq {b}")
+    return rep, rows, loaded
+
+
+def test_mid_workload_full_depth_trajectories():
+    # the mid-size workload at its own depth (8 layers): sequences 0 and 5 of the batch of 8, every step of the
+    # oracle's trajectories teacher-forced, then the whole batch decoded in one call
+    w = synth.WORKLOADS["mid"]
+    eng, flt = engine(w, w.batch)
+    rep, rows, _ = forced_and_free("mid", w, (0, 5), eng, flt, exempt_frac=0.05, batch_rows=(0, 5))   # measured 3.3 % of the positions
+    assert rep.max_logit_err < 2e-2
+
+
+def test_8b_g256_two_layers_whole_trajectory():
+    # the benchmarked workload's widths, vocabulary and decode arguments at two layers: every step of the
+    # oracle's trajectory teacher-forced (512 rows, full recompute), then a free-running decode
+    w = synth.with_layers(synth.WORKLOADS["8b_g256"], 2)
+    eng, flt = engine(w, 1)
+    rep, rows, _ = forced_and_free("8b_g256_L2", w, (0,), eng, flt, exempt_frac=0.05)
+    assert rep.max_logit_err < 2e-2

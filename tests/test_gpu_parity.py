@@ -23,7 +23,11 @@ def build(w: synth.Workload, seed=SEED, lm_head_scale=1.0, max_batch=None):
     weights = synth.make_weights(w.model, seed, "cpu", lm_head_scale=lm_head_scale)
     eng = Bd.Engine(w.model, Pz.to_dev(weights), max_batch or w.batch, w.prompt_len + w.gen_len,
                     w.prefix_cache or w.dual_cache)
-    ora = Pz.oracle_model(w.model, weights)
+    # bf16 models: the primary oracle rounds every matrix-product input to bf16 (the arithmetic under
+    # test); `alt` is the same model with float32 activations, whose distance defines the resolution D
+    bf = w.model.dtype == "bf16"
+    ora = Pz.oracle_model(w.model, weights, gemm_input="bf16" if bf else "fp32")
+    ora.alt = Pz.oracle_model(w.model, weights) if bf else None
     flt = synth.make_filter(seed, w.block_len, w.filter_hidden, "cpu")
     prompt = synth.make_prompt(seed, w.batch, w.prompt_len, w.prompt_hi, "cpu")
     return eng, ora, flt, prompt
@@ -85,14 +89,16 @@ def test_tiny_trajectory_and_teacher_forced_steps():
     fdev = {k: v.cuda() for k, v in flt.items()}
     cfg = Pz.cfg_for(w)
     rep = Pz.StepReport()
-    same = Pz.teacher_forced(eng, [trace], w.prompt_len, cfg, fdev, w.model, w.threshold, rep)
+    forced = Pz.teacher_forced(eng, [trace], w.prompt_len, cfg, fdev, w.model, w.threshold, rep)
     print("tiny teacher-forced:", rep)
     assert rep.max_logit_err < 1e-4
+    # a random-init model puts every confidence near 1/vocab: the candidates for the forced position are
+    # close together, and a few fall inside the resolution of a 1e-4 tolerance
+    assert rep.exempt_tokens == 0 and rep.exempt_decisions <= 4
     tok, st, dl = eng.generate(prompt.cuda(), fdev, cfg)
     torch.cuda.synchronize()
-    if same:
-        np.testing.assert_array_equal(tok.cpu().numpy()[0], resp)
-        assert int(st[0]) == steps and int(dl[0]) == dlen
+    Pz.check_generate(tok.cpu().numpy()[0], st[0], dl[0], trace, resp, steps, dlen, forced.first_exempt[0],
+                      w.prompt_len, w.block_len, "tiny")
     assert not np.any(tok.cpu().numpy() == w.model.mask_id)
 
 
@@ -224,17 +230,19 @@ def test_bf16_kv_cache_and_eotp(B, s, dual):
         outs.append(Pz.oracle_generate(ora, prompt[b].numpy(), w, Pz.np_filter(flt), tr))
         traces.append(tr)
         assert outs[b][2] == (128 if s == 64 else 96)     # EOS forced from position 70: stop after the block holding it
+    Pz.annotate_fmt(traces, ora.alt, w)
     rep = Pz.StepReport()
-    same = Pz.teacher_forced(eng, traces, w.prompt_len, cfg, fdev, w.model, w.threshold, rep)
+    forced = Pz.teacher_forced(eng, traces, w.prompt_len, cfg, fdev, w.model, w.threshold, rep)
     print(f"bf16 {'dual' if dual else 'prefix'}-cache B={B} s={s} teacher-forced:", rep)
     assert rep.max_logit_err < 2e-2
+    # near-ties of this model that a bf16 path cannot resolve (rules in tests/parity.py); measured 2 to 6 %
+    assert rep.exempt_tokens + rep.exempt_decisions <= 0.08 * rep.positions
     tok, st, dl = eng.generate(prompt.cuda(), fdev, Pz.cfg_for(w))
     assert dl.tolist() == [outs[0][2]] * B
     assert np.all(tok.cpu().numpy()[:, outs[0][2]:] == w.model.mask_id)
-    if same:
-        for b in range(B):
-            np.testing.assert_array_equal(tok.cpu().numpy()[b], outs[b][0])
-            assert int(st[b]) == outs[b][1]
+    for b in range(B):
+        Pz.check_generate(tok.cpu().numpy()[b], st[b], dl[b], traces[b], *outs[b], forced.first_exempt[b],
+                          w.prompt_len, w.block_len, f"bf16 kv cache seq {b}")
 
 
 def test_bf16_small_teacher_forced_and_generate():
@@ -247,16 +255,18 @@ def test_bf16_small_teacher_forced_and_generate():
         tr = []
         outs.append(Pz.oracle_generate(ora, prompt[b].numpy(), w, Pz.np_filter(flt), tr))
         traces.append(tr)
+    Pz.annotate_fmt(traces, ora.alt, w)
     rep = Pz.StepReport()
-    same = Pz.teacher_forced(eng, traces, w.prompt_len, cfg, fdev, w.model, w.threshold, rep)
+    forced = Pz.teacher_forced(eng, traces, w.prompt_len, cfg, fdev, w.model, w.threshold, rep)
     print("bf16 small teacher-forced:", rep)
     assert rep.max_logit_err < 2e-2
+    # near-ties of this model that a bf16 path cannot resolve (rules in tests/parity.py); measured 2 to 6 %
+    assert rep.exempt_tokens + rep.exempt_decisions <= 0.08 * rep.positions
     tok, st, dl = eng.generate(prompt.cuda(), fdev, cfg)
     assert not np.any(tok.cpu().numpy() == w.model.mask_id)
-    if same:
-        for b in range(2):
-            np.testing.assert_array_equal(tok.cpu().numpy()[b], outs[b][0])
-            assert int(st[b]) == outs[b][1]
+    for b in range(2):
+        Pz.check_generate(tok.cpu().numpy()[b], st[b], dl[b], traces[b], *outs[b], forced.first_exempt[b],
+                          w.prompt_len, w.block_len, f"bf16 small seq {b}")
 
 
 def test_bf16_prefix_cache_and_eotp():
@@ -271,17 +281,19 @@ def test_bf16_prefix_cache_and_eotp():
         outs.append(Pz.oracle_generate(ora, prompt[b].numpy(), w, Pz.np_filter(flt), tr))
         traces.append(tr)
         assert outs[b][2] == 128          # EOS bias from position 70: stop after block 1 of 3
+    Pz.annotate_fmt(traces, ora.alt, w)
     rep = Pz.StepReport()
-    same = Pz.teacher_forced(eng, traces, w.prompt_len, cfg, fdev, w.model, w.threshold, rep)
+    forced = Pz.teacher_forced(eng, traces, w.prompt_len, cfg, fdev, w.model, w.threshold, rep)
     print("bf16 prefix-cache teacher-forced:", rep)
     assert rep.max_logit_err < 2e-2
+    # near-ties of this model that a bf16 path cannot resolve (rules in tests/parity.py); measured 2 to 6 %
+    assert rep.exempt_tokens + rep.exempt_decisions <= 0.08 * rep.positions
     tok, st, dl = eng.generate(prompt.cuda(), fdev, cfg)
     assert dl.tolist() == [128, 128, 128]
     assert np.all(tok.cpu().numpy()[:, 128:] == w.model.mask_id)
-    if same:
-        for b in range(3):
-            np.testing.assert_array_equal(tok.cpu().numpy()[b], outs[b][0])
-            assert int(st[b]) == outs[b][1]
+    for b in range(3):
+        Pz.check_generate(tok.cpu().numpy()[b], st[b], dl[b], traces[b], *outs[b], forced.first_exempt[b],
+                          w.prompt_len, w.block_len, f"bf16 prefix cache seq {b}")
 
 
 def test_generate_is_deterministic_bf16():

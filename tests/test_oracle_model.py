@@ -52,15 +52,29 @@ def bf_rope_head(v, t, base):
     return out
 
 
-def bf_forward(s, w, tokens, key_limit=None, pos0=0):
-    """Pure-Python forward.  key_limit (optional) restricts every query to keys < key_limit."""
+def scalar_bf16(x):
+    """Nearest bf16 value of one number (ties to even), through the bits of its float32 form."""
+    import struct
+    u = struct.unpack("<I", struct.pack("<f", x))[0]
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return struct.unpack("<f", struct.pack("<I", u))[0]
+
+
+ROUND_POINTS = ("attn_norm", "q", "k", "v", "prob", "attn_out", "ffn_norm", "swiglu", "final_norm")
+
+
+def bf_forward(s, w, tokens, key_limit=None, pos0=0, round_at=()):
+    """Pure-Python forward.  key_limit (optional) restricts every query to keys < key_limit.
+    `round_at` names the matrix-product inputs that are rounded to bf16 (any of ROUND_POINTS)."""
+    def rnd(name, vec):
+        return [scalar_bf16(x) for x in vec] if name in round_at else vec
     T = len(tokens)
     W = {k: np.asarray(v).tolist() for k, v in w.items()}
     h = [list(W["tok_emb"][t]) for t in tokens]
     H, Dh = s.n_heads, s.head_dim
     for l in range(s.n_layers):
         p = f"layers.{l}."
-        a = [bf_norm(h[t], W[p + "attn_norm_g"], s.rms_eps) for t in range(T)]
+        a = [rnd("attn_norm", bf_norm(h[t], W[p + "attn_norm_g"], s.rms_eps)) for t in range(T)]
         q = [bf_matvec(W[p + "wq"], a[t]) for t in range(T)]
         k = [bf_matvec(W[p + "wk"], a[t]) for t in range(T)]
         v = [bf_matvec(W[p + "wv"], a[t]) for t in range(T)]
@@ -68,6 +82,9 @@ def bf_forward(s, w, tokens, key_limit=None, pos0=0):
             for hh in range(H):
                 q[t][hh * Dh:(hh + 1) * Dh] = bf_rope_head(q[t][hh * Dh:(hh + 1) * Dh], pos0 + t, s.rope_base)
                 k[t][hh * Dh:(hh + 1) * Dh] = bf_rope_head(k[t][hh * Dh:(hh + 1) * Dh], pos0 + t, s.rope_base)
+        q = [rnd("q", r) for r in q]
+        k = [rnd("k", r) for r in k]
+        v = [rnd("v", r) for r in v]
         o = [[0.0] * (H * Dh) for _ in range(T)]
         nk = T if key_limit is None else key_limit
         for t in range(T):
@@ -77,19 +94,20 @@ def bf_forward(s, w, tokens, key_limit=None, pos0=0):
                 m = max(sc)
                 ex = [math.exp(x - m) for x in sc]
                 z = sum(ex)
+                pr = rnd("prob", [x / z for x in ex])
                 for e in range(Dh):
-                    o[t][hh * Dh + e] = sum(ex[u] / z * v[u][hh * Dh + e] for u in range(nk))
+                    o[t][hh * Dh + e] = sum(pr[u] * v[u][hh * Dh + e] for u in range(nk))
         for t in range(T):
-            proj = bf_matvec(W[p + "wo"], o[t])
+            proj = bf_matvec(W[p + "wo"], rnd("attn_out", o[t]))
             h[t] = [x + y for x, y in zip(h[t], proj)]
         for t in range(T):
-            f = bf_norm(h[t], W[p + "ffn_norm_g"], s.rms_eps)
+            f = rnd("ffn_norm", bf_norm(h[t], W[p + "ffn_norm_g"], s.rms_eps))
             g = bf_matvec(W[p + "w_gate"], f)
             u = bf_matvec(W[p + "w_up"], f)
-            act = [gi / (1.0 + math.exp(-gi)) * ui for gi, ui in zip(g, u)]
+            act = rnd("swiglu", [gi / (1.0 + math.exp(-gi)) * ui for gi, ui in zip(g, u)])
             dn = bf_matvec(W[p + "w_down"], act)
             h[t] = [x + y for x, y in zip(h[t], dn)]
-    return [bf_matvec(W["lm_head"], bf_norm(h[t], W["final_norm_g"], s.rms_eps)) for t in range(T)]
+    return [bf_matvec(W["lm_head"], rnd("final_norm", bf_norm(h[t], W["final_norm_g"], s.rms_eps))) for t in range(T)]
 
 
 # ----------------------------------------------------------------- tests
@@ -393,3 +411,36 @@ def test_bf16_gemm_inputs_stay_close_to_full_precision():
     b = O.Model(s, w, np.float32, gemm_input="bf16").forward(tokens)
     e = np.max(np.abs(a - b)) / np.max(np.abs(a))
     assert 1e-5 < e < 3e-2          # rounding is present, and of the size of bf16's 2^-9 steps
+
+
+def test_bf16_gemm_inputs_are_rounded_exactly_where_stated():
+    """The bf16-input mode against scalar loops that round, one number at a time, at the named points:
+    the normalised activations of both half-layers and of the head, the rotated queries and keys, the
+    values, the softmax probabilities, the attention output and the SwiGLU output.  Leaving any one of
+    them unrounded (or rounding none) must move the result away from the oracle's."""
+    s = tiny_shape()
+    w = {k: np.asarray([[scalar_bf16(x) for x in row] for row in np.atleast_2d(v)]).reshape(np.shape(v))
+         for k, v in tiny_weights(s, 8).items()}                        # bf16-representable weights
+    tokens = [1, 4, 10, 10, 8, 2]
+    got = O.Model(s, w, np.float64, gemm_input="bf16").forward(np.array(tokens))
+    ref = np.array(bf_forward(s, w, tokens, round_at=ROUND_POINTS))
+    np.testing.assert_allclose(got, ref, rtol=1e-9, atol=1e-12)
+    scale = np.max(np.abs(ref))
+    for left_out in ROUND_POINTS:
+        other = np.array(bf_forward(s, w, tokens, round_at=tuple(p for p in ROUND_POINTS if p != left_out)))
+        assert np.max(np.abs(other - got)) > 1e-5 * scale, left_out
+    assert np.max(np.abs(np.array(bf_forward(s, w, tokens)) - got)) > 1e-4 * scale
+
+
+def test_filter_training_in_float32_tracks_float64():
+    """The trainer's precision switch: the float32 run starts on the float64 loss curve and stays near it
+    on a well-conditioned problem."""
+    r = np.random.default_rng(5)
+    C = r.uniform(size=(120, 8))
+    Y = (r.uniform(size=(120, 8)) < 0.2 + 0.6 * C).astype(np.float64)
+    flt = {"w1": r.normal(0, 0.4, (6, 8)), "b1": r.normal(0, 1, 6), "w2": r.normal(0, 0.4, (8, 6)), "b2": r.normal(0, 1, 8)}
+    th64, l64 = O.train_filter(flt, C, Y, 50, lr=1e-2)
+    th32, l32 = O.train_filter(flt, C, Y, 50, lr=1e-2, dtype=np.float32)
+    assert all(v.dtype == np.float32 for v in th32.values()) and all(v.dtype == np.float64 for v in th64.values())
+    np.testing.assert_allclose(l32, l64, rtol=1e-4)
+    assert abs(l32[0] - l64[0]) < 1e-6 and l64[-1] < l64[0]
