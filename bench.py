@@ -9,7 +9,8 @@ whenever a generation completes), with weights, prompt and state already residen
 
 Prints ONE JSON line.  `value` = generated tokens per second (tokens committed per step on this
 trajectory x steps per second); `roofline` is for the dominant kernel (the gate/up SwiGLU GEMM),
-timed live with HIP events on the launch stream; `cpu_baseline` is the CPU oracle timed on this
+timed live with HIP event pairs on the launch stream (no correction: a pair also sees the gap between
+the events and the kernel, so the figure is a slight under-estimate of the kernel's rate); `cpu_baseline` is the CPU oracle timed on this
 host on a bounded sample of the same workload.
 """
 from __future__ import annotations
@@ -83,9 +84,15 @@ def cpu_baseline(w, tokens_per_step, seed, n_layers_sample=2):
     per_step = t_embed + t_layers / n_layers_sample * m.n_layers + t_head
     per_step *= w.batch           # the oracle decodes one sequence at a time
     steps_per_s = 1.0 / per_step
+    # threads the oracle's matrix products actually ran on: NumPy's BLAS pool
+    try:
+        from threadpoolctl import threadpool_info
+        blas_threads = max([p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"] or [1])
+    except Exception:
+        blas_threads = None
     return {
-        "value": steps_per_s * tokens_per_step, "unit": "tokens/s", "cores": torch.get_num_threads(),
-        "kind": "oracle", "steps_per_s": steps_per_s,
+        "value": steps_per_s * tokens_per_step, "unit": "tokens/s", "cores": blas_threads or os.cpu_count(),
+        "host_cpus": os.cpu_count(), "kind": "oracle", "steps_per_s": steps_per_s,
         "sample": (f"one denoising step of one sequence: embedding + {n_layers_sample} of {m.n_layers} layers "
                    f"+ LM head + decode rule at full width, T={T}, fp32 NumPy; layer time scaled to "
                    f"{m.n_layers} layers and to batch {w.batch} (measured {t_layers + t_embed + t_head:.1f} s of "
@@ -175,6 +182,7 @@ def cached_workload(args, w, eng, flt, prompt, cfg, f, X0, state0, traj_steps, t
                        "store_rebuild_ms_per_block": refresh_ms},
         "roofline": roof,
         "setup_s": setup_s,
+        **({"eotp_steps_saved": eotp_on_off(w, eng, prompt, flt, cfg, traj_steps, tokens_total)} if w.eotp else {}),
     }
 
 
@@ -236,6 +244,30 @@ def batch_schedules(w, eng, prompt, flt, cfg):
                      "steps_per_sequence": st.cpu().tolist(), "tokens_equal_lock_step": bool(torch.equal(tok, ref))}
     cfg.ragged = Bd.RAGGED_OFF
     return out
+
+
+def eotp_on_off(w, eng, prompt, flt, cfg, steps_on, tokens_on):
+    """The same decode with End-of-Text Prediction switched off (every block of the window is decoded):
+    steps and wall time against the EoTP run (Sec. 3.3; App. B counts the cost of the padding the same way)."""
+    import torch
+    from paper_2509_25188_amd import binding as Bd
+    off = Bd.DecodeCfg.from_buffer_copy(cfg)
+    off.eotp = Bd.EOTP_OFF
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    tok, st, dl = eng.generate(prompt, flt, off)
+    torch.cuda.synchronize()
+    t_off = time.perf_counter() - t0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    eng.generate(prompt, flt, cfg)
+    torch.cuda.synchronize()
+    t_on = time.perf_counter() - t0
+    steps_off = int(st.max())
+    return {"steps_eotp_on": int(steps_on), "steps_eotp_off": steps_off,
+            "steps_saved_fraction": 1.0 - steps_on / steps_off, "generate_wall_s_eotp_on": t_on,
+            "generate_wall_s_eotp_off": t_off, "wall_time_ratio_off_over_on": t_off / t_on,
+            "tokens_decoded_eotp_on": int(tokens_on), "tokens_decoded_eotp_off": int(dl.sum().item())}
 
 
 TRAFFIC_WORKLOAD = "8b_g256"      # the workload the committed counter runs were taken on
@@ -409,6 +441,8 @@ def main():
                      "launches": n_launch, "avg_launch_ms": avg_kern_ms, "flop_per_launch": gu_flops},
         "setup_s": setup_s,
     }
+    if w.eotp and not w.eotp_step:
+        result["eotp_steps_saved"] = eotp_on_off(w, eng, prompt, flt, cfg, traj_steps, tokens_total)
     if args.pipeline:
         result["pipeline"] = pipeline(w, eng, prompt, cfg, args.seed, dev, args.filter_layers)
     if args.batch_schedules:

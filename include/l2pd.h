@@ -121,8 +121,11 @@ enum { L2PD_EOTP_OFF = 0, L2PD_EOTP_BLOCK = 1, L2PD_EOTP_STEP = 2 };
  *                       fewer forwards.
  *   L2PD_RAGGED_COMPACT as BLOCKS, and l2pd_generate moves the sequences that are still decoding to the
  *                       leading rows whenever some have finished, so later forwards run over fewer rows
- *                       (l2pd_denoise_step, and l2pd_generate with L2PD_EOTP_STEP, treat it as BLOCKS).
- * Full recompute only (kv_cache must be L2PD_CACHE_NONE). */
+ *                       (l2pd_denoise_step, l2pd_generate with L2PD_EOTP_STEP, and the cached modes treat it
+ *                       as BLOCKS).
+ * With a K/V cache (Sec. 4.3) and per-sequence blocks every sequence's slice of the stores is rebuilt when
+ * that sequence enters a new block (a forward over that sequence alone), and a step's block rows sit at
+ * per-sequence positions; l2pd_generate then looks at the device state before every step. */
 enum { L2PD_RAGGED_OFF = 0, L2PD_RAGGED_BLOCKS = 1, L2PD_RAGGED_COMPACT = 2 };
 
 /* Decode arguments of Alg. 2 / Alg. 3: generation length L_gen, block size s, threshold tau. */
@@ -248,8 +251,8 @@ enum {
 /* Selects one kernel class (L2PD_K_NONE switches timing off) and clears the counters. */
 int32_t l2pd_profile_select(l2pd_ctx* ctx, int32_t kernel_class);
 /* Synchronises the recorded events and returns the number of timed launches of the selected class
- * since the last select and the sum of their durations in milliseconds (event-pair time minus the time
- * of an event pair with nothing inside, which is sampled on the same stream next to the timed launches). */
+ * since the last select and the sum of their event-pair durations in milliseconds (each includes the gap
+ * between the event and the kernel on the stream: an upper bound of the kernel's own time by a few percent). */
 int32_t l2pd_profile_read(l2pd_ctx* ctx, int64_t* launches_out, double* total_ms_out);
 
 const char* l2pd_strerror(int32_t status);

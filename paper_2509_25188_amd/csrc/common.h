@@ -15,6 +15,7 @@ typedef __hip_bfloat16 bf16;
 // Device control block (int32 words).  Written by k_prepare at the start of every step.  The words
 // from CTL_SEQ_GB on hold the active block of every sequence: the batch's common one in lock step,
 // the sequence's own with per-sequence block pointers.
+// After them (from CTL_SEQ_GB + max_batch on; k_prepare is told where) one word per sequence: 1 once it is done.
 enum { CTL_GB = 0, CTL_ALL_DONE = 1, CTL_ACTIVE = 2, CTL_TMAX = 3, CTL_WORDS = 8, CTL_SEQ_GB = 8 };
 
 // Every kernel of a step is gated: once decoding has stopped (or, with the prefix cache, once the
@@ -59,7 +60,8 @@ void launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t s);
 void launch_rope_table(float* cos_t, float* sin_t, int max_pos, int head_dim, float base, hipStream_t s);
 void launch_init_decode(int32_t* X, const int32_t* prompt, int B, int P, int G, int mask_id, int32_t* state,
                         int* ctl, hipStream_t s);
-void launch_prepare(const int32_t* state, int B, int n_blocks, int ragged, int* ctl, hipStream_t s);
+void launch_prepare(const int32_t* state, int B, int n_blocks, int ragged, int* ctl, hipStream_t s,
+                    int done_at = 0);   // done_at > 0: also ctl[done_at + b] = sequence b's done flag
 void launch_embed(float* h, const void* emb, int dtype, const int32_t* tokens, RowMap tokmap, int rows, int d,
                   Gate g, hipStream_t s);
 // h (+= part[0] + ... + part[n_parts-1] in that order when given) -> y = rmsnorm(h) * gain, rows taken
@@ -119,6 +121,8 @@ int filter_param_count(int s, int hidden, int n_layers);
 int filter_train_supported(int s, int hidden, int n_layers);
 void launch_filter_train(const TrainArgs& a, hipStream_t s);
 void launch_seq_len(const int32_t* X, int B, int P, int G, int eos_id, int* teff, int* ctl, hipStream_t s);
+// keys[b] = base + ctl[CTL_SEQ_GB + b] * per_gb: keys a sequence's block rows may see under the prefix cache
+void launch_block_keys(const int* ctl, int B, int base, int per_gb, int* keys, hipStream_t s);
 
 // ---- vocabulary reduction over materialised logits (fp32 path and the logits tap) ----
 struct BiasArgs {
@@ -135,9 +139,10 @@ void launch_vocab_partials(float* logits, int rows, int V, int chunk, int mask_i
 void launch_gemm_f32(const float* A, const float* W, float* C, int M, int N, int K, int accumulate, Gate g,
                      hipStream_t s);
 // rotate q [rows, d] in place and copy/rotate k, v rows into the [B, Tmax, d] key/value stores at pos0 + t
+// (seq_gb / pos_per_gb: per-sequence position offsets as in QkvEpilogue)
 void launch_rope_store_f32(float* q, const float* k, const float* v, float* kstore, float* vstore, int B, int Tq,
-                           int pos0, int Tmax, int H, int Dh, const float* cos_t, const float* sin_t, Gate g,
-                           hipStream_t s);
+                           int pos0, int Tmax, int H, int Dh, const float* cos_t, const float* sin_t,
+                           const int* seq_gb, int pos_per_gb, Gate g, hipStream_t s);
 void launch_attn_f32(const float* q, const float* kstore, const float* vstore, float* out, int B, int Tq, int Tk,
                      int Tmax, int H, int Dh, const int* tk_dev, Gate g, hipStream_t s);
 void launch_swiglu_f32(const float* gate, const float* up, float* act, size_t n, Gate g, hipStream_t s);
@@ -149,7 +154,14 @@ struct QkvEpilogue {
   bf16* vtstore;         // [B, H, Dh, Tpad]
   const float *cos_t, *sin_t;  // [max_pos, Dh/2]
   int Tq, pos0, Tpad, H, Dh, d;
+  // per-sequence block pointers with a K/V cache: row t of sequence b sits at position
+  // pos0 + seq_gb[b] * pos_per_gb + t (seq_gb = the control block's per-sequence active blocks); null: pos0 + t
+  const int* seq_gb;
+  int pos_per_gb;
 };
+__device__ __forceinline__ int seq_pos_offset(const int* seq_gb, int per_gb, int b) {
+  return seq_gb ? seq_gb[b] * per_gb : 0;
+}
 void launch_gemm_qkv_bf16(const bf16* A, const bf16* wq, const bf16* wk, const bf16* wv, int M, int K,
                           const QkvEpilogue& e, Gate g, hipStream_t s);
 // partial[z][M,N] = A[:, z-th K slice] * W[:, slice]^T, z < splits (1 or 2)

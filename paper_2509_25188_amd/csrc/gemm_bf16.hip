@@ -344,7 +344,7 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
   } else if constexpr (EPI == EPI_QKV) {
     const QkvEpilogue& e = a.qkv;
     const int half = e.Dh / 2, gph = half / 32;
-    const bool vec4 = (e.Tq % 4 == 0) && (e.pos0 % 4 == 0) && (e.Tpad % 4 == 0);
+    const bool vec4 = (e.Tq % 4 == 0) && (e.pos0 % 4 == 0) && (e.Tpad % 4 == 0) && (!e.seq_gb || e.pos_per_gb % 4 == 0);
 #pragma unroll
     for (int p = 0; p < FN / 2; ++p) {
       int G = tile_n * (BN / 64) + wn * (FN / 2) + p;
@@ -360,7 +360,7 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
           for (int rq = 0; rq < 4; ++rq) {
             int row0 = row_base + i * 32 + rq * 8 + hf * 4;
             if (vec4 && row0 + 3 < a.M) {
-              int b = row0 / e.Tq, pos = e.pos0 + row0 % e.Tq;
+              int b = row0 / e.Tq, pos = e.pos0 + seq_pos_offset(e.seq_gb, e.pos_per_gb, b) + row0 % e.Tq;
               size_t o = ((size_t)(b * e.H + head) * e.Dh + dim) * e.Tpad + pos;
               unsigned short* vt = reinterpret_cast<unsigned short*>(e.vtstore);
               uint2 lo4, hi4;
@@ -375,7 +375,7 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
               for (int rr = 0; rr < 4; ++rr) {
                 int row = row0 + rr;
                 if (row >= a.M) continue;
-                int b = row / e.Tq, pos = e.pos0 + row % e.Tq;
+                int b = row / e.Tq, pos = e.pos0 + seq_pos_offset(e.seq_gb, e.pos_per_gb, b) + row % e.Tq;
                 size_t o = ((size_t)(b * e.H + head) * e.Dh + dim) * e.Tpad + pos;
                 unsigned short* vt = reinterpret_cast<unsigned short*>(e.vtstore);
                 vt[o] = f2bf(acc[i][2 * p][rq * 4 + rr]);
@@ -392,15 +392,20 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
 #pragma unroll
           for (int rq = 0; rq < 4; ++rq) {
             const int row0 = row_base + i * 32 + rq * 8 + hf * 4;
-            int t = row0 % e.Tq;
+            int t = row0 % e.Tq, bq = row0 / e.Tq;
+            int off = (e.seq_gb && row0 < a.M) ? e.seq_gb[bq] * e.pos_per_gb : 0;
 #pragma unroll
             for (int rr = 0; rr < 4; ++rr) {
               const int r = rq * 4 + rr;
               const bool live = row0 + rr < a.M;
-              const unsigned ti = (unsigned)(e.pos0 + t) * (unsigned)half + (unsigned)dim;   // < 2^31 by construction
+              const unsigned ti = (unsigned)(e.pos0 + off + t) * (unsigned)half + (unsigned)dim;   // < 2^31 by construction
               cs[r] = live ? e.cos_t[ti] : 0.f;
               sn[r] = live ? e.sin_t[ti] : 0.f;
-              if (++t == e.Tq) t = 0;
+              if (++t == e.Tq) {   // next sequence of the batch
+                t = 0;
+                ++bq;
+                off = (e.seq_gb && row0 + rr + 1 < a.M) ? e.seq_gb[bq] * e.pos_per_gb : 0;
+              }
             }
           }
           // rotate, round, and turn "one column, four rows" per lane into "four columns, one row"
@@ -425,7 +430,7 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
             if (mat == 0) {
               o = (size_t)row * e.d + head * e.Dh + c4;
             } else {
-              const int b = row / e.Tq, pos = e.pos0 + row % e.Tq;
+              const int b = row / e.Tq, pos = e.pos0 + seq_pos_offset(e.seq_gb, e.pos_per_gb, b) + row % e.Tq;
               o = ((size_t)b * e.Tpad + pos) * e.d + head * e.Dh + c4;
             }
             uint2 lo, hi;   // feature c4..c4+3 and its partner c4+half..c4+half+3

@@ -54,7 +54,7 @@ void launch_gemm_f32(const float* A, const float* W, float* C, int M, int N, int
 // stores at absolute position pos0 + t.
 __global__ void k_rope_store_f32(float* q, const float* k, const float* v, float* kstore, float* vstore, int B,
                                  int Tq, int pos0, int Tmax, int H, int Dh, const float* cos_t, const float* sin_t,
-                                 Gate g) {
+                                 const int* seq_gb, int pos_per_gb, Gate g) {
   if (gate_skip(g)) return;
   const int half = Dh / 2, d = H * Dh;
   size_t n = (size_t)B * Tq * H * half;
@@ -63,7 +63,7 @@ __global__ void k_rope_store_f32(float* q, const float* k, const float* v, float
   int e = i % half;
   int hh = (i / half) % H;
   int r = i / ((size_t)half * H);
-  int b = r / Tq, t = r % Tq, pos = pos0 + t;
+  int b = r / Tq, t = r % Tq, pos = pos0 + seq_pos_offset(seq_gb, pos_per_gb, b) + t;
   float c = cos_t[pos * half + e], sn = sin_t[pos * half + e];
   size_t src = (size_t)r * d + hh * Dh + e;
   size_t dst = ((size_t)b * Tmax + pos) * d + hh * Dh + e;
@@ -77,11 +77,11 @@ __global__ void k_rope_store_f32(float* q, const float* k, const float* v, float
   vstore[dst + half] = v[src + half];
 }
 void launch_rope_store_f32(float* q, const float* k, const float* v, float* kstore, float* vstore, int B, int Tq,
-                           int pos0, int Tmax, int H, int Dh, const float* cos_t, const float* sin_t, Gate g,
-                           hipStream_t s) {
+                           int pos0, int Tmax, int H, int Dh, const float* cos_t, const float* sin_t,
+                           const int* seq_gb, int pos_per_gb, Gate g, hipStream_t s) {
   size_t n = (size_t)B * Tq * H * (Dh / 2);
   hipLaunchKernelGGL(k_rope_store_f32, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, q, k, v, kstore, vstore,
-                     B, Tq, pos0, Tmax, H, Dh, cos_t, sin_t, g);
+                     B, Tq, pos0, Tmax, H, Dh, cos_t, sin_t, seq_gb, pos_per_gb, g);
 }
 
 // Bidirectional softmax attention, one wavefront per (sequence, head, query): lanes own keys for the

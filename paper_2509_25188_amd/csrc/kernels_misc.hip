@@ -56,7 +56,7 @@ void launch_init_decode(int32_t* X, const int32_t* prompt, int B, int P, int G, 
 // Active block of the lock-step batch = smallest block index among sequences that are not done.
 // With `ragged` every sequence works on its own block (per-sequence block pointers): nobody idles
 // while another sequence finishes the common block.
-__global__ void k_prepare(const int32_t* state, int B, int n_blocks, int ragged, int* ctl) {
+__global__ void k_prepare(const int32_t* state, int B, int n_blocks, int ragged, int* ctl, int done_at) {
   if (threadIdx.x == 0 && blockIdx.x == 0) {
     int gb = n_blocks, all_done = 1, n_active = 0;
     for (int b = 0; b < B; ++b) {
@@ -75,11 +75,20 @@ __global__ void k_prepare(const int32_t* state, int B, int n_blocks, int ragged,
     for (int b = 0; b < B; ++b) {
       const int own = state[b * 3 + 0] < last ? state[b * 3 + 0] : last;
       ctl[CTL_SEQ_GB + b] = ragged ? own : ctl[CTL_GB];
+      if (done_at > 0) ctl[done_at + b] = state[b * 3 + 2] ? 1 : 0;
     }
   }
 }
-void launch_prepare(const int32_t* state, int B, int n_blocks, int ragged, int* ctl, hipStream_t s) {
-  hipLaunchKernelGGL(k_prepare, dim3(1), dim3(64), 0, s, state, B, n_blocks, ragged, ctl);
+void launch_prepare(const int32_t* state, int B, int n_blocks, int ragged, int* ctl, hipStream_t s, int done_at) {
+  hipLaunchKernelGGL(k_prepare, dim3(1), dim3(64), 0, s, state, B, n_blocks, ragged, ctl, done_at);
+}
+
+__global__ void k_block_keys(const int* ctl, int B, int base, int per_gb, int* keys) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b < B) keys[b] = base + ctl[CTL_SEQ_GB + b] * per_gb;
+}
+void launch_block_keys(const int* ctl, int B, int base, int per_gb, int* keys, hipStream_t s) {
+  hipLaunchKernelGGL(k_block_keys, dim3((B + 63) / 64), dim3(64), 0, s, ctl, B, base, per_gb, keys);
 }
 
 // Batch compaction: rows of sequences that are not done move to the front (order kept), finished
@@ -378,7 +387,7 @@ __global__ void __launch_bounds__(256) k_skinny_qkv_finish(const float* parts, i
     x1 += p[z * part_stride];
     x2 += p[z * part_stride + half];
   }
-  const int b = row / e.Tq, pos = e.pos0 + row % e.Tq;
+  const int b = row / e.Tq, pos = e.pos0 + seq_pos_offset(e.seq_gb, e.pos_per_gb, b) + row % e.Tq;
   if (mat == 2) {
     unsigned short* vt = reinterpret_cast<unsigned short*>(e.vtstore);
     const size_t o = ((size_t)(b * e.H + head) * e.Dh + i) * e.Tpad + pos;

@@ -54,7 +54,6 @@ struct l2pd_ctx {
   // timing aid
   int prof_class = 0;
   std::vector<ProfileEv> prof;
-  std::vector<ProfileEv> prof_empty;   // brackets with nothing inside, sampled next to the timed ones
   std::vector<ProfileEv> prof_pool;
   int last_hip_error = 0;
   int pend_splits = 0;   // bf16: split-K partials of the last down projection still to be folded into h
@@ -101,7 +100,7 @@ Layout make_layout(const l2pd_model_desc& m, int max_batch, int max_seq, int cac
   const size_t head_rows = (size_t)max_batch * 256;   // block_len <= 256
   L.cos_t = c.take((size_t)L.Tpad * (m.head_dim / 2) * 4);
   L.sin_t = c.take((size_t)L.Tpad * (m.head_dim / 2) * 4);
-  L.ctl = c.take((size_t)(CTL_WORDS + max_batch) * 4);
+  L.ctl = c.take((size_t)(CTL_WORDS + 2 * max_batch) * 4);   // control words, per-sequence blocks, per-sequence done flags
   L.state = c.take((size_t)max_batch * 3 * 4);
   L.state2 = c.take((size_t)max_batch * 3 * 4);   // second copies for batch compaction
   L.perm = c.take((size_t)max_batch * 4);
@@ -192,23 +191,6 @@ struct Timed {
       on = false;
       return;
     }
-    // every 16th timed launch is preceded by a bracket with nothing inside: what an event pair costs
-    // by itself on this stream, subtracted when the timings are read
-    if (c->prof.size() % 16 == 0) {
-      ProfileEv e0;
-      bool ok = true;
-      if (!c->prof_pool.empty()) {
-        e0 = c->prof_pool.back();
-        c->prof_pool.pop_back();
-      } else {
-        ok = hipEventCreate(&e0.a) == hipSuccess && hipEventCreate(&e0.b) == hipSuccess;
-      }
-      if (ok) {
-        (void)hipEventRecord(e0.a, s);
-        (void)hipEventRecord(e0.b, s);
-        c->prof_empty.push_back(e0);
-      }
-    }
     (void)hipEventRecord(ev.a, s);
   }
   ~Timed() {
@@ -226,7 +208,9 @@ struct Pass {
   const int32_t* tokens;
   bool per_layer_kv;    // prefix cache: one K/V store per layer
   bool kv_only_last;    // refresh pass: the last layer only has to leave its K/V
-  const int* tk_dev = nullptr;   // step-granular EoTP: per-sequence number of keys (device), else null
+  const int* tk_dev = nullptr;   // per-sequence number of keys (device), else null
+  int kv_seq = 0;       // first sequence slot of the K/V stores this pass works on (single-sequence store rebuilds)
+  int pos_per_gb = 0;   // > 0: per-sequence block pointers with a cache: sequence b's rows sit at pos0 + own block * pos_per_gb
 };
 
 void run_layers(l2pd_ctx* c, const Pass& p, Gate g, hipStream_t s) {
@@ -235,7 +219,9 @@ void run_layers(l2pd_ctx* c, const Pass& p, Gate g, hipStream_t s) {
   const int rows = p.B * p.Tq, d = m.d_model, F = m.d_ffn, H = m.n_heads, Dh = m.head_dim;
   const RowMap ident = {rows, 0, 0, 0};
   float* h = c->at<float>(L.h);
-  launch_embed(h, c->tok_emb, m.dtype, p.tokens, RowMap{p.Tq, p.Tfull, p.pos0, 0}, rows, d, g, s);
+  launch_embed(h, c->tok_emb, m.dtype, p.tokens, RowMap{p.Tq, p.Tfull, p.pos0, p.pos_per_gb}, rows, d, g, s);
+  const int* seq_gb = p.pos_per_gb ? c->at<int>(L.ctl) + CTL_SEQ_GB : nullptr;
+  const size_t kv_seq_off = (size_t)p.kv_seq * L.Tpad * d * (m.dtype == L2PD_FP32 ? 4 : 2);
   const float* cos_t = c->at<float>(L.cos_t);
   const float* sin_t = c->at<float>(L.sin_t);
   bool pending = false;   // bf16: split-K partials of the previous projection not yet folded into h
@@ -247,8 +233,8 @@ void run_layers(l2pd_ctx* c, const Pass& p, Gate g, hipStream_t s) {
     if (m.dtype == L2PD_FP32) {
       float* xn = c->at<float>(L.xn);
       float* q = c->at<float>(L.q);
-      float* ks = reinterpret_cast<float*>(c->ws + L.kstore + kvo_k);
-      float* vs = reinterpret_cast<float*>(c->ws + L.vstore + kvo_v);
+      float* ks = reinterpret_cast<float*>(c->ws + L.kstore + kvo_k + kv_seq_off);
+      float* vs = reinterpret_cast<float*>(c->ws + L.vstore + kvo_v + kv_seq_off);
       { Timed t(c, L2PD_K_NORM, s);
         launch_rmsnorm(h, nullptr, 0, 0, ident, c->attn_g[l], m.dtype, xn, rows, d, m.rms_eps, true, g, s); }
       { Timed t(c, L2PD_K_GEMM_QKV, s);
@@ -256,7 +242,7 @@ void run_layers(l2pd_ctx* c, const Pass& p, Gate g, hipStream_t s) {
         launch_gemm_f32(xn, (const float*)c->wk[l], c->at<float>(L.tmp_k), rows, d, d, 0, g, s);
         launch_gemm_f32(xn, (const float*)c->wv[l], c->at<float>(L.tmp_v), rows, d, d, 0, g, s);
         launch_rope_store_f32(q, c->at<float>(L.tmp_k), c->at<float>(L.tmp_v), ks, vs, p.B, p.Tq, p.pos0, L.Tpad, H,
-                              Dh, cos_t, sin_t, g, s); }
+                              Dh, cos_t, sin_t, seq_gb, p.pos_per_gb, g, s); }
       if (p.kv_only_last && l + 1 == m.n_layers) break;
       { Timed t(c, L2PD_K_ATTN, s);
         launch_attn_f32(q, ks, vs, c->at<float>(L.attn), p.B, p.Tq, p.Tk, L.Tpad, H, Dh, p.tk_dev, g, s); }
@@ -275,15 +261,15 @@ void run_layers(l2pd_ctx* c, const Pass& p, Gate g, hipStream_t s) {
     } else {
       bf16* xn = c->at<bf16>(L.xn);
       bf16* q = c->at<bf16>(L.q);
-      bf16* ks = reinterpret_cast<bf16*>(c->ws + L.kstore + kvo_k);
-      bf16* vts = reinterpret_cast<bf16*>(c->ws + L.vstore + kvo_v);
+      bf16* ks = reinterpret_cast<bf16*>(c->ws + L.kstore + kvo_k + kv_seq_off);
+      bf16* vts = reinterpret_cast<bf16*>(c->ws + L.vstore + kvo_v + kv_seq_off);
       float* parts = c->at<float>(L.parts);
       const bool skinny = rows <= kSkinnyRows;
       { Timed t(c, L2PD_K_NORM, s);
         launch_rmsnorm(h, pending ? parts : nullptr, pend_splits, pend_stride, ident, c->attn_g[l], m.dtype, xn, rows,
                        d, m.rms_eps, true, g, s); }
       pending = false;
-      QkvEpilogue e = {q, ks, vts, cos_t, sin_t, p.Tq, p.pos0, L.Tpad, H, Dh, d};
+      QkvEpilogue e = {q, ks, vts, cos_t, sin_t, p.Tq, p.pos0, L.Tpad, H, Dh, d, seq_gb, p.pos_per_gb};
       { Timed t(c, L2PD_K_GEMM_QKV, s);
         if (skinny) {
           const int S = skinny_splits(3 * d, d);
@@ -404,7 +390,6 @@ int check_decode_args(const l2pd_ctx* c, int B, int P, const l2pd_decode_cfg* cf
   if (cfg->eotp < 0 || cfg->eotp > L2PD_EOTP_STEP) return L2PD_EINVAL;
   if (cfg->eotp == L2PD_EOTP_STEP && cfg->kv_cache) return L2PD_ENOTIMPL;   // shortened sequences: full recompute only
   if (cfg->ragged < 0 || cfg->ragged > L2PD_RAGGED_COMPACT) return L2PD_EINVAL;
-  if (cfg->ragged && cfg->kv_cache) return L2PD_ENOTIMPL;   // the K/V stores are rebuilt for one common block
   if (cfg->bias.value != 0.f && (cfg->bias.token_id < 0 || cfg->bias.token_id >= c->m.vocab)) return L2PD_EINVAL;
   if (isnan(cfg->bias.value)) return L2PD_EINVAL;
   return L2PD_OK;
@@ -434,7 +419,19 @@ void run_refresh(l2pd_ctx* c, const int32_t* X, int B, int P, const l2pd_decode_
   run_layers(c, p, g, s);
 }
 
-// One denoising step for the lock-step batch.  host_gb >= 0 is required with the prefix cache.
+// The same for one sequence of the batch (per-sequence block pointers with a cache): its slice of the
+// stores is rebuilt from its own tokens for its own block gb.
+void run_refresh_seq(l2pd_ctx* c, const int32_t* X, int b, int P, const l2pd_decode_cfg* cfg, int gb, Gate g,
+                     hipStream_t s) {
+  const int T = P + cfg->gen_len;
+  const int rows = cfg->kv_cache == L2PD_CACHE_DUAL ? T : P + gb * cfg->block_len;
+  Pass p = {1, rows, 0, rows, T, X + (size_t)b * T, true, true};
+  p.kv_seq = b;
+  run_layers(c, p, g, s);
+}
+
+// One denoising step for the lock-step batch.  host_gb >= 0 is required with a cache, unless every
+// sequence follows its own block pointer (then the store rebuilds are the caller's, per sequence).
 // t_run > 0 (step-granular EoTP): the forward runs over the first t_run positions of every sequence,
 // each sequence attending to its own teff[b] <= t_run keys.
 void run_step(l2pd_ctx* c, int32_t* X, int B, int P, const l2pd_decode_cfg* cfg, const l2pd_filter* f,
@@ -444,9 +441,22 @@ void run_step(l2pd_ctx* c, int32_t* X, int B, int P, const l2pd_decode_cfg* cfg,
   const int sl = cfg->block_len, T = P + cfg->gen_len, nb = cfg->gen_len / sl;
   int* ctl = c->at<int>(L.ctl);
   launch_prepare(state, B, nb, cfg->ragged, ctl, s);
-  Gate g = {ctl, cfg->kv_cache ? host_gb : -1};
+  const bool own_blocks_cached = cfg->kv_cache && cfg->ragged;
+  Gate g = {ctl, (cfg->kv_cache && !own_blocks_cached) ? host_gb : -1};
   BiasArgs bias = {cfg->bias.token_id, cfg->bias.gen_pos_from, sl, cfg->bias.value};
-  if (cfg->kv_cache) {
+  if (own_blocks_cached) {
+    // per-sequence block pointers: every sequence's block rows sit at its own positions (read from the
+    // control block by the embedding, the rotation / store epilogues and the update), and with the prefix
+    // cache every sequence sees its own number of keys
+    Pass p = {B, sl, P, T, T, X, true, false};
+    p.pos_per_gb = sl;
+    if (cfg->kv_cache == L2PD_CACHE_PREFIX) {
+      launch_block_keys(ctl, B, P + sl, sl, c->at<int>(L.teff), s);
+      p.tk_dev = c->at<int>(L.teff);
+    }
+    run_layers(c, p, g, s);
+    run_head(c, B, sl, RowMap{B * sl, 0, 0, 0}, taps.logits, true, bias, g, s);
+  } else if (cfg->kv_cache) {
     // block rows only; their K/V go into the store at the block's positions, and the queries see
     // the store up to the end of the block (prefix cache) or all of it (dual cache)
     const int cpos = P + host_gb * sl;
@@ -487,7 +497,10 @@ void run_step(l2pd_ctx* c, int32_t* X, int B, int P, const l2pd_decode_cfg* cfg,
 
 int ensure_pinned(l2pd_ctx* c) {
   if (c->pinned) return L2PD_OK;
-  HIP_TRY(c, hipHostMalloc(reinterpret_cast<void**>(&c->pinned), 2 * CTL_WORDS * sizeof(int), hipHostMallocDefault));
+  // two slots of control words for the polling loop; one view of the whole control block (per-sequence
+  // blocks and done flags) starts at slot 0 for the schedules that need it
+  const size_t words = std::max<size_t>(2 * CTL_WORDS, CTL_WORDS + 2 * (size_t)c->max_batch);
+  HIP_TRY(c, hipHostMalloc(reinterpret_cast<void**>(&c->pinned), words * sizeof(int), hipHostMallocDefault));
   HIP_TRY(c, hipEventCreateWithFlags(&c->poll_ev[0], hipEventDisableTiming));
   HIP_TRY(c, hipEventCreateWithFlags(&c->poll_ev[1], hipEventDisableTiming));
   return L2PD_OK;
@@ -593,7 +606,6 @@ void l2pd_destroy(l2pd_ctx* c) {
   if (!c) return;
   for (auto& e : c->prof) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
   for (auto& e : c->prof_pool) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
-  for (auto& e : c->prof_empty) { (void)hipEventDestroy(e.a); (void)hipEventDestroy(e.b); }
   if (c->pinned) (void)hipHostFree(c->pinned);
   for (auto& e : c->poll_ev) if (e) (void)hipEventDestroy(e);
   delete c;
@@ -642,11 +654,19 @@ int32_t l2pd_denoise_step(l2pd_ctx* c, int32_t* tokens_dev, int32_t B, int32_t p
     HIP_TRY(c, hipStreamSynchronize(s));
     const int nb = cfg->gen_len / cfg->block_len;
     host_gb = nb;
-    for (int b = 0; b < B; ++b)
+    for (int b = 0; b < B; ++b) {
+      if (hs[b * 3] < 0) return L2PD_EINVAL;
       if (!hs[b * 3 + 2] && hs[b * 3] < host_gb) host_gb = hs[b * 3];
+    }
     if (host_gb >= nb) return L2PD_OK;   // every sequence is done: nothing to do
-    if (host_gb < 0) return L2PD_EINVAL;
-    if (!cfg->keep_kv) run_refresh(c, tokens_dev, B, prompt_len, cfg, host_gb, Gate{nullptr, -1}, s);
+    if (cfg->ragged) {
+      // every live sequence's slice of the stores is rebuilt for its own block
+      for (int b = 0; b < B && !cfg->keep_kv; ++b)
+        if (!hs[b * 3 + 2] && hs[b * 3] < nb)
+          run_refresh_seq(c, tokens_dev, b, prompt_len, cfg, hs[b * 3], Gate{nullptr, -1}, s);
+    } else if (!cfg->keep_kv) {
+      run_refresh(c, tokens_dev, B, prompt_len, cfg, host_gb, Gate{nullptr, -1}, s);
+    }
   }
   StepTaps taps = {logits_dev, conf_dev, pred_dev, filt_dev, unmask_dev};
   int t_run = 0;
@@ -745,6 +765,26 @@ int32_t l2pd_generate(l2pd_ctx* c, const int32_t* prompt_dev, int32_t B, int32_t
       run_step(c, X, B, P, cfg, f, state, -1, no_taps, s, t_run);
     }
     launch_seq_len(X, B, P, G, c->m.eos_id, c->at<int>(L.teff), ctl, s);
+  } else if (cfg->kv_cache && cfg->ragged) {
+    // Per-sequence block pointers with a cache: the host looks at the whole control block before every
+    // step (a sequence that has moved on to a new block needs its slice of the stores rebuilt first, a
+    // forward over that sequence alone), then enqueues one step for the batch.  Every live sequence
+    // commits at least one position per step, so gen_len iterations suffice.
+    std::vector<int> host_gb((size_t)B, -1);
+    const int done_at = CTL_SEQ_GB + c->max_batch, words = CTL_WORDS + 2 * c->max_batch;
+    for (int k = 0; k <= G; ++k) {
+      launch_prepare(state, B, nb, 1, ctl, s, done_at);
+      HIP_TRY(c, hipMemcpyAsync(c->pinned, ctl, (size_t)words * sizeof(int), hipMemcpyDeviceToHost, s));
+      HIP_TRY(c, hipStreamSynchronize(s));
+      if (c->pinned[CTL_ALL_DONE]) break;
+      for (int b = 0; b < B; ++b) {
+        const int gb = c->pinned[CTL_SEQ_GB + b];
+        if (c->pinned[done_at + b] || gb == host_gb[b]) continue;
+        run_refresh_seq(c, X, b, P, cfg, gb, Gate{nullptr, -1}, s);
+        host_gb[b] = gb;
+      }
+      run_step(c, X, B, P, cfg, f, state, -1, no_taps, s);
+    }
   } else if (cfg->kv_cache) {
     for (int gb = 0; gb < nb; ++gb) {
       launch_prepare(state, B, nb, cfg->ragged, ctl, s);
@@ -844,9 +884,7 @@ int32_t l2pd_filter_train_static(const l2pd_filter* f, const float* conf_rows_de
 int32_t l2pd_profile_select(l2pd_ctx* c, int32_t cls) {
   if (!c || cls < 0 || cls > L2PD_K_UPDATE) return L2PD_EINVAL;
   for (auto& e : c->prof) c->prof_pool.push_back(e);
-  for (auto& e : c->prof_empty) c->prof_pool.push_back(e);
   c->prof.clear();
-  c->prof_empty.clear();
   c->prof_class = cls;
   return L2PD_OK;
 }
@@ -860,14 +898,6 @@ int32_t l2pd_profile_read(l2pd_ctx* c, int64_t* launches_out, double* total_ms_o
     HIP_TRY(c, hipEventElapsedTime(&ms, e.a, e.b));
     total += ms;
   }
-  double empty = 0.0;
-  for (auto& e : c->prof_empty) {
-    HIP_TRY(c, hipEventSynchronize(e.b));
-    float ms = 0.f;
-    HIP_TRY(c, hipEventElapsedTime(&ms, e.a, e.b));
-    empty += ms;
-  }
-  if (!c->prof_empty.empty()) total -= empty / (double)c->prof_empty.size() * (double)c->prof.size();
   *launches_out = (int64_t)c->prof.size();
   *total_ms_out = total > 0.0 ? total : 0.0;
   return L2PD_OK;

@@ -116,8 +116,7 @@ def test_decode_argument_checks_return_before_any_launch():
 
 
 def test_mode_combinations_that_are_not_built_are_refused():
-    # the cached modes rebuild their K/V store for one common block, and step-granular EoTP resizes the
-    # forward every step: per-sequence block pointers / step-granular EoTP with a cache must say so
+    # step-granular EoTP resizes the forward every step: with a K/V cache it must say that it is not built
     lib = Bd.lib()
     m = synth.WORKLOADS["tiny"].model
     d = Bd.model_desc(m)
@@ -135,8 +134,6 @@ def test_mode_combinations_that_are_not_built_are_refused():
             return lib.l2pd_generate(ctx, 0x1000, 1, 32, C.byref(cfg), C.byref(f), 0x1000, None, None, None)
 
         for cache in ("prefix_cache", "dual_cache"):
-            assert gen(Bd.Engine.cfg_struct(64, 32, 0.5, ragged=Bd.RAGGED_BLOCKS, **{cache: True})) == Bd.L2PD_ENOTIMPL
-            assert gen(Bd.Engine.cfg_struct(64, 32, 0.5, ragged=Bd.RAGGED_COMPACT, **{cache: True})) == Bd.L2PD_ENOTIMPL
             assert gen(Bd.Engine.cfg_struct(64, 32, 0.5, eotp=Bd.EOTP_STEP, **{cache: True})) == Bd.L2PD_ENOTIMPL
     finally:
         lib.l2pd_destroy(ctx)

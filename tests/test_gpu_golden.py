@@ -89,3 +89,28 @@ def test_8b_g256_two_layers_whole_trajectory():
     eng, flt = engine(w, 1)
     rep, rows, _ = forced_and_free("8b_g256_L2", w, (0,), eng, flt, exempt_frac=0.05)
     assert rep.max_logit_err < 2e-2
+
+
+def test_8b_b32_prefix_two_layers_trajectories_and_batch_of_32():
+    # block 64, prefix cache, EoTP with the end-of-text bias from generation position 400: sequences 0 and 17
+    # of the batch, each teacher-forced along its own stored trajectory and decoded alone; then the whole
+    # batch of 32 DIFFERENT prompts in one call, rows 0 and 17 against the same stored results (a batched
+    # block-only step has 2048 rows and takes other GEMM tiles and split depths than the 64-row step of a
+    # single sequence, so the rows agree to rounding, not bit for bit: compared under the exemption rules)
+    w = synth.with_layers(synth.WORKLOADS["8b_b32_prefix"], 2)
+    eng, flt = engine(w, w.batch)
+    rep, rows, loaded = forced_and_free("8b_b32_prefix_L2", w, (0, 17), eng, flt, exempt_frac=0.05)
+    assert rep.max_logit_err < 2e-2
+    cfg = Pz.cfg_for(w)
+    prompts = synth.make_prompt(SEED, w.batch, w.prompt_len, w.prompt_hi, "cuda")
+    assert len({tuple(r) for r in prompts.cpu().numpy().tolist()}) == w.batch          # 32 different prompts
+    tok, st, dl = eng.generate(prompts, flt, cfg)
+    tok, st, dl = tok.cpu().numpy(), st.cpu().numpy(), dl.cpu().numpy()
+    stop = (w.bias_from // w.block_len + 1) * w.block_len
+    assert np.all(dl == stop) and not np.any(tok[:, :stop] == w.model.mask_id) and np.all(tok[:, stop:] == w.model.mask_id)
+    assert len(set(st.tolist())) > 1                                                    # sequences in different states
+    for b in (0, 17):
+        recs, result, first_exempt = loaded[b]
+        assert int(dl[b]) == result[2]
+        Pz.check_generate(tok[b], st[b], dl[b], recs, *result, first_exempt, w.prompt_len, w.block_len,
+                          f"8b_b32_prefix_L2 batch of 32, row {b}")

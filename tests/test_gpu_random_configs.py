@@ -24,7 +24,7 @@ def draw(seed):
     B = int(r.integers(1, 4))
     eotp_mode = int(r.integers(0, 3))                       # off, block, step
     cache = int(r.integers(0, 3)) if eotp_mode != 2 else 0   # step-granular EoTP is full recompute only
-    ragged = int(r.integers(0, 3)) if cache == 0 else 0      # batch schedules are full recompute only
+    ragged = int(r.integers(0, 3))                            # lock step, own blocks, own blocks + compaction
     bias_from = int(r.integers(0, G)) if eotp_mode and r.random() < 0.8 else -1
     w = synth.Workload(f"rand{seed}", TINY, B, P, G, s, int(r.choice([8, 32, 48])), float(r.choice([0.3, 0.5, 0.8])),
                        eotp=eotp_mode > 0, eotp_step=eotp_mode == 2, prefix_cache=cache == 1, dual_cache=cache == 2,

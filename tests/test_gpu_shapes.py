@@ -203,7 +203,7 @@ def test_lm_head_wide_tile_batched_blocks():
     assert torch.allclose(taps["conf"], taps2["conf"], rtol=1e-5, atol=1e-7)
 
 
-def _full_size_decode(name, batch, rows_identical):
+def _full_size_decode(name, batch, duplicate_last):
     """Whole decode of a named workload at its full depth and batch, in the launch configuration that
     bench.py times; checked through properties that hold at any size (the oracle would need hours)."""
     w = synth.WORKLOADS[name]
@@ -212,8 +212,8 @@ def _full_size_decode(name, batch, rows_identical):
     eng = Bd.engine_for(w, SEED, "cuda")
     flt = synth.make_filter(SEED, w.block_len, w.filter_hidden, "cuda")
     prompt = synth.make_prompt(SEED, w.batch, w.prompt_len, w.prompt_hi, "cuda")
-    if rows_identical:
-        prompt = prompt[:1].repeat(w.batch, 1).contiguous()
+    if duplicate_last:
+        prompt[-1] = prompt[0]          # the last sequence repeats the first; all others differ
     tok, st, dl = eng.generate(prompt, flt, Pz.cfg_for(w))
     torch.cuda.synchronize()
     return w, tok.cpu().numpy(), st.cpu().numpy(), dl.cpu().numpy()
@@ -238,12 +238,14 @@ def test_full_size_eotp_workload_properties():
 
 
 def test_full_size_batched_prefix_cache_properties():
-    # 32 sequences, 32 layers, block 64, prefix cache: identical prompts must give identical rows
-    # (rows of a batch never interact and run through the same kernels), and every row obeys Alg. 3
+    # 32 sequences with 31 different prompts, 32 layers, block 64, prefix cache: the sequences sit in
+    # different states throughout (different step counts), every row obeys Alg. 3, and the one repeated
+    # prompt gives a repeated row (rows of a batch never interact and run through the same kernels)
     w, tok, steps, dlen = _full_size_decode("8b_b32_prefix", 32, True)
     _check_eotp_properties(w, tok, steps, dlen)
-    assert np.all(tok == tok[0]) and np.all(steps == steps[0]) and np.all(dlen == dlen[0])
-    print(f"8b_b32_prefix at full size: {int(steps[0])} steps per sequence, {int(dlen[0])} tokens each")
+    assert np.array_equal(tok[31], tok[0]) and steps[31] == steps[0]
+    assert len({tuple(r) for r in tok[:31].tolist()}) == 31 and len(set(steps.tolist())) > 1
+    print(f"8b_b32_prefix at full size: steps per sequence {steps.min()}..{steps.max()}, {int(dlen[0])} tokens each")
 
 
 def test_8b_width_batch_rows_are_bit_identical_to_their_single_runs():
