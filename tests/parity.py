@@ -245,9 +245,11 @@ def check_generate(tok_row, steps, dlen, trace, resp, o_steps, o_dlen, first_exe
         np.testing.assert_array_equal(tok_row, resp)
         assert int(steps) == int(o_steps) and int(dlen) == int(o_dlen)
         return True
+    keep = min(int(dlen), int(o_dlen))     # step-granular EoTP discards what was committed behind the end-of-text
     for rec in trace[:first_exempt]:
         g0 = rec["block"] * block_len
         idx = np.nonzero(np.asarray(rec["sel"]))[0]
+        idx = idx[g0 + idx < keep]
         np.testing.assert_array_equal(tok_row[g0 + idx], np.asarray(rec["pre"])[idx])
     same = bool(np.array_equal(tok_row, resp)) and int(steps) == int(o_steps)
     print(f"{what}: first exempt step {first_exempt} of {len(trace)}; free-running result identical to the oracle's: {same} "

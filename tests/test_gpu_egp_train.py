@@ -59,9 +59,19 @@ def test_egp_rollout_bf16_rows_close_where_labels_agree():
     Co, Yo, per_block = O.egp_rollout(ora, prompt[0].numpy(), ref[0], w.gen_len, w.block_len, w.model.mask_id)
     n = int(steps[0])
     C, Y = C.cpu().numpy()[0, :n], Y.cpu().numpy()[0, :n]
-    print("bf16 EGP rollout: steps", n, "oracle", len(Co))
-    if n == len(Co) and np.array_equal(Y, Yo):          # same decisions (near-ties may differ in bf16)
-        assert np.max(np.abs(C - Co) / np.maximum(Co, 1e-3)) < 0.4
+    # Both rollouts follow the same trajectory until a near-tie is resolved differently in bf16 (a prediction
+    # that equals the reference in one arithmetic and not in the other).  Up to and including the first row
+    # whose labels differ the two were computed from the same state, so those confidence rows must agree;
+    # if no row differs the rollouts are identical throughout.
+    m = min(n, len(Co))
+    differ = [i for i in range(m) if not np.array_equal(Y[i], Yo[i])]
+    k = min(differ[0] + 1, m) if differ else m
+    print(f"bf16 EGP rollout: {n} rows, oracle {len(Co)}; first row with different labels: "
+          f"{differ[0] if differ else None}; confidence rows compared: {k}")
+    assert k >= 1
+    assert np.max(np.abs(C[:k] - Co[:k]) / np.maximum(Co[:k], 1e-3)) < 0.4
+    if not differ:
+        assert n == len(Co)
     # invariants that hold whatever the rounding: labels are 0/1, committed entries are (1.0, 1), the last row of a
     # block has no masked position left afterwards, row count within bounds
     assert set(np.unique(Y)) <= {0.0, 1.0}

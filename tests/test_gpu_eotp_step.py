@@ -76,3 +76,39 @@ def test_step_eotp_bf16_ragged_lengths_in_a_batch():
     for b in range(3):
         Pz.check_generate(tok.cpu().numpy()[b], st[b], dl[b], traces[b], *outs[b], forced.first_exempt[b],
                           w.prompt_len, w.block_len, f"step EoTP bf16 seq {b}")
+
+
+def test_step_eotp_bf16_prompt_shorter_than_block_in_a_batch():
+    # prompt_len < block_len: once a sequence has been shortened inside its block, the head's rows past its
+    # end map onto rows of the NEXT sequence in the forward's row space.  Those rows must be read, never
+    # written (the final norm folds the last projection's partials without writing the sum back), or two head
+    # rows would add the partials to one row of the residual stream twice.
+    w = small_bf16("bf_es2", 2, 256, 2, 128, 320, 1500, 3, 8, 96, 32, hidden=32, tau=0.8, eotp=True, eotp_step=True,
+                   bias_from=12, bias_value=60.0)
+    eng, ora, flt, prompt = build(w, lm_head_scale=25.0)
+    fdev = {k: v.cuda() for k, v in flt.items()}
+    traces, outs = oracle_runs(w, ora, flt, prompt)
+    assert any(t["n"] < 32 for tr in traces for t in tr)          # steps on a shortened first block
+    assert all(o[2] < 32 for o in outs)                             # every sequence ends inside block 0
+    Pz.annotate_fmt(traces, ora.alt, w)
+    rep = Pz.StepReport()
+    forced = Pz.teacher_forced(eng, traces, w.prompt_len, Pz.cfg_for(w), fdev, w.model, w.threshold, rep)
+    print("step-granular EoTP bf16, prompt 8 < block 32, teacher-forced:", rep, "decoded lengths", [o[2] for o in outs])
+    assert rep.max_logit_err < 2e-2
+    assert rep.exempt_tokens + rep.exempt_decisions <= 0.08 * rep.positions
+    # the batched call itself: the last (most shortened) state of every sequence imposed in ONE step of B = 3
+    last = [tr[-1] for tr in traces]
+    assert last[0]["n"] < 32
+    X = torch.tensor(np.stack([r["X_before"] for r in last]), dtype=torch.int32, device="cuda")
+    state = torch.tensor([[0, len(tr) - 1, 0] for tr in traces], dtype=torch.int32, device="cuda")
+    taps = eng.denoise_step(X, w.prompt_len, state, fdev, Pz.cfg_for(w), want_logits=True)
+    torch.cuda.synchronize()
+    rep3 = Pz.StepReport()
+    for b in range(3):
+        Pz.check_step(last[b], taps, b, w.model, w.threshold, Pz.tol_for(w.model), rep3)
+    print("  batched step on the shortened states:", rep3)
+    assert rep3.max_logit_err < 2e-2
+    tok, st, dl = eng.generate(prompt.cuda(), fdev, Pz.cfg_for(w))
+    for b in range(3):
+        Pz.check_generate(tok.cpu().numpy()[b], st[b], dl[b], traces[b], *outs[b], forced.first_exempt[b],
+                          w.prompt_len, w.block_len, f"step EoTP bf16 short prompt seq {b}")
