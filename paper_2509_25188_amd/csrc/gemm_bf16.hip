@@ -18,6 +18,8 @@
 // tile: fragment 2p of a wave holds side 0 and fragment 2p+1 side 1 of the same 32 columns.
 #include "common.h"
 
+#include <type_traits>
+
 namespace l2pd {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
@@ -100,7 +102,18 @@ __device__ __forceinline__ void dma16(const void* gptr, unsigned lds_addr) {
                : "memory", "m0");
 }
 
-template <int BM, int BN, int BK, int WM, int WN, int NS, int EPI>
+// AREG (tiles whose wavefronts all sit side by side in M, WN == 1): a wavefront's A rows are read by that
+// wavefront alone, so staging them in LDS buys no reuse and costs LDS bandwidth twice (the write of the
+// direct-to-LDS load and the fragment read), and LDS bandwidth is what bounds the loop (taking A's LDS
+// traffic out of the 256 x 192 gate/up loop, A not loaded at all, moves it from 1.04 to 1.22 PFLOP/s).
+// With AREG the A fragments go global -> registers directly, in the MFMA operand layout (lane (row, half)
+// loads the 16 bytes it feeds to a K-step), through a ring of four register sets, the stage they are
+// for being NS-1 stages ahead like the LDS ring of B; only B is staged in LDS.  The K loop is unrolled
+// four times so that the register sets are addressed statically.  A must be quad-tiled in memory (see
+// gemm_a_quad_tiled): the operand layout puts consecutive lanes on consecutive rows, and from a row-major A
+// every lane's 16 bytes would lie in a cache line of their own (64 tag look-ups per wavefront load; measured
+// 131 us against 107 for the gate/up GEMM); quad-tiled, one wavefront load is eight whole lines.
+template <int BM, int BN, int BK, int WM, int WN, int NS, int EPI, bool AREG = false>
 __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
   constexpr int NT = WM * WN * 64;
   constexpr int NW = WM * WN;
@@ -108,17 +121,22 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
   constexpr bool PAIR = (EPI == EPI_QKV || EPI == EPI_SWIGLU);
   static_assert(!PAIR || (FN % 2 == 0), "pair epilogues need an even number of column fragments");
   static_assert(BK == 32 || BK == 64, "LDS tile rows hold 32 or 64 K elements");
+  static_assert(!AREG || (WN == 1 && NS == 4), "A in registers: wavefronts side by side in M, four register sets");
   constexpr int CPR = BK / 8;               // 16-byte chunks per LDS row
   constexpr int RPD = 64 / CPR;             // rows filled by one direct-to-LDS wave load (1 KB)
   constexpr int KEY_SHIFT = BK == 64 ? 1 : 2;   // rows per 256-byte bank sweep = 1 << KEY_SHIFT
-  constexpr int LPS = (BM + BN) / RPD / NW; // direct-to-LDS loads per thread per stage
-  static_assert(LPS * NW * RPD == BM + BN, "tile/threads mismatch");
-  static_assert(NS >= 3 && (NS - 2) * LPS < 64, "ring depth: at least 3 stages, vmcnt is 6 bits");
+  constexpr int KS = BK / 16;               // MFMA K-steps per stage
+  constexpr int LROWS = AREG ? BN : BM + BN;    // tile rows staged in LDS
+  constexpr int LPS = LROWS / RPD / NW;     // direct-to-LDS loads per thread per stage
+  constexpr int LPSW = LPS + (AREG ? FM * KS : 0);   // vector memory loads per thread per stage (what vmcnt counts)
+  static_assert(LPS * NW * RPD == LROWS, "tile/threads mismatch");
+  static_assert(NS >= 3 && (NS - 2) * LPSW < 64, "ring depth: at least 3 stages, vmcnt is 6 bits");
 
   if (gate_skip(a.gate)) return;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  // [stage][A: BM rows | B: BN rows][BK bf16]
-  constexpr int STAGE_BYTES = (BM + BN) * BK * 2;
+  // [stage][A: BM rows (unless AREG) | B: BN rows][BK bf16]
+  constexpr int STAGE_BYTES = LROWS * BK * 2;
+  constexpr int BROW0 = AREG ? 0 : BM;      // first LDS row of the B tile
 
   // ---- tile assignment: consecutive ids on one XCD share a weight panel ----
   const int total = a.tiles_m * a.tiles_n * a.splits;
@@ -152,11 +170,11 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
     const int q = wave + i * NW;
     const int rr = q * RPD + lane / CPR;         // row in the combined [A; B] tile
     const int c = (lane % CPR) ^ ((rr >> KEY_SHIFT) & (CPR - 1));   // global chunk that belongs at this lane's slot
-    if (rr < BM) {
+    if (rr < BROW0) {
       int gr = min(m0 + rr, a.M - 1);
       src[i] = a.A + (size_t)gr * a.K + k_begin + c * 8;
     } else {
-      const int r = rr - BM;
+      const int r = rr - BROW0;
       const bf16* base;
       size_t grow;
       if constexpr (!PAIR) {
@@ -189,15 +207,42 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
   // LDS byte address of this wave's first slot in stage 0 (wave-uniform, goes to M0)
   const unsigned lds0 = __builtin_amdgcn_readfirstlane(
       (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)(smem + wave * 1024));
-  constexpr int KS = BK / 16;   // MFMA K-steps per stage
+  // AREG: this lane's 16 bytes of fragment i at K-step 0 of stage 0
+  const bf16* pa[FM];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+  {
+    // quad-tiled A (see gemm_a_quad_tiled): chunk c of row r at ((r / 4) * (K / 8) + c) * 32 + (r % 4) * 8
+    const int r = min(m0 + wm * (BM / WM) + i * 32 + lj, a.M - 1);
+    pa[i] = a.A + ((size_t)(r >> 2) * (a.K / 8) + k_begin / 8 + hf) * 32 + (r & 3) * 8;
+  }
+  bf16x8_t ra[AREG ? 4 : 1][FM][KS];
   // Loads of one stage are issued in KS parts (load i belongs to part i % KS), one part per K-step,
   // so that they trickle into the texture-address queue behind MFMAs instead of arriving as a burst
   // from every wave right after the barrier (a burst stalls instruction issue until the queue drains).
-  auto issue_part = [&](int kt, int part) {
-    const unsigned dst = lds0 + (kt % NS) * STAGE_BYTES;
+  // kt < 0: nothing left to stage in LDS.  The A register loads (AREG) are issued all the same, from the
+  // last stage's address when stage kt_a lies behind the end of K: the compiler counts the loads it knows
+  // of to place its own waits, and a count that depended on a branch would make it wait for every load.
+  auto issue_part = [&](auto setc, int kt, int kt_a, int part) {
+    constexpr int SET = decltype(setc)::value;    // AREG: register set of stage kt_a (kt_a % 4, known statically)
+    if (kt >= 0) {
+      const unsigned dst = lds0 + (kt % NS) * STAGE_BYTES;
 #pragma unroll
-    for (int i = 0; i < LPS; ++i)
-      if (i % KS == part) dma16(src[i] + kt * BK, dst + i * NW * 1024);
+      for (int i = 0; i < LPS; ++i)
+        if (i % KS == part) dma16(src[i] + kt * BK, dst + i * NW * 1024);
+    }
+    if constexpr (AREG) {
+      // plain loads; the direct-to-LDS loads around them are volatile asm with a memory clobber, so all of
+      // them stay where they are in the instruction stream and vmcnt counts LPSW loads per stage
+      const int kc = min(kt_a, nk - 1);
+#pragma unroll
+      for (int pp = 0; pp < KS; ++pp)
+        if (pp == part) {
+#pragma unroll
+          for (int i = 0; i < FM; ++i)
+            ra[SET][i][pp] = *reinterpret_cast<const bf16x8_t*>(pa[i] + (kc * (BK / 8) + pp * 2) * 32);
+        }
+    }
   };
 
   f32x16 acc[FM][FN];
@@ -213,7 +258,7 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
 #pragma unroll
   for (int i = 0; i < FM; ++i) offA[i] = (wm * (BM / WM) + i * 32 + lj) * (BK * 2);
 #pragma unroll
-  for (int j = 0; j < FN; ++j) offB[j] = BM * (BK * 2) + (wn * (BN / WN) + j * 32 + lj) * (BK * 2);
+  for (int j = 0; j < FN; ++j) offB[j] = BROW0 * (BK * 2) + (wn * (BN / WN) + j * 32 + lj) * (BK * 2);
   const int key = (lj >> KEY_SHIFT) & (CPR - 1);   // row's swizzle key (fragment bases are multiples of 32)
 
   // Software pipeline.  Fragments are double-buffered in registers: the ds_reads of K-step kk+1 are
@@ -224,46 +269,73 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
   bf16x8_t fa[2][FM], fb[2][FN];
   auto read_frags = [&](int buf, const unsigned char* base, int kk) {
     const int sw = ((kk * 2 + hf) ^ key) << 4;
+    if constexpr (!AREG) {
 #pragma unroll
-    for (int i = 0; i < FM; ++i) fa[buf][i] = *reinterpret_cast<const bf16x8_t*>(base + offA[i] + sw);
+      for (int i = 0; i < FM; ++i) fa[buf][i] = *reinterpret_cast<const bf16x8_t*>(base + offA[i] + sw);
+    }
 #pragma unroll
     for (int j = 0; j < FN; ++j) fb[buf][j] = *reinterpret_cast<const bf16x8_t*>(base + offB[j] + sw);
   };
-  // One K-step: the FM*FN MFMAs on fragment set `cur`, with the FM+FN ds_reads that fetch set
-  // `cur ^ 1` (K-step kk_next of the stage at `nbase`) slotted in between them, one read after each
-  // of the first MFMAs, so that every read is issued while an MFMA occupies the matrix pipe.
-  auto step = [&](int cur, const unsigned char* nbase, int kk_next, int dma_kt, int dma_part) {
+  // One K-step: the FM*FN MFMAs on fragment set `cur`, with the ds_reads that fetch set `cur ^ 1`
+  // (K-step kk_next of the stage at `nbase`) slotted in between them, one read after each of the
+  // first MFMAs, so that every read is issued while an MFMA occupies the matrix pipe.  (AREG: the A
+  // fragments of the step are register set SET's, and only the FN reads of B are slotted in.)
+  constexpr int NR = AREG ? FN : FM + FN;
+  auto step = [&](auto setc, auto dsetc, int cur, const unsigned char* nbase, int kk_next, int dma_kt, int dma_kt_a,
+                  int dma_part) {
+    constexpr int SET = decltype(setc)::value;
     const int sw = ((kk_next * 2 + hf) ^ key) << 4;
     const int nxt = cur ^ 1;
 #pragma unroll
     for (int idx = 0; idx < FM * FN; ++idx) {
       const int i = idx / FN, j = idx % FN;
-      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0);
-#pragma unroll
-      for (int r = 0; r < FM + FN; ++r) {
-        if ((r < FM * FN ? r : FM * FN - 1) != idx) continue;   // read r goes after MFMA min(r, last)
-        if (r < FM) fa[nxt][r] = *reinterpret_cast<const bf16x8_t*>(nbase + offA[r] + sw);
-        else fb[nxt][r - FM] = *reinterpret_cast<const bf16x8_t*>(nbase + offB[r - FM] + sw);
+      if constexpr (AREG) {
+        // cur == the K-step within the stage (KS == 2); both candidates are registers, the select is static
+        // after unrolling because every call site passes a constant
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur == 0 ? ra[SET][i][0] : ra[SET][i][KS - 1], fb[cur][j],
+                                                            acc[i][j], 0, 0, 0);
+      } else {
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0);
       }
-      if (idx == 0 && dma_kt >= 0) issue_part(dma_kt, dma_part);   // asm volatile: stays in program order
+#pragma unroll
+      for (int r = 0; r < NR; ++r) {
+        if ((r < FM * FN ? r : FM * FN - 1) != idx) continue;   // read r goes after MFMA min(r, last)
+        if constexpr (AREG) {
+          fb[nxt][r] = *reinterpret_cast<const bf16x8_t*>(nbase + offB[r] + sw);
+        } else {
+          if (r < FM) fa[nxt][r] = *reinterpret_cast<const bf16x8_t*>(nbase + offA[r] + sw);
+          else fb[nxt][r - FM] = *reinterpret_cast<const bf16x8_t*>(nbase + offB[r - FM] + sw);
+        }
+      }
+      if (idx == 0 && (AREG || dma_kt >= 0)) issue_part(dsetc, dma_kt, dma_kt_a, dma_part);   // stays in program order
     }
 #pragma unroll
     for (int idx = 0; idx < FM * FN; ++idx) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA, then the LDS reads of its slot
 #pragma unroll
-      for (int r = 0; r < FM + FN; ++r)
+      for (int r = 0; r < NR; ++r)
         if ((r < FM * FN ? r : FM * FN - 1) == idx) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
     }
     __builtin_amdgcn_sched_barrier(0);
   };
+  static_assert(!AREG || KS == 2, "A in registers: two K-steps per stage");
 
+  {
+    auto pro = [&](auto setc) {
+      constexpr int ST = decltype(setc)::value;
+      if (ST < NS - 1 && (AREG || ST < nk)) {   // AREG: nk is a multiple of four
 #pragma unroll
-  for (int st = 0; st < NS - 1; ++st)
-    if (st < nk) {
-#pragma unroll
-      for (int part = 0; part < KS; ++part) issue_part(st, part);
-    }
-  if (nk >= NS - 1) wait_vmcnt<(NS - 2) * LPS>();
+        for (int part = 0; part < KS; ++part) issue_part(setc, ST, ST, part);
+      }
+    };
+    pro(std::integral_constant<int, 0>{});
+    pro(std::integral_constant<int, 1>{});
+    pro(std::integral_constant<int, 2>{});
+    static_assert(NS - 1 <= 5, "prologue covers up to five stages");
+    if constexpr (NS - 1 > 3) pro(std::integral_constant<int, 3>{});
+    if constexpr (NS - 1 > 4) pro(std::integral_constant<int, 4>{});
+  }
+  if (nk >= NS - 1) wait_vmcnt<(NS - 2) * LPSW>();
   else wait_vmcnt<0>();
   lds_barrier();
   // Drain scalar loads here, so that only in-order LDS reads are pending when the loop is entered
@@ -271,15 +343,18 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
   __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
   read_frags(0, smem, 0);
   __builtin_amdgcn_sched_barrier(0);
-  for (int kt = 0; kt < nk; ++kt) {
+  // One stage of the K loop; SET = kt % 4 names the register sets statically (ignored without AREG).
+  auto stage = [&](auto setc, int kt) {
+    constexpr int SET = decltype(setc)::value;
     const unsigned char* base = smem + (kt % NS) * STAGE_BYTES;
     // parts 1 .. KS-1 of stage kt+NS-2 (its part 0 went out with the last K-step of iteration kt-1)
     const int dma_a = (kt >= 1 && kt + NS - 2 < nk) ? kt + NS - 2 : -1;
 #pragma unroll
-    for (int kk = 0; kk < KS - 1; ++kk) step(kk & 1, base, kk + 1, dma_a, kk + 1);
+    for (int kk = 0; kk < KS - 1; ++kk)
+      step(setc, std::integral_constant<int, (SET + NS - 2) % 4>{}, kk & 1, base, kk + 1, dma_a, kt + NS - 2, kk + 1);
     if (kt + 1 < nk) {
       // stage kt+1 has landed once at most the loads of the NS-3 younger stages are outstanding
-      if (kt + NS - 2 < nk) wait_vmcnt<(NS - 3) * LPS>();
+      if (kt + NS - 2 < nk) wait_vmcnt<(NS - 3) * LPSW>();
       else wait_vmcnt<0>();
       lds_barrier();   // stage kt+1 visible to all; every wave is past its reads of stage kt-1
     }
@@ -288,7 +363,18 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
     // fetch stale but valid LDS that nobody uses): a branch around them would make the compiler's
     // LDS wait counts conservative at the join.  The buffer of stage kt-1 is free from here on:
     // start refilling it with stage kt+NS-1.
-    step((KS - 1) & 1, smem + ((kt + 1) % NS) * STAGE_BYTES, 0, (kt + NS - 1 < nk) ? kt + NS - 1 : -1, 0);
+    step(setc, std::integral_constant<int, (SET + NS - 1) % 4>{}, (KS - 1) & 1, smem + ((kt + 1) % NS) * STAGE_BYTES, 0,
+         (kt + NS - 1 < nk) ? kt + NS - 1 : -1, kt + NS - 1, 0);
+  };
+  if constexpr (AREG) {
+    for (int kt = 0; kt < nk; kt += 4) {   // the launcher guarantees nk % 4 == 0
+      stage(std::integral_constant<int, 0>{}, kt);
+      stage(std::integral_constant<int, 1>{}, kt + 1);
+      stage(std::integral_constant<int, 2>{}, kt + 2);
+      stage(std::integral_constant<int, 3>{}, kt + 3);
+    }
+  } else {
+    for (int kt = 0; kt < nk; ++kt) stage(std::integral_constant<int, 0>{}, kt);
   }
   lds_barrier();
 
@@ -517,10 +603,10 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
-template <int BM, int BN, int BK, int WM, int WN, int NS, int EPI>
+template <int BM, int BN, int BK, int WM, int WN, int NS, int EPI, bool AREG = false>
 static void launch(GemmArgs& a, hipStream_t s) {
-  auto kern = k_gemm_bf16<BM, BN, BK, WM, WN, NS, EPI>;
-  constexpr int smem = NS * (BM + BN) * BK * 2;
+  auto kern = k_gemm_bf16<BM, BN, BK, WM, WN, NS, EPI, AREG>;
+  constexpr int smem = NS * ((AREG ? 0 : BM) + BN) * BK * 2;
   static DynLdsAttr attr;
   attr.ensure(reinterpret_cast<const void*>(kern), smem);
   a.tiles_m = (a.M + BM - 1) / BM;
@@ -554,6 +640,16 @@ static int pick_tile(int M, int N) {   // 0: 128x128, 1: 256x128, 2: 256x256, 3:
   return best;
 }
 
+// The A-in-registers loop is unrolled over its four register sets: K must be a whole number of four
+// 32-wide stages; the widths are those for which the RMSNorm has a kernel that writes the quad-tiled layout.
+// (The layout changes no arithmetic: a row's results are the same bits on either path.)
+// Only the 256 x 192 tile takes it: there a wavefront feeds two A fragments to every K-step (gate/up at 512
+// rows: 101 -> 92 us); with the single A fragment of the 128 x 192 tile, LDS traffic is nearly all B's and the
+// register path gains nothing (Q/K/V at 512 rows: 77.3 -> 78.7 us).
+bool gemm_a_quad_tiled(int M, int N, int K) {
+  return pick_tile(M, N) == 3 && K % 128 == 0 && K >= 2048 && K <= 8192;
+}
+
 void launch_gemm_qkv_bf16(const bf16* A, const bf16* wq, const bf16* wk, const bf16* wv, int M, int K,
                           const QkvEpilogue& e, Gate g, hipStream_t s) {
   GemmArgs a = {};
@@ -561,7 +657,10 @@ void launch_gemm_qkv_bf16(const bf16* A, const bf16* wq, const bf16* wk, const b
   a.M = M; a.N = 3 * e.d; a.K = K; a.splits = 1; a.gate = g; a.qkv = e;
   switch (pick_tile(M, a.N)) {
     case 4: launch<128, 192, 32, 4, 1, 4, EPI_QKV>(a, s); break;
-    case 3: launch<256, 192, 32, 4, 1, 4, EPI_QKV>(a, s); break;
+    case 3:
+      if (gemm_a_quad_tiled(M, a.N, K)) launch<256, 192, 32, 4, 1, 4, EPI_QKV, true>(a, s);
+      else launch<256, 192, 32, 4, 1, 4, EPI_QKV>(a, s);
+      break;
     case 2: launch<256, 256, 32, 4, 2, 4, EPI_QKV>(a, s); break;
     case 1: launch<256, 128, 32, 4, 2, 6, EPI_QKV>(a, s); break;
     default: launch<128, 128, 64, 2, 2, 4, EPI_QKV>(a, s);
@@ -633,7 +732,10 @@ void launch_gemm_swiglu_bf16(const bf16* A, const bf16* wg, const bf16* wu, bf16
   }
   switch (pick_tile(M, a.N)) {
     case 4: launch<128, 192, 32, 4, 1, 4, EPI_SWIGLU>(a, s); break;
-    case 3: launch<256, 192, 32, 4, 1, 4, EPI_SWIGLU>(a, s); break;
+    case 3:
+      if (gemm_a_quad_tiled(M, a.N, K)) launch<256, 192, 32, 4, 1, 4, EPI_SWIGLU, true>(a, s);
+      else launch<256, 192, 32, 4, 1, 4, EPI_SWIGLU>(a, s);
+      break;
     case 2: launch<256, 256, 32, 4, 2, 4, EPI_SWIGLU>(a, s); break;
     case 1: launch<256, 128, 32, 4, 2, 6, EPI_SWIGLU>(a, s); break;
     default: launch<128, 128, 64, 2, 2, 4, EPI_SWIGLU>(a, s);

@@ -267,11 +267,20 @@ __global__ void __launch_bounds__(256) k_rmsnorm_vec(float* h, const float* part
 template <typename T, int VPL>
 __global__ void __launch_bounds__(256) k_rmsnorm_row(float* h, const float* parts, int n_parts, size_t part_stride,
                                                     RowMap src, const T* gain, T* y, int rows, int d, float eps,
-                                                    int wb, Gate g) {
+                                                    int wb, int quad_tiled, Gate g) {
   if (gate_skip(g)) return;
   __shared__ float s_part[4];
   const int tid = threadIdx.x;
-  const int r = blockIdx.x;
+  int r = blockIdx.x;
+  if (quad_tiled) {
+    // Quad-tiled output interleaves four rows inside every 128-byte line.  Workgroups are dealt to the 8
+    // XCDs round-robin by their id; give the four rows of a group to workgroups of one XCD, so that the
+    // line is completed in that XCD's L2 before it is written back.  (A permutation of [0, gridDim.x), the
+    // grid being the row count rounded up to 32.)
+    const int xcd = r & 7, slot = r >> 3;
+    r = ((slot >> 2) * 8 + xcd) * 4 + (slot & 3);
+    if (r >= rows) return;
+  }
   const size_t srow = (size_t)map_row(src, r, g.ctl);
   const int d4 = d >> 2;
   float4* x = reinterpret_cast<float4*>(h + srow * d);
@@ -318,6 +327,8 @@ __global__ void __launch_bounds__(256) k_rmsnorm_row(float* h, const float* part
   ss = (s_part[0] + s_part[1]) + (s_part[2] + s_part[3]);
   const float inv = rsqrtf(ss / (float)d + eps);
   T* o = y + (size_t)r * d;
+  // quad-tiled: the row's 16-byte chunk c sits at ((r / 4) * (d / 8) + c) * 32 + (r % 4) * 8 elements
+  T* oq = y + (size_t)(r >> 2) * 4 * d + (r & 3) * 8;
 #pragma unroll
   for (int k = 0; k < VPL; ++k) {
     const int i = tid + 256 * k;
@@ -330,7 +341,8 @@ __global__ void __launch_bounds__(256) k_rmsnorm_row(float* h, const float* part
       } else {
         T o4[4] = {from_f<T>(v[k].x * inv * to_f<T>(gp[0])), from_f<T>(v[k].y * inv * to_f<T>(gp[1])),
                    from_f<T>(v[k].z * inv * to_f<T>(gp[2])), from_f<T>(v[k].w * inv * to_f<T>(gp[3]))};
-        *reinterpret_cast<uint2*>(o + 4 * i) = *reinterpret_cast<const uint2*>(o4);
+        T* dst = quad_tiled ? oq + (i >> 1) * 32 + (i & 1) * 4 : o + 4 * i;
+        *reinterpret_cast<uint2*>(dst) = *reinterpret_cast<const uint2*>(o4);
       }
     }
   }
@@ -338,14 +350,28 @@ __global__ void __launch_bounds__(256) k_rmsnorm_row(float* h, const float* part
 
 template <typename T>
 static void launch_rmsnorm_t(float* h, const float* parts, int n_parts, size_t part_stride, RowMap src, const T* gain,
-                             T* y, int rows, int d, float eps, bool write_back, Gate g, hipStream_t s) {
+                             T* y, int rows, int d, float eps, bool write_back, Gate g, hipStream_t s, bool quad_tiled) {
   const int wb = write_back ? 1 : 0;
+  if (quad_tiled) {
+    // only the one-row-per-workgroup kernels write it (gemm_a_quad_tiled() asks for it within their range only)
+    if (sizeof(T) != 2 || d % 8 != 0 || d < 2048 || d > 8192 || src.off_per_gb || src.off_base || src.rows_per_seq < rows) {
+      // a caller's mistake, not an input's: the consumer would read another layout than the one written
+      fprintf(stderr, "l2pd: quad-tiled RMSNorm output asked for outside its range (d = %d)\n", d);
+      abort();
+    }
+    const int grid_q = (rows + 31) / 32 * 32;
+    if (d <= 4096)
+      hipLaunchKernelGGL((k_rmsnorm_row<T, 4>), dim3(grid_q), dim3(256), 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, wb, 1, g);
+    else
+      hipLaunchKernelGGL((k_rmsnorm_row<T, 8>), dim3(grid_q), dim3(256), 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, wb, 1, g);
+    return;
+  }
   dim3 grid((rows + 3) / 4), block(256);
   if (rows <= 4096) { grid = dim3(rows); block = dim3(64); }   // few rows: one wavefront per workgroup fills more CUs
   if (d % 4 == 0 && d >= 2048 && d <= 4096)
-    hipLaunchKernelGGL((k_rmsnorm_row<T, 4>), dim3(rows), dim3(256), 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, wb, g);
+    hipLaunchKernelGGL((k_rmsnorm_row<T, 4>), dim3(rows), dim3(256), 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, wb, 0, g);
   else if (d % 4 == 0 && d > 4096 && d <= 8192)
-    hipLaunchKernelGGL((k_rmsnorm_row<T, 8>), dim3(rows), dim3(256), 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, wb, g);
+    hipLaunchKernelGGL((k_rmsnorm_row<T, 8>), dim3(rows), dim3(256), 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, wb, 0, g);
   else if (d % 4 == 0 && d <= 1024)
     hipLaunchKernelGGL((k_rmsnorm_vec<T, 4>), grid, block, 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, wb, g);
   else if (d % 4 == 0 && d <= 4096)
@@ -356,12 +382,13 @@ static void launch_rmsnorm_t(float* h, const float* parts, int n_parts, size_t p
     hipLaunchKernelGGL(k_rmsnorm<T>, grid, block, 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, wb, g);
 }
 void launch_rmsnorm(float* h, const float* parts, int n_parts, size_t part_stride, RowMap src, const void* gain,
-                    int dtype, void* y, int rows, int d, float eps, bool write_back, Gate g, hipStream_t s) {
+                    int dtype, void* y, int rows, int d, float eps, bool write_back, Gate g, hipStream_t s,
+                    bool quad_tiled) {
   if (!parts) n_parts = 0;
   if (dtype == L2PD_FP32)
-    launch_rmsnorm_t<float>(h, parts, n_parts, part_stride, src, (const float*)gain, (float*)y, rows, d, eps, write_back, g, s);
+    launch_rmsnorm_t<float>(h, parts, n_parts, part_stride, src, (const float*)gain, (float*)y, rows, d, eps, write_back, g, s, quad_tiled);
   else
-    launch_rmsnorm_t<bf16>(h, parts, n_parts, part_stride, src, (const bf16*)gain, (bf16*)y, rows, d, eps, write_back, g, s);
+    launch_rmsnorm_t<bf16>(h, parts, n_parts, part_stride, src, (const bf16*)gain, (bf16*)y, rows, d, eps, write_back, g, s, quad_tiled);
 }
 
 // ------------------------------------------------------------------------------------------------

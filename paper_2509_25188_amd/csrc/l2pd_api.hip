@@ -109,7 +109,7 @@ Layout make_layout(const l2pd_model_desc& m, int max_batch, int max_seq, int cac
   L.X = c.take(rows * 4);
   L.X2 = c.take(rows * 4);
   L.h = c.take(rows * d * 4);
-  L.xn = c.take(rows * d * es);
+  L.xn = c.take(align_up(rows, 4) * d * es);   // the quad-tiled layout holds whole groups of four rows
   L.q = c.take(rows * d * es);
   L.attn = c.take(rows * d * es);
   L.act = c.take(rows * F * es);
@@ -265,9 +265,12 @@ void run_layers(l2pd_ctx* c, const Pass& p, Gate g, hipStream_t s) {
       bf16* vts = reinterpret_cast<bf16*>(c->ws + L.vstore + kvo_v + kv_seq_off);
       float* parts = c->at<float>(L.parts);
       const bool skinny = rows <= kSkinnyRows;
+      // the activations go to the fused GEMMs in the layout these ask for (row-major or quad-tiled)
+      const bool tiled_qkv = !skinny && gemm_a_quad_tiled(rows, 3 * d, d);
+      const bool tiled_ffn = !skinny && gemm_a_quad_tiled(rows, 2 * F, d);
       { Timed t(c, L2PD_K_NORM, s);
         launch_rmsnorm(h, pending ? parts : nullptr, pend_splits, pend_stride, ident, c->attn_g[l], m.dtype, xn, rows,
-                       d, m.rms_eps, true, g, s); }
+                       d, m.rms_eps, true, g, s, tiled_qkv); }
       pending = false;
       QkvEpilogue e = {q, ks, vts, cos_t, sin_t, p.Tq, p.pos0, L.Tpad, H, Dh, d, seq_gb, p.pos_per_gb};
       { Timed t(c, L2PD_K_GEMM_QKV, s);
@@ -298,7 +301,8 @@ void run_layers(l2pd_ctx* c, const Pass& p, Gate g, hipStream_t s) {
         else
           launch_gemm_partial_bf16(ao, (const bf16*)c->wo[l], parts, stride_d, rows, d, d, so, g, s); }
       { Timed t(c, L2PD_K_NORM, s);
-        launch_rmsnorm(h, parts, so, stride_d, ident, c->ffn_g[l], m.dtype, xn, rows, d, m.rms_eps, true, g, s); }
+        launch_rmsnorm(h, parts, so, stride_d, ident, c->ffn_g[l], m.dtype, xn, rows, d, m.rms_eps, true, g, s,
+                       tiled_ffn); }
       bf16* act = c->at<bf16>(L.act);
       { Timed t(c, L2PD_K_GEMM_GATEUP, s);
         if (skinny && !swiglu_few_rows_fused(rows, F)) {

@@ -33,6 +33,13 @@ def test_stored_trajectory_obeys_the_decode_rule(path):
     if "block" not in z:                      # result of a decode only (EoTP-off companion)
         assert not meta["eotp"] and int(z["decoded_len"]) == G and not np.any(z["tokens"] == m.mask_id)
         assert G // s <= int(z["steps"]) <= G
+        on = path.replace("_eotp_off", "")
+        if os.path.exists(on):
+            # Alg. 3 changes nothing before it stops: the run with EoTP is a prefix of the run without, and shorter
+            zo = np.load(on)
+            dl = int(zo["decoded_len"])
+            np.testing.assert_array_equal(zo["tokens"][:dl], z["tokens"][:dl])
+            assert int(zo["steps"]) < int(z["steps"])
         return
     X, blk, sel, masked = z["X_before"], z["block"], z["sel"].astype(bool), z["masked"].astype(bool)
     conf, pre, p = z["conf"], z["pre"], z["p"]

@@ -114,3 +114,75 @@ def test_8b_b32_prefix_two_layers_trajectories_and_batch_of_32():
         assert int(dl[b]) == result[2]
         Pz.check_generate(tok[b], st[b], dl[b], recs, *result, first_exempt, w.prompt_len, w.block_len,
                           f"8b_b32_prefix_L2 batch of 32, row {b}")
+
+
+def have(case, seq=0):
+    return os.path.exists(path_of(case, seq))
+
+
+def needs(*cases):
+    missing = [c for c in cases if not have(c)]
+    return pytest.mark.skipif(bool(missing), reason=f"stored trajectory not generated: {missing} "
+                                                    "(python tests/golden/make_trajectories.py <case>; hours of CPU)")
+
+
+@needs("8b_g1024_eotp_L2")
+def test_8b_g1024_eotp_two_layers_whole_trajectory_and_steps_saved():
+    # generation length 1024 with EoTP (Alg. 3), the end-of-text bias from generation position 400, 1280 rows of
+    # full recompute: every stored step teacher-forced, then the free-running decode; then the same decode with
+    # EoTP off against the stored EoTP-off result: the steps EoTP saves (Sec. 3.3)
+    w = synth.with_layers(synth.WORKLOADS["8b_g1024_eotp"], 2)
+    eng, flt = engine(w, 1)
+    rep, rows, loaded = forced_and_free("8b_g1024_eotp_L2", w, (0,), eng, flt, exempt_frac=0.05)
+    assert rep.max_logit_err < 2e-2
+    tok_on, st_on, dl_on = rows[0]
+    recs, (o_tok, o_steps, o_dlen), first_exempt = loaded[0]
+    stop = (w.bias_from // w.block_len + 1) * w.block_len
+    assert dl_on == o_dlen == stop and np.all(tok_on[stop:] == w.model.mask_id)
+    if not have("8b_g1024_eotp_L2_eotp_off"):
+        pytest.skip("EoTP-off companion not generated")
+    meta, _, (f_tok, f_steps, f_dlen) = Pz.load_trajectory(path_of("8b_g1024_eotp_L2_eotp_off", 0))
+    cfg_off = Pz.cfg_for(dataclasses.replace(w, eotp=False))
+    prompt = synth.make_prompt(SEED, 1, w.prompt_len, w.prompt_hi, "cuda")
+    tok, st, dl = eng.generate(prompt, flt, cfg_off)
+    tok, st, dl = tok.cpu().numpy()[0], int(st[0]), int(dl[0])
+    assert dl == f_dlen == w.gen_len and not np.any(tok == w.model.mask_id)
+    np.testing.assert_array_equal(f_tok[:stop], o_tok[:stop])          # the oracle's two runs coincide up to the stop
+    np.testing.assert_array_equal(tok[:stop], tok_on[:stop])           # and so do the library's
+    print(f"EoTP on: {st_on} steps (oracle {o_steps}); off: {st} steps (oracle {f_steps}); saved {st - st_on} "
+          f"(oracle {f_steps - o_steps}) = {100.0 * (st - st_on) / st:.1f} % of the steps")
+    assert st > st_on and f_steps > o_steps
+    if first_exempt is None and np.array_equal(tok, f_tok):
+        assert st == f_steps
+    else:
+        # a near-tie somewhere flips a decision and the later blocks differ; the count of steps stays close
+        assert abs(st - f_steps) <= 0.1 * f_steps
+
+
+@needs("8b_g256_full")
+def test_8b_g256_full_depth_whole_trajectory():
+    # the benchmarked workload itself: 32 layers, 512 rows, every step of the oracle's whole trajectory
+    # teacher-forced (logits at the first and last step of every block), then the free-running decode
+    w = synth.WORKLOADS["8b_g256"]
+    eng, flt = engine(w, 1)
+    rep, rows, loaded = forced_and_free("8b_g256_full", w, (0,), eng, flt, exempt_frac=0.15)
+    print("8b_g256 at 32 layers:", rep)
+
+
+@needs("8b_g1024_eotp_full_states_from_L2")
+def test_8b_g1024_eotp_full_depth_block_boundaries():
+    # 32 layers, 1280 rows: the first and last state of every block of the two-layer trajectory, evaluated by the
+    # oracle at full depth
+    w = synth.WORKLOADS["8b_g1024_eotp"]
+    eng, flt = engine(w, 1)
+    rep, _, _ = forced_and_free("8b_g1024_eotp_full_states_from_L2", w, (0,), eng, flt, exempt_frac=0.15)
+    print("8b_g1024_eotp at 32 layers:", rep)
+
+
+@needs("8b_b32_prefix_full_states_from_L2")
+def test_8b_b32_prefix_full_depth_block_boundaries():
+    # 32 layers, block 64, prefix cache rebuilt from every imposed state (sequence 0 of the batch alone)
+    w = synth.WORKLOADS["8b_b32_prefix"]
+    eng, flt = engine(w, 1)
+    rep, _, _ = forced_and_free("8b_b32_prefix_full_states_from_L2", w, (0,), eng, flt, exempt_frac=0.15)
+    print("8b_b32_prefix at 32 layers:", rep)
