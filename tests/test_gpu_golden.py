@@ -161,11 +161,15 @@ def test_8b_g1024_eotp_two_layers_whole_trajectory_and_steps_saved():
 
 @needs("8b_g256_full")
 def test_8b_g256_full_depth_whole_trajectory():
-    # the benchmarked workload itself: 32 layers, 512 rows, every step of the oracle's whole trajectory
-    # teacher-forced (logits at the first and last step of every block), then the free-running decode
+    # the benchmarked workload itself: 32 layers, 512 rows, every step of the oracle's whole trajectory (242
+    # steps) teacher-forced, logits compared at the first and last step of every block, then the free-running
+    # decode.  The logit tolerance is 1.5 x the noise floor stored with the trajectory (the same oracle
+    # accumulated in float64: 1.9e-2 of the largest logit at this depth), see forced_and_free; at this depth the
+    # two oracle evaluations differ by 0.31 logit units, so more positions are near-ties than at two layers
+    # (measured 6.8 % exempt).
     w = synth.WORKLOADS["8b_g256"]
     eng, flt = engine(w, 1)
-    rep, rows, loaded = forced_and_free("8b_g256_full", w, (0,), eng, flt, exempt_frac=0.15)
+    rep, rows, loaded = forced_and_free("8b_g256_full", w, (0,), eng, flt, exempt_frac=0.10)
     print("8b_g256 at 32 layers:", rep)
 
 

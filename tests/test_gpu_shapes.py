@@ -51,6 +51,18 @@ def test_8b_width_two_layers_full_recompute():
     assert rep.max_logit_err < 2e-2
 
 
+def test_8b_width_row_count_that_no_tile_divides():
+    # 509 rows (a prime): the last 256-row GEMM tile, the last group of 32 rows of the quad-tiled activations and
+    # the last group of four are all ragged; one layer, first and last block
+    w = synth.with_layers(synth.WORKLOADS["8b_g256"], 1)
+    w = dataclasses.replace(w, prompt_len=221, gen_len=288)
+    eng, ora, flt = setup(w)
+    rep = Pz.StepReport()
+    forced_steps(w, eng, ora, flt, [(0, 0, 6), (8, 17, 7)], rep)
+    print("8b width, 509 rows:", rep)
+    assert rep.max_logit_err < 2e-2
+
+
 def test_8b_width_eotp_workload_bias_and_long_window():
     # T = 1280 (ragged against 256-row tiles), EOS logit bias from generation position 300
     w = synth.with_layers(synth.WORKLOADS["8b_g1024_eotp"], 1)
@@ -136,44 +148,6 @@ def test_mid_workload_full_depth_batch8():
         print(f"mid: batch row {b} vs its own run: identical={same} steps {int(s1[0])} vs {steps[b]}")
         # different batch sizes pick different GEMM tiles (same K order per element), so rows agree
         assert same and int(s1[0]) == steps[b]
-
-
-def test_8b_full_depth_step_against_both_oracle_precisions():
-    """The benchmarked configuration itself (32 layers, 512 rows), one teacher-forced step.
-
-    A random-init network of this depth amplifies rounding noise: the oracle evaluated with
-    bf16-rounded matrix-product inputs and the oracle with fp32 activations already differ from each
-    other by about 2e-2 of the largest logit (7e-3 at one layer, 1.4e-2 at eight layers, measured).
-    The HIP path must lie within that same distance of both (a kernel error would show as a distance
-    well above the distance between the two oracles), and its decisions must follow the margin rules
-    against the bf16-input oracle, whose arithmetic it implements."""
-    w = synth.WORKLOADS["8b_g256"]
-    weights = synth.make_weights(w.model, SEED, "cpu")
-    ora16 = Pz.oracle_model(w.model, weights, gemm_input="bf16")
-    ora32 = Pz.oracle_model(w.model, weights)
-    eng = Bd.Engine(w.model, Pz.to_dev(weights), 1, w.prompt_len + w.gen_len)
-    del weights
-    flt = synth.make_filter(SEED, w.block_len, w.filter_hidden)
-    fdev = {k: v.cuda() for k, v in flt.items()}
-    block = 3
-    X = Pz.random_state(w, 2, block, 11)
-    rec16 = Pz.oracle_step_record(ora16, X, w, Pz.np_filter(flt), block)
-    Xd = torch.tensor(X, dtype=torch.int32, device="cuda").view(1, -1)
-    state = torch.tensor([[block, 7, 0]], dtype=torch.int32, device="cuda")
-    taps = eng.denoise_step(Xd, w.prompt_len, state, fdev, Pz.cfg_for(w), want_logits=True)
-    torch.cuda.synchronize()
-    lo = w.prompt_len + block * w.block_len
-    ref32 = ora32.forward(X, lo, w.block_len)
-    got = taps["logits"][0].cpu().numpy()
-    e16, e32 = Pz.rel_err(got, rec16["logits"]), Pz.rel_err(got, ref32)
-    e_fmt = Pz.rel_err(rec16["logits"], ref32)
-    print(f"8b full depth: logit distance HIP/bf16-input oracle {e16:.3e}, HIP/fp32-activation oracle {e32:.3e}, "
-          f"between the two oracles {e_fmt:.3e}")
-    assert e16 < 1.5 * e_fmt + 5e-3 and e32 < 1.5 * e_fmt + 5e-3
-    assert e16 < 4e-2 and e32 < 5e-2
-    rep = Pz.StepReport()
-    Pz.check_step(rec16, taps, 0, w.model, w.threshold, 4e-2, rep)
-    print("8b full depth decisions vs bf16-input oracle:", rep)
 
 
 def test_lm_head_wide_tile_batched_blocks():
