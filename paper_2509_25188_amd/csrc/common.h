@@ -69,7 +69,7 @@ void launch_embed(float* h, const void* emb, int dtype, const int32_t* tokens, R
 // when `write_back` is set; the final norm before the LM head leaves h alone (h is dead after it, and
 // two head rows may map to one row of h, so a write-back would race).
 // quad_tiled (bf16, identity row map, d within the one-row-per-workgroup kernels' range): y is written in the
-// layout gemm_a_quad_tiled() describes instead of row-major; the arithmetic is the same.
+// layout gemm_qkv_a_quad_tiled() describes instead of row-major; the arithmetic is the same.
 void launch_rmsnorm(float* h, const float* parts, int n_parts, size_t part_stride, RowMap src, const void* gain,
                     int dtype, void* y, int rows, int d, float eps, bool write_back, Gate g, hipStream_t s,
                     bool quad_tiled = false);
@@ -165,14 +165,15 @@ struct QkvEpilogue {
 __device__ __forceinline__ int seq_pos_offset(const int* seq_gb, int per_gb, int b) {
   return seq_gb ? seq_gb[b] * per_gb : 0;
 }
-// Whether the fused Q/K/V and gate/up GEMMs of M rows, N output columns and depth K read their A operand
-// straight into registers; they then expect it "quad-tiled": groups of four rows, and inside a group the
+// Whether the fused Q/K/V (M rows, model width d, head size Dh) / gate/up (M rows, FFN width F) GEMM of
+// depth K reads its A operand straight into registers; it then expects it "quad-tiled": groups of four rows, and inside a group the
 // 16-byte chunks (8 bf16) of the four rows interleaved, element (r, k) at
 //   ((r / 4) * (K / 8) + k / 8) * 32 + (r % 4) * 8 + k % 8,
 // so that the 32 rows x 2 chunks a wavefront feeds to one MFMA K-step are eight whole 128-byte lines.
 // The buffer needs its row count rounded up to four.  A function of the launch shape only; the producer of
 // A (the RMSNorm before the GEMM) asks the same question.
-bool gemm_a_quad_tiled(int M, int N, int K);
+bool gemm_qkv_a_quad_tiled(int M, int d, int K, int Dh);
+bool gemm_swiglu_a_quad_tiled(int M, int F, int K);
 void launch_gemm_qkv_bf16(const bf16* A, const bf16* wq, const bf16* wk, const bf16* wv, int M, int K,
                           const QkvEpilogue& e, Gate g, hipStream_t s);
 // partial[z][M,N] = A[:, z-th K slice] * W[:, slice]^T, z < splits (1 or 2)

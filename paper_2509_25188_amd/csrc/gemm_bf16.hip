@@ -26,7 +26,13 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
-enum { EPI_PARTIAL = 0, EPI_QKV = 1, EPI_SWIGLU = 2, EPI_LMHEAD = 3 };
+enum { EPI_PARTIAL = 0, EPI_QKV = 1, EPI_SWIGLU = 2, EPI_LMHEAD = 3, EPI_QKV16 = 4 };
+// EPI_QKV and EPI_QKV16 compute the same Q/K/V projection with the same rotation arithmetic; they differ in
+// how the weight rows are dealt to the MFMA column fragments.  EPI_QKV puts 32 first-half features of a head
+// in one fragment and their rotation partners (feature + Dh/2) in the next, so a lane holds both members of
+// a pair (needs an even number of fragments per wavefront).  EPI_QKV16 makes every fragment self-contained:
+// columns 0..15 are 16 first-half features, columns 16..31 their partners, and a lane fetches its partner's
+// value from the lane 16 further on; any number of fragments per wavefront then works (96-column tiles).
 
 struct GemmArgs {
   const bf16* A;
@@ -110,7 +116,7 @@ __device__ __forceinline__ void dma16(const void* gptr, unsigned lds_addr) {
 // loads the 16 bytes it feeds to a K-step), through a ring of four register sets, the stage they are
 // for being NS-1 stages ahead like the LDS ring of B; only B is staged in LDS.  The K loop is unrolled
 // four times so that the register sets are addressed statically.  A must be quad-tiled in memory (see
-// gemm_a_quad_tiled): the operand layout puts consecutive lanes on consecutive rows, and from a row-major A
+// gemm_qkv_a_quad_tiled in common.h): the operand layout puts consecutive lanes on consecutive rows, and from a row-major A
 // every lane's 16 bytes would lie in a cache line of their own (64 tag look-ups per wavefront load; measured
 // 131 us against 107 for the gate/up GEMM); quad-tiled, one wavefront load is eight whole lines.
 template <int BM, int BN, int BK, int WM, int WN, int NS, int EPI, bool AREG = false>
@@ -177,7 +183,14 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
       const int r = rr - BROW0;
       const bf16* base;
       size_t grow;
-      if constexpr (!PAIR) {
+      if constexpr (EPI == EPI_QKV16) {
+        const int half = a.qkv.Dh / 2, gpq = half / 16;
+        const int Gq = tile_n * (BN / 32) + (r >> 5), j = r & 31;
+        const int hg = Gq / gpq, gi = Gq % gpq;
+        const int mat = min(hg / a.qkv.H, 2), head = hg % a.qkv.H;
+        base = mat == 0 ? a.B0 : (mat == 1 ? a.B1 : a.B2);
+        grow = (size_t)(head * a.qkv.Dh + gi * 16 + (j & 15) + (j >> 4) * half);
+      } else if constexpr (!PAIR) {
         int gn = min(n0 + r, a.N - 1);
         base = a.B0;
         if (a.n_sub > 0) {
@@ -212,7 +225,7 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
 #pragma unroll
   for (int i = 0; i < FM; ++i)
   {
-    // quad-tiled A (see gemm_a_quad_tiled): chunk c of row r at ((r / 4) * (K / 8) + c) * 32 + (r % 4) * 8
+    // quad-tiled A (see gemm_qkv_a_quad_tiled in common.h): chunk c of row r at ((r / 4) * (K / 8) + c) * 32 + (r % 4) * 8
     const int r = min(m0 + wm * (BM / WM) + i * 32 + lj, a.M - 1);
     pa[i] = a.A + ((size_t)(r >> 2) * (a.K / 8) + k_begin / 8 + hf) * 32 + (r & 3) * 8;
   }
@@ -281,8 +294,9 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
   // first MFMAs, so that every read is issued while an MFMA occupies the matrix pipe.  (AREG: the A
   // fragments of the step are register set SET's, and only the FN reads of B are slotted in.)
   constexpr int NR = AREG ? FN : FM + FN;
-  auto step = [&](auto setc, auto dsetc, int cur, const unsigned char* nbase, int kk_next, int dma_kt, int dma_kt_a,
+  auto step = [&](auto setc, auto dsetc, int kk, const unsigned char* nbase, int kk_next, int dma_kt, int dma_kt_a,
                   int dma_part) {
+    const int cur = kk & 1;   // fragment set of K-step kk
     constexpr int SET = decltype(setc)::value;
     const int sw = ((kk_next * 2 + hf) ^ key) << 4;
     const int nxt = cur ^ 1;
@@ -290,10 +304,9 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
     for (int idx = 0; idx < FM * FN; ++idx) {
       const int i = idx / FN, j = idx % FN;
       if constexpr (AREG) {
-        // cur == the K-step within the stage (KS == 2); both candidates are registers, the select is static
-        // after unrolling because every call site passes a constant
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur == 0 ? ra[SET][i][0] : ra[SET][i][KS - 1], fb[cur][j],
-                                                            acc[i][j], 0, 0, 0);
+        // every call site passes a constant kk (the K loop over a stage is fully unrolled), so the register
+        // set is addressed statically
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ra[SET][i][kk], fb[cur][j], acc[i][j], 0, 0, 0);
       } else {
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0);
       }
@@ -318,14 +331,20 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
     }
     __builtin_amdgcn_sched_barrier(0);
   };
-  static_assert(!AREG || KS == 2, "A in registers: two K-steps per stage");
 
+  // Prologue.  Without AREG: stages 0 .. NS-2 in full.  With AREG: stages 0 .. NS-3 in full and part 0 of stage
+  // NS-2; its other parts go out with the K-steps of stage 0, like those of every later stage.  (If the prologue
+  // loaded them too, stage 0 would load the same registers again, the compiler would drop the prologue's loads
+  // as dead, and the count below would no longer be the number of loads in flight.)  The wait counts loads,
+  // so nothing may move across it: scheduling barriers on both sides.
+  constexpr int P0 = (LPS + KS - 1) / KS + (AREG ? FM : 0);   // loads of part 0 of a stage
   {
     auto pro = [&](auto setc) {
       constexpr int ST = decltype(setc)::value;
       if (ST < NS - 1 && (AREG || ST < nk)) {   // AREG: nk is a multiple of four
 #pragma unroll
-        for (int part = 0; part < KS; ++part) issue_part(setc, ST, ST, part);
+        for (int part = 0; part < KS; ++part)
+          if (!AREG || ST < NS - 2 || part == 0) issue_part(setc, ST, ST, part);
       }
     };
     pro(std::integral_constant<int, 0>{});
@@ -335,8 +354,14 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
     if constexpr (NS - 1 > 3) pro(std::integral_constant<int, 3>{});
     if constexpr (NS - 1 > 4) pro(std::integral_constant<int, 4>{});
   }
-  if (nk >= NS - 1) wait_vmcnt<(NS - 2) * LPSW>();
-  else wait_vmcnt<0>();
+  __builtin_amdgcn_sched_barrier(0);
+  if constexpr (AREG) {
+    wait_vmcnt<(NS - 3) * LPSW + P0>();   // stage 0 has landed: only the later stages' loads are outstanding
+  } else {
+    if (nk >= NS - 1) wait_vmcnt<(NS - 2) * LPSW>();
+    else wait_vmcnt<0>();
+  }
+  __builtin_amdgcn_sched_barrier(0);
   lds_barrier();
   // Drain scalar loads here, so that only in-order LDS reads are pending when the loop is entered
   // and the compiler can wait for "all but the newest reads" instead of lgkmcnt(0) at its head.
@@ -348,10 +373,11 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
     constexpr int SET = decltype(setc)::value;
     const unsigned char* base = smem + (kt % NS) * STAGE_BYTES;
     // parts 1 .. KS-1 of stage kt+NS-2 (its part 0 went out with the last K-step of iteration kt-1)
-    const int dma_a = (kt >= 1 && kt + NS - 2 < nk) ? kt + NS - 2 : -1;
+    // (without AREG the prologue has issued all of stage NS-2 already)
+    const int dma_a = ((AREG || kt >= 1) && kt + NS - 2 < nk) ? kt + NS - 2 : -1;
 #pragma unroll
     for (int kk = 0; kk < KS - 1; ++kk)
-      step(setc, std::integral_constant<int, (SET + NS - 2) % 4>{}, kk & 1, base, kk + 1, dma_a, kt + NS - 2, kk + 1);
+      step(setc, std::integral_constant<int, (SET + NS - 2) % 4>{}, kk, base, kk + 1, dma_a, kt + NS - 2, kk + 1);
     if (kt + 1 < nk) {
       // stage kt+1 has landed once at most the loads of the NS-3 younger stages are outstanding
       if (kt + NS - 2 < nk) wait_vmcnt<(NS - 3) * LPSW>();
@@ -363,7 +389,7 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
     // fetch stale but valid LDS that nobody uses): a branch around them would make the compiler's
     // LDS wait counts conservative at the join.  The buffer of stage kt-1 is free from here on:
     // start refilling it with stage kt+NS-1.
-    step(setc, std::integral_constant<int, (SET + NS - 1) % 4>{}, (KS - 1) & 1, smem + ((kt + 1) % NS) * STAGE_BYTES, 0,
+    step(setc, std::integral_constant<int, (SET + NS - 1) % 4>{}, KS - 1, smem + ((kt + 1) % NS) * STAGE_BYTES, 0,
          (kt + NS - 1 < nk) ? kt + NS - 1 : -1, kt + NS - 1, 0);
   };
   if constexpr (AREG) {
@@ -530,6 +556,104 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
         }
       }
     }
+  } else if constexpr (EPI == EPI_QKV16) {
+    const QkvEpilogue& e = a.qkv;
+    const int half = e.Dh / 2, gpq = half / 16;
+    const bool vec4 = (e.Tq % 4 == 0) && (e.pos0 % 4 == 0) && (e.Tpad % 4 == 0) && (!e.seq_gb || e.pos_per_gb % 4 == 0);
+    const int up = (lj >> 4) & 1;   // 0: this lane's column is a first-half feature, 1: its rotation partner
+    const int lr = lj & 3;
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+      const int Gq = tile_n * (BN / 32) + wn * FN + j;
+      const int hg = Gq / gpq, gi = Gq % gpq;
+      const int mat = hg / e.H, head = hg % e.H;
+      if (mat > 2) continue;                        // uniform over the wavefront
+      const int dim1 = gi * 16 + (lj & 15);         // first-half feature of this lane's pair
+      const int dim = dim1 + up * half;             // this lane's own feature
+#pragma unroll
+      for (int i = 0; i < FM; ++i) {
+        if (mat == 2) {
+          // V^T store, as in EPI_QKV
+          unsigned short* vt = reinterpret_cast<unsigned short*>(e.vtstore);
+#pragma unroll
+          for (int rq = 0; rq < 4; ++rq) {
+            const int row0 = row_base + i * 32 + rq * 8 + hf * 4;
+            if (vec4 && row0 + 3 < a.M) {
+              const int b = row0 / e.Tq, pos = e.pos0 + seq_pos_offset(e.seq_gb, e.pos_per_gb, b) + row0 % e.Tq;
+              const size_t o = ((size_t)(b * e.H + head) * e.Dh + dim) * e.Tpad + pos;
+              uint2 v4;
+              v4.x = pack_bf16(acc[i][j][rq * 4 + 0], acc[i][j][rq * 4 + 1]);
+              v4.y = pack_bf16(acc[i][j][rq * 4 + 2], acc[i][j][rq * 4 + 3]);
+              *reinterpret_cast<uint2*>(vt + o) = v4;
+            } else {
+#pragma unroll
+              for (int rr = 0; rr < 4; ++rr) {
+                const int row = row0 + rr;
+                if (row >= a.M) continue;
+                const int b = row / e.Tq, pos = e.pos0 + seq_pos_offset(e.seq_gb, e.pos_per_gb, b) + row % e.Tq;
+                vt[((size_t)(b * e.H + head) * e.Dh + dim) * e.Tpad + pos] = f2bf(acc[i][j][rq * 4 + rr]);
+              }
+            }
+          }
+        } else {
+          unsigned short* dst = reinterpret_cast<unsigned short*>(mat == 0 ? e.q : e.kstore);
+          float cs[16], sn[16];   // all table reads before the first store (see EPI_QKV)
+#pragma unroll
+          for (int rq = 0; rq < 4; ++rq) {
+            const int row0 = row_base + i * 32 + rq * 8 + hf * 4;
+            int t = row0 % e.Tq, bq = row0 / e.Tq;
+            int off = (e.seq_gb && row0 < a.M) ? e.seq_gb[bq] * e.pos_per_gb : 0;
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+              const int r = rq * 4 + rr;
+              const bool live = row0 + rr < a.M;
+              const unsigned ti = (unsigned)(e.pos0 + off + t) * (unsigned)half + (unsigned)dim1;
+              cs[r] = live ? e.cos_t[ti] : 0.f;
+              sn[r] = live ? e.sin_t[ti] : 0.f;
+              if (++t == e.Tq) {
+                t = 0;
+                ++bq;
+                off = (e.seq_gb && row0 + rr + 1 < a.M) ? e.seq_gb[bq] * e.pos_per_gb : 0;
+              }
+            }
+          }
+          // The pair's other member sits 16 lanes away in the same register.  The same two explicitly rounded
+          // operations per output as EPI_QKV: x1 cos - x2 sin for the first half, x2 cos + x1 sin for its partner.
+          float o[16];
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const float x = acc[i][j][r];
+            const float xp = __shfl_xor(x, 16, 64);
+            const float ps = __fmul_rn(xp, sn[r]);
+            o[r] = __fmaf_rn(x, cs[r], up ? ps : -ps);
+          }
+          const int c4 = gi * 16 + (lj & 12) + up * half;   // after the transpose: first of this lane's four features
+#pragma unroll
+          for (int rq = 0; rq < 4; rq += 2) {   // two row groups share one transpose: low / high half words
+            unsigned w[4];
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) w[rr] = pack_bf16(o[rq * 4 + rr], o[rq * 4 + 4 + rr]);
+            quad_transpose(w, lane);
+#pragma unroll
+            for (int h2 = 0; h2 < 2; ++h2) {
+              const int row = row_base + i * 32 + (rq + h2) * 8 + hf * 4 + lr;
+              if (row >= a.M) continue;
+              size_t oo;
+              if (mat == 0) {
+                oo = (size_t)row * e.d + head * e.Dh + c4;
+              } else {
+                const int b = row / e.Tq, pos = e.pos0 + seq_pos_offset(e.seq_gb, e.pos_per_gb, b) + row % e.Tq;
+                oo = ((size_t)b * e.Tpad + pos) * e.d + head * e.Dh + c4;
+              }
+              uint2 st;
+              st.x = h2 ? (w[0] >> 16) | (w[1] & 0xffff0000u) : (w[0] & 0xffffu) | (w[1] << 16);
+              st.y = h2 ? (w[2] >> 16) | (w[3] & 0xffff0000u) : (w[2] & 0xffffu) | (w[3] << 16);
+              *reinterpret_cast<uint2*>(dst + oo) = st;
+            }
+          }
+        }
+      }
+    }
   } else {  // EPI_LMHEAD
     const LmHeadEpilogue& e = a.lm;
     float* s_m = reinterpret_cast<float*>(smem);            // [WN][BM]   (tile buffers are dead now)
@@ -629,6 +753,7 @@ static double tile_cost(int M, int N, int bm, int bn, double rate) {
   const double rounds = (double)(((long long)tiles + 255) / 256);
   return rounds * bm * bn / rate;
 }
+constexpr double kRate256x96 = 1.20;   // 256 x 96, A in registers (Q/K/V only)
 static int pick_tile(int M, int N) {   // 0: 128x128, 1: 256x128, 2: 256x256, 3: 256x192, 4: 128x192
   if (M <= 128) return 0;
   const double c[5] = {tile_cost(M, N, 128, 128, 0.80), tile_cost(M, N, 256, 128, 0.95),
@@ -640,14 +765,28 @@ static int pick_tile(int M, int N) {   // 0: 128x128, 1: 256x128, 2: 256x256, 3:
   return best;
 }
 
-// The A-in-registers loop is unrolled over its four register sets: K must be a whole number of four
-// 32-wide stages; the widths are those for which the RMSNorm has a kernel that writes the quad-tiled layout.
-// (The layout changes no arithmetic: a row's results are the same bits on either path.)
-// Only the 256 x 192 tile takes it: there a wavefront feeds two A fragments to every K-step (gate/up at 512
-// rows: 101 -> 92 us); with the single A fragment of the 128 x 192 tile, LDS traffic is nearly all B's and the
-// register path gains nothing (Q/K/V at 512 rows: 77.3 -> 78.7 us).
-bool gemm_a_quad_tiled(int M, int N, int K) {
-  return pick_tile(M, N) == 3 && K % 128 == 0 && K >= 2048 && K <= 8192;
+// The A-in-registers loop is unrolled over its four register sets: K must be a whole number of four stages
+// (32 wide in the 256 x 192 tile, 64 wide in the 256 x 96 one); the widths are those for which the RMSNorm has
+// a kernel that writes the quad-tiled layout.  (The layout changes no arithmetic: a row's results are the same
+// bits on either path.)  Only tiles whose wavefronts feed two A fragments to every K-step take it: gate/up at
+// 512 rows 101 -> 90 us; with the single A fragment of the 128 x 192 tile, LDS traffic is nearly all B's and
+// the register path gains nothing (Q/K/V at 512 rows: 77.3 -> 78.7 us).
+static bool quad_tiled_widths(int K, int stage) { return K % (4 * stage) == 0 && K >= 2048 && K <= 8192; }
+bool gemm_swiglu_a_quad_tiled(int M, int F, int K) { return pick_tile(M, 2 * F) == 3 && quad_tiled_widths(K, 32); }
+
+// Q/K/V: besides the tiles of pick_tile, 256 x 96 with A in registers (EPI_QKV16): 512 rows x 12288 columns
+// are 256 such tiles, one per CU, where 256 x 192 would occupy half the chip and 128 x 192 (one A fragment
+// per wavefront) is bound by its LDS traffic.  Index 5.
+static int pick_tile_qkv(int M, int N, int K, int Dh) {
+  const int t = pick_tile(M, N);
+  if (M <= 128 || !quad_tiled_widths(K, 64) || Dh % 32 != 0) return t;
+  static const int bm[5] = {128, 256, 256, 256, 128}, bn[5] = {128, 128, 256, 192, 192};
+  static const double rate[5] = {0.80, 0.95, 1.25, 1.15, 0.90};
+  return tile_cost(M, N, 256, 96, kRate256x96) < tile_cost(M, N, bm[t], bn[t], rate[t]) ? 5 : t;
+}
+bool gemm_qkv_a_quad_tiled(int M, int d, int K, int Dh) {
+  const int t = pick_tile_qkv(M, 3 * d, K, Dh);
+  return t == 5 || (t == 3 && quad_tiled_widths(K, 32));
 }
 
 void launch_gemm_qkv_bf16(const bf16* A, const bf16* wq, const bf16* wk, const bf16* wv, int M, int K,
@@ -655,10 +794,11 @@ void launch_gemm_qkv_bf16(const bf16* A, const bf16* wq, const bf16* wk, const b
   GemmArgs a = {};
   a.A = A; a.B0 = wq; a.B1 = wk; a.B2 = wv;
   a.M = M; a.N = 3 * e.d; a.K = K; a.splits = 1; a.gate = g; a.qkv = e;
-  switch (pick_tile(M, a.N)) {
+  switch (pick_tile_qkv(M, a.N, K, e.Dh)) {
+    case 5: launch<256, 96, 64, 4, 1, 4, EPI_QKV16, true>(a, s); break;
     case 4: launch<128, 192, 32, 4, 1, 4, EPI_QKV>(a, s); break;
     case 3:
-      if (gemm_a_quad_tiled(M, a.N, K)) launch<256, 192, 32, 4, 1, 4, EPI_QKV, true>(a, s);
+      if (quad_tiled_widths(K, 32)) launch<256, 192, 32, 4, 1, 4, EPI_QKV, true>(a, s);
       else launch<256, 192, 32, 4, 1, 4, EPI_QKV>(a, s);
       break;
     case 2: launch<256, 256, 32, 4, 2, 4, EPI_QKV>(a, s); break;
@@ -733,7 +873,7 @@ void launch_gemm_swiglu_bf16(const bf16* A, const bf16* wg, const bf16* wu, bf16
   switch (pick_tile(M, a.N)) {
     case 4: launch<128, 192, 32, 4, 1, 4, EPI_SWIGLU>(a, s); break;
     case 3:
-      if (gemm_a_quad_tiled(M, a.N, K)) launch<256, 192, 32, 4, 1, 4, EPI_SWIGLU, true>(a, s);
+      if (quad_tiled_widths(K, 32)) launch<256, 192, 32, 4, 1, 4, EPI_SWIGLU, true>(a, s);
       else launch<256, 192, 32, 4, 1, 4, EPI_SWIGLU>(a, s);
       break;
     case 2: launch<256, 256, 32, 4, 2, 4, EPI_SWIGLU>(a, s); break;

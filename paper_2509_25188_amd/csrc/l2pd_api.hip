@@ -266,8 +266,8 @@ void run_layers(l2pd_ctx* c, const Pass& p, Gate g, hipStream_t s) {
       float* parts = c->at<float>(L.parts);
       const bool skinny = rows <= kSkinnyRows;
       // the activations go to the fused GEMMs in the layout these ask for (row-major or quad-tiled)
-      const bool tiled_qkv = !skinny && gemm_a_quad_tiled(rows, 3 * d, d);
-      const bool tiled_ffn = !skinny && gemm_a_quad_tiled(rows, 2 * F, d);
+      const bool tiled_qkv = !skinny && gemm_qkv_a_quad_tiled(rows, d, d, Dh);
+      const bool tiled_ffn = !skinny && gemm_swiglu_a_quad_tiled(rows, F, d);
       { Timed t(c, L2PD_K_NORM, s);
         launch_rmsnorm(h, pending ? parts : nullptr, pend_splits, pend_stride, ident, c->attn_g[l], m.dtype, xn, rows,
                        d, m.rms_eps, true, g, s, tiled_qkv); }
