@@ -35,7 +35,7 @@ __global__ void __launch_bounds__(NQ * NSPL * 64) k_attn_bf16(const bf16* __rest
                                                               const bf16* __restrict__ vtstore, bf16* __restrict__ out,
                                                               int B, int Tq, int Tk_all, int Tpad, int H, int n_chunks,
                                                               float* __restrict__ chunk_out,
-                                                              const int* __restrict__ tk_dev, Gate g) {
+                                                              const int* __restrict__ tk_dev, int out_quad_tiled, Gate g) {
   if (gate_skip(g)) return;
   constexpr int NW = NQ * NSPL;
   constexpr int NT = NW * 64;
@@ -271,7 +271,11 @@ __global__ void __launch_bounds__(NQ * NSPL * 64) k_attn_bf16(const bf16* __rest
   }
   const float inv = 1.f / l;
   if (q0 + lj < Tq) {
-    unsigned short* op = reinterpret_cast<unsigned short*>(out) + ((size_t)b * Tq + q0 + lj) * d + h * DH;
+    // row-major [rows, d], or the quad-tiled layout the output projection reads into registers
+    // (gemm_qkv_a_quad_tiled in common.h describes it): four features are half a 16-byte chunk either way
+    const size_t row = (size_t)b * Tq + q0 + lj;
+    unsigned short* op = reinterpret_cast<unsigned short*>(out) +
+                         (out_quad_tiled ? ((row >> 2) * (d / 8) + h * (DH / 8)) * 32 + (row & 3) * 8 : row * d + h * DH);
 #pragma unroll
     for (int f = 0; f < FO; ++f)
 #pragma unroll
@@ -279,7 +283,8 @@ __global__ void __launch_bounds__(NQ * NSPL * 64) k_attn_bf16(const bf16* __rest
         u32x2 w;
         w.x = pack_bf16x2(o[f][rq * 4 + 0] * inv, o[f][rq * 4 + 1] * inv);
         w.y = pack_bf16x2(o[f][rq * 4 + 2] * inv, o[f][rq * 4 + 3] * inv);
-        *reinterpret_cast<u32x2*>(op + f * 32 + rq * 8 + hf * 4) = w;
+        const int col = f * 32 + rq * 8 + hf * 4;   // feature within the head
+        *reinterpret_cast<u32x2*>(op + (out_quad_tiled ? (col >> 3) * 32 + (col & 7) : col)) = w;
       }
   }
 }
@@ -314,7 +319,8 @@ __global__ void __launch_bounds__(256) k_attn_merge(const float* __restrict__ ch
 
 template <int DH, int NQ, int NSPL, int NST>
 static void launch(const bf16* q, const bf16* kstore, const bf16* vtstore, bf16* out, int B, int Tq, int Tk,
-                   int Tpad, int H, float* chunk_ws, size_t chunk_ws_bytes, const int* tk_dev, Gate g, hipStream_t s) {
+                   int Tpad, int H, float* chunk_ws, size_t chunk_ws_bytes, const int* tk_dev, Gate g, hipStream_t s,
+                   bool out_quad_tiled) {
   auto kern = k_attn_bf16<DH, NQ, NSPL, NST>;
   constexpr int tiles = NST * NSPL * (64 * DH * 2 + DH * 64 * 2);
   constexpr int xchg = (NSPL - 1) * NQ * ((DH / 32) * 16 + 2) * 64 * 4;
@@ -324,7 +330,7 @@ static void launch(const bf16* q, const bf16* kstore, const bf16* vtstore, bf16*
   const int q_tiles = (Tq + 32 * NQ - 1) / (32 * NQ), n_tiles = (Tk + 63) / 64;
   // few queries against many keys: deal the key tiles to several workgroups per query tile
   int n_chunks = 1;
-  if (chunk_ws && !tk_dev && q_tiles * H * B < 128 && n_tiles >= 2 * NSPL) {   // chunks must not be empty: launch-wide key count only
+  if (chunk_ws && !tk_dev && !out_quad_tiled && q_tiles * H * B < 128 && n_tiles >= 2 * NSPL) {   // chunks must not be empty: launch-wide key count only; the merge writes row-major
     int want = (256 + q_tiles * H * B - 1) / (q_tiles * H * B);
     if (want > 16) want = 16;
     if (want > n_tiles / NSPL) want = n_tiles / NSPL;   // a tile for every key range of a chunk
@@ -334,7 +340,7 @@ static void launch(const bf16* q, const bf16* kstore, const bf16* vtstore, bf16*
   }
   dim3 grid(q_tiles * n_chunks * H * B);
   hipLaunchKernelGGL(kern, grid, dim3(NQ * NSPL * 64), smem, s, q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, n_chunks,
-                     chunk_ws, tk_dev, g);
+                     chunk_ws, tk_dev, out_quad_tiled ? 1 : 0, g);
   if (n_chunks > 1) {
     const int n = B * H * Tq * (DH / 4);
     hipLaunchKernelGGL(k_attn_merge<DH>, dim3((n + 255) / 256), dim3(256), 0, s, chunk_ws, out, B, Tq, H, n_chunks, g);
@@ -350,7 +356,7 @@ static void launch(const bf16* q, const bf16* kstore, const bf16* vtstore, bf16*
 // chunking across workgroups on the shape of the launch, never on the data.
 void launch_attn_bf16(const bf16* q, const bf16* kstore, const bf16* vtstore, bf16* out, int B, int Tq, int Tk,
                       int Tpad, int H, int Dh, float* chunk_ws, size_t chunk_ws_bytes, const int* tk_dev, Gate g,
-                      hipStream_t s) {
+                      hipStream_t s, bool out_quad_tiled) {
   // A sequence long enough to give every CU a workgroup of 128 queries by itself: the key tiles
   // then serve four query groups instead of two (half the L2 -> LDS traffic per flop) and two
   // workgroups of 64 KB fit a CU.  Measured at 32 heads of 128, one sequence (us): 1024 tokens
@@ -358,12 +364,12 @@ void launch_attn_bf16(const bf16* q, const bf16* kstore, const bf16* vtstore, bf
   // criterion on purpose: the two configurations merge key ranges in different orders, and a row's
   // result must not depend on the batch it is part of.
   if ((long long)((Tq + 127) / 128) * H >= 256) {
-    if (Dh == 128) launch<128, 4, 2, 1>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, chunk_ws, chunk_ws_bytes, tk_dev, g, s);
-    else launch<64, 4, 2, 1>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, chunk_ws, chunk_ws_bytes, tk_dev, g, s);
+    if (Dh == 128) launch<128, 4, 2, 1>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, chunk_ws, chunk_ws_bytes, tk_dev, g, s, out_quad_tiled);
+    else launch<64, 4, 2, 1>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, chunk_ws, chunk_ws_bytes, tk_dev, g, s, out_quad_tiled);
     return;
   }
-  if (Dh == 128) launch<128, 2, 4, 1>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, chunk_ws, chunk_ws_bytes, tk_dev, g, s);
-  else launch<64, 2, 4, 1>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, chunk_ws, chunk_ws_bytes, tk_dev, g, s);
+  if (Dh == 128) launch<128, 2, 4, 1>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, chunk_ws, chunk_ws_bytes, tk_dev, g, s, out_quad_tiled);
+  else launch<64, 2, 4, 1>(q, kstore, vtstore, out, B, Tq, Tk, Tpad, H, chunk_ws, chunk_ws_bytes, tk_dev, g, s, out_quad_tiled);
 }
 
 }  // namespace l2pd

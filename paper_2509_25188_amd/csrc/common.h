@@ -174,6 +174,9 @@ __device__ __forceinline__ int seq_pos_offset(const int* seq_gb, int per_gb, int
 // A (the RMSNorm before the GEMM) asks the same question.
 bool gemm_qkv_a_quad_tiled(int M, int d, int K, int Dh);
 bool gemm_swiglu_a_quad_tiled(int M, int F, int K);
+// the same question for the [N, K] projections that write split-K partials (output and down projection), whose
+// A operands are written by the attention kernel and by the gate/up GEMM's epilogue
+bool gemm_partial_a_quad_tiled(int M, int N, int K);
 void launch_gemm_qkv_bf16(const bf16* A, const bf16* wq, const bf16* wk, const bf16* wv, int M, int K,
                           const QkvEpilogue& e, Gate g, hipStream_t s);
 // partial[z][M,N] = A[:, z-th K slice] * W[:, slice]^T, z < splits (1 or 2)
@@ -196,7 +199,7 @@ void launch_skinny_swiglu_finish(const float* parts, int n_parts, size_t part_st
 // act[M, F] = silu(A Wg^T) * (A Wu^T); few rows take the fused few-row tiles when swiglu_few_rows_fused says so
 bool swiglu_few_rows_fused(int M, int F);
 void launch_gemm_swiglu_bf16(const bf16* A, const bf16* wg, const bf16* wu, bf16* act, int M, int F, int K, Gate g,
-                             hipStream_t s);
+                             hipStream_t s, bool act_quad_tiled = false);
 struct LmHeadEpilogue {
   float* logits;         // optional [M, V]
   float* part_max;       // optional [M, n_part]
@@ -209,9 +212,10 @@ struct LmHeadEpilogue {
 int lmhead_n_part(int V);
 void launch_gemm_lmhead_bf16(const bf16* A, const bf16* W, int M, int V, int K, const LmHeadEpilogue& e, Gate g,
                              hipStream_t s);
+// out_quad_tiled: write `out` in the layout gemm_partial_a_quad_tiled() asks for instead of row-major
 void launch_attn_bf16(const bf16* q, const bf16* kstore, const bf16* vtstore, bf16* out, int B, int Tq, int Tk,
                       int Tpad, int H, int Dh, float* chunk_ws, size_t chunk_ws_bytes, const int* tk_dev, Gate g,
-                      hipStream_t s);
+                      hipStream_t s, bool out_quad_tiled = false);
 // bytes of chunk workspace that lets launch_attn_bf16 spread few queries' keys over workgroups
 inline size_t attn_chunk_ws_bytes(int H, int Dh) { return (size_t)kSkinnyRowsAttn * H * 16 * (Dh + 2) * 4; }
 

@@ -49,6 +49,7 @@ struct GemmArgs {
   // EPI_SWIGLU
   bf16* act;
   int F;
+  int act_quad_tiled;   // act in the quad-tiled layout (read into registers by the down projection) instead of row-major
   // EPI_QKV
   QkvEpilogue qkv;
   // EPI_LMHEAD
@@ -448,8 +449,12 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
             uint2 o;
             o.x = h2 ? (w[0] >> 16) | (w[1] & 0xffff0000u) : (w[0] & 0xffffu) | (w[1] << 16);
             o.y = h2 ? (w[2] >> 16) | (w[3] & 0xffff0000u) : (w[2] & 0xffffu) | (w[3] << 16);
-            if (row < a.M && col < a.F)   // F is a multiple of 4, so a group of 4 columns is in or out as a whole
-              *reinterpret_cast<uint2*>(reinterpret_cast<unsigned short*>(a.act) + (size_t)row * a.F + col) = o;
+            if (row < a.M && col < a.F) {   // F is a multiple of 4, so a group of 4 columns is in or out as a whole
+              const size_t at = a.act_quad_tiled
+                                    ? ((size_t)(row >> 2) * (a.F / 8) + (col >> 3)) * 32 + (row & 3) * 8 + (col & 7)
+                                    : (size_t)row * a.F + col;
+              *reinterpret_cast<uint2*>(reinterpret_cast<unsigned short*>(a.act) + at) = o;
+            }
           }
         }
       }
@@ -772,7 +777,7 @@ static int pick_tile(int M, int N) {   // 0: 128x128, 1: 256x128, 2: 256x256, 3:
 // 512 rows 101 -> 90 us; with the single A fragment of the 128 x 192 tile, LDS traffic is nearly all B's and
 // the register path gains nothing (Q/K/V at 512 rows: 77.3 -> 78.7 us).
 static bool quad_tiled_widths(int K, int stage) { return K % (4 * stage) == 0 && K >= 2048 && K <= 8192; }
-bool gemm_swiglu_a_quad_tiled(int M, int F, int K) { return pick_tile(M, 2 * F) == 3 && quad_tiled_widths(K, 32); }
+bool gemm_swiglu_a_quad_tiled(int M, int F, int K) { return pick_tile(M, 2 * F) == 3 && quad_tiled_widths(K, 64); }
 
 // Q/K/V: besides the tiles of pick_tile, 256 x 96 with A in registers (EPI_QKV16): 512 rows x 12288 columns
 // are 256 such tiles, one per CU, where 256 x 192 would occupy half the chip and 128 x 192 (one A fragment
@@ -813,6 +818,7 @@ void launch_gemm_partial_bf16(const bf16* A, const bf16* W, float* parts, size_t
   a.A = A; a.B0 = W; a.M = M; a.N = N; a.K = K; a.splits = splits; a.gate = g;
   a.parts = parts; a.part_stride = part_stride;
   if (splits == 1 && pick_tile(M, N) == 2) launch<256, 256, 32, 4, 2, 4, EPI_PARTIAL>(a, s);
+  else if (splits == 4 && gemm_partial_a_quad_tiled(M, N, K)) launch<256, 128, 64, 4, 1, 4, EPI_PARTIAL, true>(a, s);
   else launch<128, 128, 64, 2, 2, 4, EPI_PARTIAL>(a, s);
 }
 
@@ -824,7 +830,15 @@ void launch_gemm_partial_bf16(const bf16* A, const bf16* W, float* parts, size_t
 // sequence and of a batch then give the same bits row by row).  Up to 256 rows (batched block-only steps
 // of the cached modes, bound by the weight stream) the split goes up to eight ways, until the launch
 // has about 256 workgroups: 256 rows of the 8B shape split 4 ways, 128 rows 8 ways.
+// Above 256 rows: 256 x 128 tiles with A in registers and K split four ways when the widths allow (512 rows of
+// the 8B shape: 2 x 32 tiles x 4 = one workgroup per CU).  The tile has half the LDS traffic per MFMA of the
+// 128 x 128 one (only B is staged, and a wavefront reuses each B fragment for two A fragments), which pays for
+// the two extra partials: projection 45 -> 39 us, the RMSNorm that folds them 9.3 -> 11.8 us.
+bool gemm_partial_a_quad_tiled(int M, int N, int K) {
+  return M > 256 && N % 128 == 0 && K % 1024 == 0 && K / 4 >= 512 && N % 8 == 0;
+}
 int wide_splits(int M, int N, int K) {
+  if (M > 256 && gemm_partial_a_quad_tiled(M, N, K)) return 4;
   if (M > 256) return (K % 128 == 0 && K / 2 >= 512) ? 2 : 1;
   const int tiles = ((M + 127) / 128) * ((N + 127) / 128);
   int S = 1;
@@ -861,10 +875,10 @@ void launch_gemm_skinny_bf16(const bf16* A, const bf16* w0, const bf16* w1, cons
 bool swiglu_few_rows_fused(int M, int F) { return M <= kSkinnyRows && F % 64 == 0 && 2 * F / 64 >= 256; }
 
 void launch_gemm_swiglu_bf16(const bf16* A, const bf16* wg, const bf16* wu, bf16* act, int M, int F, int K, Gate g,
-                             hipStream_t s) {
+                             hipStream_t s, bool act_quad_tiled) {
   GemmArgs a = {};
   a.A = A; a.B0 = wg; a.B1 = wu; a.M = M; a.N = 2 * F; a.K = K; a.splits = 1; a.gate = g;
-  a.act = act; a.F = F;
+  a.act = act; a.F = F; a.act_quad_tiled = (act_quad_tiled && F % 8 == 0) ? 1 : 0;
   if (swiglu_few_rows_fused(M, F)) {
     if (M <= 32) launch<32, 64, 64, 1, 1, 6, EPI_SWIGLU>(a, s);   // one wavefront per workgroup, 72 KB ring
     else launch<64, 128, 64, 2, 2, 4, EPI_SWIGLU>(a, s);
@@ -873,7 +887,7 @@ void launch_gemm_swiglu_bf16(const bf16* A, const bf16* wg, const bf16* wu, bf16
   switch (pick_tile(M, a.N)) {
     case 4: launch<128, 192, 32, 4, 1, 4, EPI_SWIGLU>(a, s); break;
     case 3:
-      if (quad_tiled_widths(K, 32)) launch<256, 192, 32, 4, 1, 4, EPI_SWIGLU, true>(a, s);
+      if (quad_tiled_widths(K, 64)) launch<256, 192, 64, 4, 1, 4, EPI_SWIGLU, true>(a, s);
       else launch<256, 192, 32, 4, 1, 4, EPI_SWIGLU>(a, s);
       break;
     case 2: launch<256, 256, 32, 4, 2, 4, EPI_SWIGLU>(a, s); break;

@@ -111,8 +111,8 @@ Layout make_layout(const l2pd_model_desc& m, int max_batch, int max_seq, int cac
   L.h = c.take(rows * d * 4);
   L.xn = c.take(align_up(rows, 4) * d * es);   // the quad-tiled layout holds whole groups of four rows
   L.q = c.take(rows * d * es);
-  L.attn = c.take(rows * d * es);
-  L.act = c.take(rows * F * es);
+  L.attn = c.take(align_up(rows, 4) * d * es);
+  L.act = c.take(align_up(rows, 4) * F * es);
   const size_t kv_one = (size_t)max_batch * L.Tpad * d * es;
   const size_t n_kv = cache ? m.n_layers : 1;
   L.kv_layer_stride_k = kv_one;
@@ -268,6 +268,8 @@ void run_layers(l2pd_ctx* c, const Pass& p, Gate g, hipStream_t s) {
       // the activations go to the fused GEMMs in the layout these ask for (row-major or quad-tiled)
       const bool tiled_qkv = !skinny && gemm_qkv_a_quad_tiled(rows, d, d, Dh);
       const bool tiled_ffn = !skinny && gemm_swiglu_a_quad_tiled(rows, F, d);
+      const bool tiled_o = !skinny && gemm_partial_a_quad_tiled(rows, d, d);      // attention output -> output projection
+      const bool tiled_down = !skinny && gemm_partial_a_quad_tiled(rows, d, F);   // SwiGLU activations -> down projection
       { Timed t(c, L2PD_K_NORM, s);
         launch_rmsnorm(h, pending ? parts : nullptr, pend_splits, pend_stride, ident, c->attn_g[l], m.dtype, xn, rows,
                        d, m.rms_eps, true, g, s, tiled_qkv); }
@@ -288,7 +290,7 @@ void run_layers(l2pd_ctx* c, const Pass& p, Gate g, hipStream_t s) {
       bf16* ao = c->at<bf16>(L.attn);
       { Timed t(c, L2PD_K_ATTN, s);
         launch_attn_bf16(q, ks, vts, ao, p.B, p.Tq, p.Tk, L.Tpad, H, Dh, c->at<float>(L.attn_ws), L.attn_ws_bytes,
-                         p.tk_dev, g, s); }
+                         p.tk_dev, g, s, tiled_o); }
       // Few row tiles leave CUs idle on the [d, d] and [d, F] projections: split K as far as
       // wide_splits (wide path) or skinny_splits (few-row path) says.
       const int so = skinny ? skinny_splits(d, d) : wide_splits(rows, d, d);
@@ -312,7 +314,7 @@ void run_layers(l2pd_ctx* c, const Pass& p, Gate g, hipStream_t s) {
                                   2 * F, d, S, g, s);
           launch_skinny_swiglu_finish(parts, S, stride, rows, F, act, g, s);
         } else {
-          launch_gemm_swiglu_bf16(xn, (const bf16*)c->wg[l], (const bf16*)c->wu[l], act, rows, F, d, g, s);
+          launch_gemm_swiglu_bf16(xn, (const bf16*)c->wg[l], (const bf16*)c->wu[l], act, rows, F, d, g, s, tiled_down);
         } }
       { Timed t(c, L2PD_K_GEMM_DOWN, s);
         if (skinny)

@@ -51,6 +51,22 @@ def test_8b_width_two_layers_full_recompute():
     assert rep.max_logit_err < 2e-2
 
 
+def test_8b_width_forward_is_bitwise_reproducible():
+    # The GEMMs count the loads they have in flight by hand (s_waitcnt vmcnt(N)); a count that is off by a few
+    # shows as a forward whose result changes from run to run (a wrong prologue count of the 64-wide
+    # A-in-registers loop did, in one run out of four).  100 forwards of two 8B-width layers, bit for bit.
+    w = synth.with_layers(synth.WORKLOADS["8b_g256"], 2)
+    eng = Bd.engine_for(w, SEED, "cuda", max_batch=1)
+    X = synth.make_prompt(SEED, 1, w.prompt_len + w.gen_len, w.prompt_hi, "cuda")
+    first = eng.forward(X, w.prompt_len, w.block_len).clone()
+    torch.cuda.synchronize()
+    assert torch.isfinite(first).all()
+    for it in range(100):
+        again = eng.forward(X, w.prompt_len, w.block_len)
+        torch.cuda.synchronize()
+        assert torch.equal(again, first), f"forward {it} differs from the first"
+
+
 def test_8b_width_row_count_that_no_tile_divides():
     # 509 rows (a prime): the last 256-row GEMM tile, the last group of 32 rows of the quad-tiled activations and
     # the last group of four are all ragged; one layer, first and last block
