@@ -762,7 +762,7 @@ constexpr double kRate256x96 = 1.20;   // 256 x 96, A in registers (Q/K/V only)
 static int pick_tile(int M, int N) {   // 0: 128x128, 1: 256x128, 2: 256x256, 3: 256x192, 4: 128x192
   if (M <= 128) return 0;
   const double c[5] = {tile_cost(M, N, 128, 128, 0.80), tile_cost(M, N, 256, 128, 0.95),
-                       tile_cost(M, N, 256, 256, 1.25), tile_cost(M, N, 256, 192, 1.15),
+                       tile_cost(M, N, 256, 256, 1.25), tile_cost(M, N, 256, 192, 1.30),
                        tile_cost(M, N, 128, 192, 0.90)};
   int best = 0;
   for (int i = 1; i < 5; ++i)
@@ -786,12 +786,12 @@ static int pick_tile_qkv(int M, int N, int K, int Dh) {
   const int t = pick_tile(M, N);
   if (M <= 128 || !quad_tiled_widths(K, 64) || Dh % 32 != 0) return t;
   static const int bm[5] = {128, 256, 256, 256, 128}, bn[5] = {128, 128, 256, 192, 192};
-  static const double rate[5] = {0.80, 0.95, 1.25, 1.15, 0.90};
+  static const double rate[5] = {0.80, 0.95, 1.25, 1.30, 0.90};
   return tile_cost(M, N, 256, 96, kRate256x96) < tile_cost(M, N, bm[t], bn[t], rate[t]) ? 5 : t;
 }
 bool gemm_qkv_a_quad_tiled(int M, int d, int K, int Dh) {
   const int t = pick_tile_qkv(M, 3 * d, K, Dh);
-  return t == 5 || (t == 3 && quad_tiled_widths(K, 32));
+  return t == 5 || (t == 3 && quad_tiled_widths(K, 64));
 }
 
 void launch_gemm_qkv_bf16(const bf16* A, const bf16* wq, const bf16* wk, const bf16* wv, int M, int K,
@@ -803,7 +803,7 @@ void launch_gemm_qkv_bf16(const bf16* A, const bf16* wq, const bf16* wk, const b
     case 5: launch<256, 96, 64, 4, 1, 4, EPI_QKV16, true>(a, s); break;
     case 4: launch<128, 192, 32, 4, 1, 4, EPI_QKV>(a, s); break;
     case 3:
-      if (quad_tiled_widths(K, 32)) launch<256, 192, 32, 4, 1, 4, EPI_QKV, true>(a, s);
+      if (quad_tiled_widths(K, 64)) launch<256, 192, 64, 4, 1, 4, EPI_QKV, true>(a, s);
       else launch<256, 192, 32, 4, 1, 4, EPI_QKV>(a, s);
       break;
     case 2: launch<256, 256, 32, 4, 2, 4, EPI_QKV>(a, s); break;
