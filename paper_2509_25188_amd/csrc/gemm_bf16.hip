@@ -825,7 +825,8 @@ void launch_gemm_partial_bf16(const bf16* A, const bf16* W, float* parts, size_t
 // Wide path, [d, d] and [d, F] projections: 128 x 128 tiles of these narrow outputs do not fill the
 // chip at a few hundred rows, so K is split, each K range staying a multiple of the 64-wide stage and
 // at least 512 long; the partials are folded by the next RMSNorm in order.  Above 256 rows the depth is
-// a function of K alone (two ways whenever K allows it), never of the row count: a sequence must sum
+// a function of the widths alone (four ways with the A-in-registers tile below, else two ways whenever K
+// allows it), never of the row count: a sequence must sum
 // its projections in the same order whatever batch it is decoded in (full-recompute forwards of one
 // sequence and of a batch then give the same bits row by row).  Up to 256 rows (batched block-only steps
 // of the cached modes, bound by the weight stream) the split goes up to eight ways, until the launch
