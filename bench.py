@@ -48,6 +48,11 @@ def step_flops(w):
     return lin, attn, head
 
 
+def note(msg):
+    """Progress line on stderr (the one JSON line stays alone on stdout)."""
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
 def cpu_baseline(w, tokens_per_step, seed, n_layers_sample=2):
     """Times the oracle as it stands on a bounded sample: `n_layers_sample` of the layers plus
     embedding + LM head + decode rule at full width and full sequence length, one sequence."""
@@ -183,6 +188,7 @@ def cached_workload(args, w, eng, flt, prompt, cfg, f, X0, state0, traj_steps, t
         "roofline": roof,
         "setup_s": setup_s,
         **({"eotp_steps_saved": eotp_on_off(w, eng, prompt, flt, cfg, traj_steps, tokens_total)} if w.eotp else {}),
+        **({"batch_schedules": batch_schedules(w, eng, prompt, flt, cfg)} if args.batch_schedules else {}),
     }
 
 
@@ -235,12 +241,16 @@ def batch_schedules(w, eng, prompt, flt, cfg):
         cfg.ragged = mode
         eng.generate(prompt, flt, cfg)
         torch.cuda.synchronize()
+        note(f"batch schedule {name}: warm-up generation done")
         t0 = time.perf_counter()
         tok, st, dl = eng.generate(prompt, flt, cfg)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         ref = tok if ref is None else ref
+        n_steps, n_seq_steps = eng.generate_stats()
+        note(f"batch schedule {name}: {dt:.1f} s, {n_steps} step launches, {n_seq_steps} sequence-steps")
         out[name] = {"generate_wall_s": dt, "tokens_per_s": int(dl.sum()) / dt,
+                     "step_launches": n_steps, "sequence_steps": n_seq_steps,
                      "steps_per_sequence": st.cpu().tolist(), "tokens_equal_lock_step": bool(torch.equal(tok, ref))}
     cfg.ragged = Bd.RAGGED_OFF
     return out
@@ -258,6 +268,7 @@ def eotp_on_off(w, eng, prompt, flt, cfg, steps_on, tokens_on):
     tok, st, dl = eng.generate(prompt, flt, off)
     torch.cuda.synchronize()
     t_off = time.perf_counter() - t0
+    note(f"EoTP off: {t_off:.1f} s")
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     eng.generate(prompt, flt, cfg)
@@ -356,6 +367,7 @@ def main():
                                w.prefix_cache, bias, w.dual_cache)
     torch.cuda.synchronize()
     setup_s = time.time() - t0
+    note(f"weights and engine ready in {setup_s:.1f} s")
 
     # The real trajectory once (also a warm-up): total steps and tokens of one generation.
     t0 = time.time()
@@ -366,6 +378,7 @@ def main():
     tok, st, dl = eng.generate(prompt, flt, cfg)
     torch.cuda.synchronize()
     gen_wall = time.time() - t0
+    note(f"two generations done ({gen_wall:.1f} s each); timing steps")
     steps_per_seq = st.cpu().tolist()
     traj_steps = max(steps_per_seq)                 # lock-step batch: forwards of one generation
     tokens_total = int(dl.sum().item())
@@ -456,6 +469,7 @@ def main():
         torch.cuda.synchronize()
         result["copy_calibration"] = {"bytes_read_per_launch": n, "bytes_written_per_launch": n, "launches": 4}
     if not args.no_cpu_baseline:
+        note("GPU legs done; timing the CPU oracle on a bounded sample")
         result["cpu_baseline"] = cpu_baseline(w, tokens_per_step, args.seed, n_layers_sample=16)
     print(json.dumps(result))
 

@@ -121,8 +121,8 @@ enum { L2PD_EOTP_OFF = 0, L2PD_EOTP_BLOCK = 1, L2PD_EOTP_STEP = 2 };
  *                       fewer forwards.
  *   L2PD_RAGGED_COMPACT as BLOCKS, and l2pd_generate moves the sequences that are still decoding to the
  *                       leading rows whenever some have finished, so later forwards run over fewer rows
- *                       (l2pd_denoise_step, l2pd_generate with L2PD_EOTP_STEP, and the cached modes treat it
- *                       as BLOCKS).
+ *                       (with a K/V cache their slices of the stores move with them); l2pd_denoise_step and
+ *                       l2pd_generate with L2PD_EOTP_STEP treat it as BLOCKS.
  * With a K/V cache (Sec. 4.3) and per-sequence blocks every sequence's slice of the stores is rebuilt when
  * that sequence enters a new block (a forward over that sequence alone), and a step's block rows sit at
  * per-sequence positions; l2pd_generate then looks at the device state before every step. */
@@ -254,6 +254,12 @@ int32_t l2pd_profile_select(l2pd_ctx* ctx, int32_t kernel_class);
  * since the last select and the sum of their event-pair durations in milliseconds (each includes the gap
  * between the event and the kernel on the stream: an upper bound of the kernel's own time by a few percent). */
 int32_t l2pd_profile_read(l2pd_ctx* ctx, int64_t* launches_out, double* total_ms_out);
+
+/* What the last l2pd_generate on this context enqueued (host-side counters, no synchronisation): the number
+ * of step launches, and the sum over them of the sequences each ran over (batch size x steps in lock step;
+ * less with L2PD_RAGGED_COMPACT once sequences have finished: Sec. 3.3's saving carried over to a batch).
+ * Either pointer may be null. */
+int32_t l2pd_generate_stats(const l2pd_ctx* ctx, int64_t* steps_out, int64_t* sequence_steps_out);
 
 const char* l2pd_strerror(int32_t status);
 

@@ -86,7 +86,7 @@ class TrainCfg(C.Structure):
 
 
 EXPORTS = ("l2pd_workspace_bytes", "l2pd_create", "l2pd_destroy", "l2pd_forward", "l2pd_denoise_step",
-           "l2pd_generate", "l2pd_egp_rollout", "l2pd_filter_train", "l2pd_filter_train_static", "l2pd_profile_select", "l2pd_profile_read", "l2pd_strerror")
+           "l2pd_generate", "l2pd_egp_rollout", "l2pd_filter_train", "l2pd_filter_train_static", "l2pd_profile_select", "l2pd_profile_read", "l2pd_generate_stats", "l2pd_strerror")
 
 
 def load_library() -> C.CDLL:
@@ -118,6 +118,8 @@ def load_library() -> C.CDLL:
     lib.l2pd_profile_select.argtypes = [vp, i32]
     lib.l2pd_profile_read.restype = i32
     lib.l2pd_profile_read.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_double)]
+    lib.l2pd_generate_stats.restype = i32
+    lib.l2pd_generate_stats.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
     lib.l2pd_strerror.restype = C.c_char_p
     lib.l2pd_strerror.argtypes = [i32]
     return lib
@@ -270,6 +272,12 @@ class Engine:
         n, ms = C.c_int64(), C.c_double()
         _check(lib().l2pd_profile_read(self._ctx, C.byref(n), C.byref(ms)), "l2pd_profile_read")
         return n.value, ms.value
+
+    def generate_stats(self):
+        """(step launches, sum over them of the sequences each ran over) of the last generate."""
+        steps, seq_steps = C.c_int64(), C.c_int64()
+        _check(lib().l2pd_generate_stats(self._ctx, C.byref(steps), C.byref(seq_steps)), "l2pd_generate_stats")
+        return steps.value, seq_steps.value
 
 
 def train_filter(flt: Dict[str, torch.Tensor], conf_rows: torch.Tensor, label_rows: torch.Tensor, epochs: int,

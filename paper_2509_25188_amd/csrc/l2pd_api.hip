@@ -58,6 +58,8 @@ struct l2pd_ctx {
   int last_hip_error = 0;
   int pend_splits = 0;   // bf16: split-K partials of the last down projection still to be folded into h
   size_t pend_stride = 0;
+  // the last l2pd_generate: step launches enqueued, and the sum over them of the sequences each ran over
+  int64_t stat_steps = 0, stat_seq_steps = 0;
 
   template <typename T>
   T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
@@ -556,6 +558,13 @@ float* static_scratch(int32_t* st) {
 // =================================================================================================
 extern "C" {
 
+int32_t l2pd_generate_stats(const l2pd_ctx* c, int64_t* steps_out, int64_t* sequence_steps_out) {
+  if (!c) return L2PD_EINVAL;
+  if (steps_out) *steps_out = c->stat_steps;
+  if (sequence_steps_out) *sequence_steps_out = c->stat_seq_steps;
+  return L2PD_OK;
+}
+
 const char* l2pd_strerror(int32_t st) {
   switch (st) {
     case L2PD_OK: return "ok";
@@ -706,6 +715,7 @@ int32_t l2pd_generate(l2pd_ctx* c, const int32_t* prompt_dev, int32_t B, int32_t
   int* ctl = c->at<int>(L.ctl);
   const int sl = cfg->block_len, G = cfg->gen_len, nb = G / sl;
   launch_init_decode(X, prompt_dev, B, P, G, c->m.mask_id, state, ctl, s);
+  c->stat_steps = c->stat_seq_steps = 0;
   const StepTaps no_taps = {nullptr, nullptr, nullptr, nullptr, nullptr};
   // Steps enqueued between two looks at the control block.  The host always looks at the chunk
   // before the one it has just enqueued, so a finished block (or decode) is noticed one to two chunks
@@ -728,8 +738,11 @@ int32_t l2pd_generate(l2pd_ctx* c, const int32_t* prompt_dev, int32_t B, int32_t
     int issued = 0, slot = 0;
     bool have_prev = false;
     while (issued < max_steps) {
-      for (int i = 0; i < CHUNK && issued < max_steps; ++i, ++issued)
+      for (int i = 0; i < CHUNK && issued < max_steps; ++i, ++issued) {
         run_step(c, X, Bc, P, cfg, f, state, host_gb, no_taps, s);
+        ++c->stat_steps;
+        c->stat_seq_steps += Bc;
+      }
       launch_prepare(state, Bc, nb, cfg->ragged, ctl, s);
       if (hipMemcpyAsync(c->pinned + slot * CTL_WORDS, ctl, CTL_WORDS * sizeof(int), hipMemcpyDeviceToHost, s) !=
               hipSuccess ||
@@ -769,6 +782,8 @@ int32_t l2pd_generate(l2pd_ctx* c, const int32_t* prompt_dev, int32_t B, int32_t
       if (t_run < 0) { c->last_hip_error = (int)hipGetLastError(); return L2PD_EHIP; }
       if (all_done) break;
       run_step(c, X, B, P, cfg, f, state, -1, no_taps, s, t_run);
+      ++c->stat_steps;
+      c->stat_seq_steps += B;
     }
     launch_seq_len(X, B, P, G, c->m.eos_id, c->at<int>(L.teff), ctl, s);
   } else if (cfg->kv_cache && cfg->ragged) {
@@ -776,20 +791,57 @@ int32_t l2pd_generate(l2pd_ctx* c, const int32_t* prompt_dev, int32_t B, int32_t
     // step (a sequence that has moved on to a new block needs its slice of the stores rebuilt first, a
     // forward over that sequence alone), then enqueues one step for the batch.  Every live sequence
     // commits at least one position per step, so gen_len iterations suffice.
+    // With L2PD_RAGGED_COMPACT the sequences still decoding are also moved to the leading rows whenever some
+    // have finished (tokens and state by k_compact, as without a cache); their slices of the K/V stores move
+    // with them, slot by slot in ascending order (a live sequence only ever moves to a lower slot, and the
+    // slot it moves to has been vacated or belongs to a finished sequence), so later steps run over the
+    // leading rows only and no kernel needs a row -> slot indirection.
     std::vector<int> host_gb((size_t)B, -1);
     const int done_at = CTL_SEQ_GB + c->max_batch, words = CTL_WORDS + 2 * c->max_batch;
+    const size_t es = c->m.dtype == L2PD_FP32 ? 4 : 2;
+    const size_t slice = (size_t)L.Tpad * c->m.d_model * es;   // one sequence's K (or V^T) of one layer
     for (int k = 0; k <= G; ++k) {
-      launch_prepare(state, B, nb, 1, ctl, s, done_at);
+      launch_prepare(state, Bc, nb, 1, ctl, s, done_at);
       HIP_TRY(c, hipMemcpyAsync(c->pinned, ctl, (size_t)words * sizeof(int), hipMemcpyDeviceToHost, s));
       HIP_TRY(c, hipStreamSynchronize(s));
       if (c->pinned[CTL_ALL_DONE]) break;
-      for (int b = 0; b < B; ++b) {
+      int n_live = 0;
+      for (int b = 0; b < Bc; ++b) n_live += c->pinned[done_at + b] ? 0 : 1;
+      if (compacting && n_live > 0 && n_live < Bc) {
+        launch_compact(X, X_alt, state, state_alt, perm, perm_alt, B, P + G, s);
+        std::swap(X, X_alt);
+        std::swap(state, state_alt);
+        if (!perm) perm = c->at<int32_t>(L.perm2);
+        std::swap(perm, perm_alt);
+        int to = 0;
+        for (int from = 0; from < Bc; ++from) {
+          if (c->pinned[done_at + from]) continue;
+          if (from != to) {
+            for (int l = 0; l < c->m.n_layers; ++l) {
+              unsigned char* kl = c->ws + L.kstore + L.kv_layer_stride_k * l;
+              unsigned char* vl = c->ws + L.vstore + L.kv_layer_stride_v * l;
+              HIP_TRY(c, hipMemcpyAsync(kl + to * slice, kl + from * slice, slice, hipMemcpyDeviceToDevice, s));
+              HIP_TRY(c, hipMemcpyAsync(vl + to * slice, vl + from * slice, slice, hipMemcpyDeviceToDevice, s));
+            }
+            host_gb[to] = host_gb[from];
+          }
+          // the control words of the new order, for the host's own use below
+          c->pinned[CTL_SEQ_GB + to] = c->pinned[CTL_SEQ_GB + from];
+          c->pinned[done_at + to] = 0;
+          ++to;
+        }
+        Bc = n_live;
+        launch_prepare(state, Bc, nb, 1, ctl, s, done_at);   // the device's control block in the new order
+      }
+      for (int b = 0; b < Bc; ++b) {
         const int gb = c->pinned[CTL_SEQ_GB + b];
         if (c->pinned[done_at + b] || gb == host_gb[b]) continue;
         run_refresh_seq(c, X, b, P, cfg, gb, Gate{nullptr, -1}, s);
         host_gb[b] = gb;
       }
-      run_step(c, X, B, P, cfg, f, state, -1, no_taps, s);
+      run_step(c, X, Bc, P, cfg, f, state, -1, no_taps, s);
+      ++c->stat_steps;
+      c->stat_seq_steps += Bc;
     }
   } else if (cfg->kv_cache) {
     for (int gb = 0; gb < nb; ++gb) {
@@ -831,6 +883,7 @@ int32_t l2pd_egp_rollout(l2pd_ctx* c, const int32_t* prompt_dev, const int32_t* 
   int* ctl = c->at<int>(L.ctl);
   const int sl = cfg->block_len, G = cfg->gen_len, nb = G / sl;
   launch_init_decode(X, prompt_dev, B, P, G, c->m.mask_id, state, ctl, s);
+  c->stat_steps = c->stat_seq_steps = 0;
   const StepTaps no_taps = {nullptr, nullptr, nullptr, nullptr, nullptr};
   const EgpArgs egp = {reference_dev, conf_rows_dev, label_rows_dev};
   // every step commits at least one position per unfinished sequence: at most gen_len steps;

@@ -111,6 +111,11 @@ def test_decode_argument_checks_return_before_any_launch():
                                      None, None) == Bd.L2PD_EINVAL                          # no state
         assert lib.l2pd_profile_select(ctx, 99) == Bd.L2PD_EINVAL
         assert lib.l2pd_profile_select(ctx, Bd.K_GEMM_GATEUP) == Bd.L2PD_OK
+        steps, seq_steps = C.c_int64(-1), C.c_int64(-1)
+        assert lib.l2pd_generate_stats(ctx, C.byref(steps), C.byref(seq_steps)) == Bd.L2PD_OK
+        assert (steps.value, seq_steps.value) == (0, 0)                                      # nothing generated yet
+        assert lib.l2pd_generate_stats(ctx, None, None) == Bd.L2PD_OK
+        assert lib.l2pd_generate_stats(None, C.byref(steps), C.byref(seq_steps)) == Bd.L2PD_EINVAL
     finally:
         lib.l2pd_destroy(ctx)
 

@@ -139,15 +139,23 @@ def test_ragged_batch_with_kv_cache_equals_the_oracle_fp32(dual, eotp):
     need_lock, need_rag = int(per_block.max(axis=0).sum()), int(per_block.sum(axis=1).max())
     (t0, s0, d0), n_lock = forwards(eng, prompt.cuda(), fdev, cfg_of(w, False))
     (t1, s1, d1), n_rag = forwards(eng, prompt.cuda(), fdev, cfg_of(w, Bd.RAGGED_BLOCKS))
-    (t2, s2, d2), n_cmp = forwards(eng, prompt.cuda(), fdev, cfg_of(w, Bd.RAGGED_COMPACT))   # taken as BLOCKS with a cache
+    rows_rag = eng.generate_stats()[1]
+    (t2, s2, d2), n_cmp = forwards(eng, prompt.cuda(), fdev, cfg_of(w, Bd.RAGGED_COMPACT))   # live sequences moved to the front, their K/V slices with them
+    steps_cmp, rows_cmp = eng.generate_stats()
     for b in range(w.batch):
         for t, st, dl in ((t0, s0, d0), (t1, s1, d1), (t2, s2, d2)):
             np.testing.assert_array_equal(t.cpu().numpy()[b], want[b][0])
             assert int(st[b]) == want[b][1] and int(dl[b]) == want[b][2]
     print(f"{'dual' if dual else 'prefix'} cache, eotp={eotp}: steps {s1.tolist()}; forwards needed lock step {need_lock}, "
           f"own blocks {need_rag}; enqueued {n_lock}, {n_rag}")
-    assert n_rag == need_rag == n_cmp   # the host looks before every step: not one forward too many
+    assert n_rag == need_rag == n_cmp == steps_cmp   # the host looks before every step: not one forward too many
     assert need_rag <= need_lock and n_rag <= n_lock
+    # compaction: a step runs over the sequences still decoding only, so the sequence-steps are the sum of the
+    # sequences' own step counts once every finished sequence has been dropped at the host's next look
+    print(f"sequence-steps: own blocks {rows_rag}, with compaction {rows_cmp}, sum of the step counts {int(s2.sum())}")
+    assert rows_rag == w.batch * n_rag and rows_cmp == int(s2.sum())
+    if len(set(s2.tolist())) > 1:
+        assert rows_cmp < rows_rag
     if not eotp:
         assert need_rag < need_lock     # six blocks of spread step counts: own blocks really save forwards
 
@@ -192,3 +200,13 @@ def test_ragged_bf16_kv_cache_rows_match_lock_step(B, dual):
     # expected whenever every rebuild stays on one path; the invariants hold regardless
     assert not torch.any(t1[:, :96] == w.model.mask_id) and torch.all(t1[:, 96:] == w.model.mask_id)
     assert n_rag <= n_lock
+    # compaction on top: the live sequences and their slices of the stores move to the front; the same
+    # invariants, and a step runs over the sequences still decoding only
+    rows_rag = eng.generate_stats()[1]
+    (t2, s2, d2), n_cmp = forwards(eng, prompt.cuda(), fdev, cfg_of(w, Bd.RAGGED_COMPACT))
+    rows_cmp = eng.generate_stats()[1]
+    assert torch.equal(d2, d1)
+    assert not torch.any(t2[:, :96] == w.model.mask_id) and torch.all(t2[:, 96:] == w.model.mask_id)
+    assert rows_cmp == int(s2.sum()) <= rows_rag
+    print(f"  compaction: steps {s2.tolist()}, identical to own blocks {torch.equal(t1, t2) and torch.equal(s1, s2)}, "
+          f"sequence-steps {rows_rag} -> {rows_cmp}")
