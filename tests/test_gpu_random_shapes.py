@@ -47,6 +47,40 @@ def test_random_bf16_shape_forward(seed):
         assert Pz.rel_err(alone, got[B - 1]) < 2e-2
 
 
+# Widths from 2048 up take the tiles that read their A operand into registers from quad-tiled activations
+# (256 x 96 for Q/K/V, 256 x 192 for gate/up, 256 x 128 with K split four ways for the output and down
+# projections where K is a multiple of 1024); the 8B-width tests cover one shape of them.  Others by hand:
+# both head sizes, gate/up columns that no tile divides, depths that do and do not allow the four-way split,
+# row counts that no tile divides, a batch whose row groups straddle sequences.
+WIDE = [
+    # (d, H, Dh, F, V, B, T)
+    (2048, 32, 64, 4096, 1500, 1, 300),     # head size 64; O and down both split four ways
+    (2048, 16, 128, 5632, 1100, 2, 261),    # F = 5.5 x 1024: down takes 128 x 128 tiles and a row-major act; 522 rows
+    (2560, 20, 128, 6400, 900, 1, 515),     # K = 2560 for Q/K/V and gate/up; 12800 gate/up columns (66.7 tiles of 192)
+    (3072, 24, 128, 3072, 700, 3, 171),     # three sequences of 171 rows: 513 rows, quads straddle sequences
+]
+
+
+@pytest.mark.parametrize("case", range(len(WIDE)))
+def test_wide_bf16_shape_forward(case):
+    d, H, Dh, F, V, B, T = WIDE[case]
+    m = synth.ModelShape(1, d, H, Dh, F, V, V - 1, V - 2, dtype="bf16")
+    weights = synth.make_weights(m, 140 + case, "cpu")
+    ora = Pz.oracle_model(m, weights, gemm_input="bf16")
+    eng = Bd.Engine(m, Pz.to_dev(weights), B, T)
+    X = synth.make_prompt(160 + case, B, T, m.vocab - 2, "cpu")
+    got = eng.forward(X.cuda()).cpu().numpy()
+    again = eng.forward(X.cuda()).cpu().numpy()
+    np.testing.assert_array_equal(got, again)                     # bit-reproducible
+    worst = max(Pz.rel_err(got[b], ora.forward(X[b].numpy())) for b in range(B))
+    print(f"d={d} H={H}x{Dh} F={F} V={V} B={B} T={T}: {worst:.2e}")
+    assert worst < 2e-2
+    if B > 1:
+        # more than 256 rows in the batch, fewer in one sequence: other tiles, same arithmetic up to the split depth
+        alone = eng.forward(X[B - 1:B].cuda()).cpu().numpy()[0]
+        assert Pz.rel_err(alone, got[B - 1]) < 2e-2
+
+
 def draw_step(seed):
     r = np.random.default_rng(3000 + seed)
     Dh = int(r.choice([64, 128]))
