@@ -65,6 +65,16 @@ def test_8b_width_forward_is_bitwise_reproducible():
         again = eng.forward(X, w.prompt_len, w.block_len)
         torch.cuda.synchronize()
         assert torch.equal(again, first), f"forward {it} differs from the first"
+    # 2048 rows take other tiles (256 x 192 for Q/K/V as well): 40 forwards of a batch of four
+    eng4 = Bd.engine_for(w, SEED, "cuda", max_batch=4)
+    X4 = synth.make_prompt(SEED + 1, 4, w.prompt_len + w.gen_len, w.prompt_hi, "cuda")
+    first4 = eng4.forward(X4, w.prompt_len, w.block_len).clone()
+    torch.cuda.synchronize()
+    assert torch.isfinite(first4).all()
+    for it in range(40):
+        again = eng4.forward(X4, w.prompt_len, w.block_len)
+        torch.cuda.synchronize()
+        assert torch.equal(again, first4), f"batched forward {it} differs from the first"
 
 
 def test_8b_width_row_count_that_no_tile_divides():
