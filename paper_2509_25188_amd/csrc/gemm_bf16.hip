@@ -567,25 +567,57 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
     const bool vec4 = (e.Tq % 4 == 0) && (e.pos0 % 4 == 0) && (e.Tpad % 4 == 0) && (!e.seq_gb || e.pos_per_gb % 4 == 0);
     const int up = (lj >> 4) & 1;   // 0: this lane's column is a first-half feature, 1: its rotation partner
     const int lr = lj & 3;
+    // which matrix / head / 16-feature group each of the wavefront's column fragments belongs to (uniform)
+    int f_mat[FN], f_head[FN], f_gi[FN];
 #pragma unroll
     for (int j = 0; j < FN; ++j) {
       const int Gq = tile_n * (BN / 32) + wn * FN + j;
-      const int hg = Gq / gpq, gi = Gq % gpq;
-      const int mat = hg / e.H, head = hg % e.H;
-      if (mat > 2) continue;                        // uniform over the wavefront
-      const int dim1 = gi * 16 + (lj & 15);         // first-half feature of this lane's pair
-      const int dim = dim1 + up * half;             // this lane's own feature
+      const int hg = Gq / gpq;
+      f_gi[j] = Gq % gpq;
+      f_mat[j] = hg / e.H;
+      f_head[j] = hg % e.H;
+    }
 #pragma unroll
-      for (int i = 0; i < FM; ++i) {
+    for (int i = 0; i < FM; ++i) {
+      // Sequence and position of this lane's 16 rows (register r: row (r/4)*8 + hf*4 + r%4 of the fragment), worked
+      // out once per row fragment and shared by all column fragments.
+      int seq_r[16], pos_r[16];
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        const int row0 = row_base + i * 32 + rq * 8 + hf * 4;
+        int t = row0 % e.Tq, bq = row0 / e.Tq;
+        int off = (e.seq_gb && row0 < a.M) ? e.seq_gb[bq] * e.pos_per_gb : 0;
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+          seq_r[rq * 4 + rr] = bq;
+          pos_r[rq * 4 + rr] = e.pos0 + off + t;
+          if (++t == e.Tq) {   // next sequence of the batch
+            t = 0;
+            ++bq;
+            off = (e.seq_gb && row0 + rr + 1 < a.M) ? e.seq_gb[bq] * e.pos_per_gb : 0;
+          }
+        }
+      }
+      // after the transposes a lane stores row `lr` of each group of four
+      int seq_st[4], pos_st[4];
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        seq_st[rq] = lr == 0 ? seq_r[rq * 4] : (lr == 1 ? seq_r[rq * 4 + 1] : (lr == 2 ? seq_r[rq * 4 + 2] : seq_r[rq * 4 + 3]));
+        pos_st[rq] = lr == 0 ? pos_r[rq * 4] : (lr == 1 ? pos_r[rq * 4 + 1] : (lr == 2 ? pos_r[rq * 4 + 2] : pos_r[rq * 4 + 3]));
+      }
+#pragma unroll
+      for (int j = 0; j < FN; ++j) {
+        const int mat = f_mat[j], head = f_head[j];
+        if (mat > 2) continue;                               // uniform over the wavefront
+        const int dim1 = f_gi[j] * 16 + (lj & 15);
+        const int dim = dim1 + up * half;                    // this lane's own feature
         if (mat == 2) {
-          // V^T store, as in EPI_QKV
           unsigned short* vt = reinterpret_cast<unsigned short*>(e.vtstore);
 #pragma unroll
           for (int rq = 0; rq < 4; ++rq) {
             const int row0 = row_base + i * 32 + rq * 8 + hf * 4;
             if (vec4 && row0 + 3 < a.M) {
-              const int b = row0 / e.Tq, pos = e.pos0 + seq_pos_offset(e.seq_gb, e.pos_per_gb, b) + row0 % e.Tq;
-              const size_t o = ((size_t)(b * e.H + head) * e.Dh + dim) * e.Tpad + pos;
+              const size_t o = ((size_t)(seq_r[rq * 4] * e.H + head) * e.Dh + dim) * e.Tpad + pos_r[rq * 4];
               uint2 v4;
               v4.x = pack_bf16(acc[i][j][rq * 4 + 0], acc[i][j][rq * 4 + 1]);
               v4.y = pack_bf16(acc[i][j][rq * 4 + 2], acc[i][j][rq * 4 + 3]);
@@ -593,37 +625,22 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
             } else {
 #pragma unroll
               for (int rr = 0; rr < 4; ++rr) {
-                const int row = row0 + rr;
-                if (row >= a.M) continue;
-                const int b = row / e.Tq, pos = e.pos0 + seq_pos_offset(e.seq_gb, e.pos_per_gb, b) + row % e.Tq;
-                vt[((size_t)(b * e.H + head) * e.Dh + dim) * e.Tpad + pos] = f2bf(acc[i][j][rq * 4 + rr]);
+                if (row0 + rr >= a.M) continue;
+                vt[((size_t)(seq_r[rq * 4 + rr] * e.H + head) * e.Dh + dim) * e.Tpad + pos_r[rq * 4 + rr]] =
+                    f2bf(acc[i][j][rq * 4 + rr]);
               }
             }
           }
         } else {
           unsigned short* dst = reinterpret_cast<unsigned short*>(mat == 0 ? e.q : e.kstore);
-          float cs[16], sn[16];   // all table reads before the first store (see EPI_QKV)
+          float cs[16], sn[16];   // all table reads before the first store of the fragment
 #pragma unroll
-          for (int rq = 0; rq < 4; ++rq) {
-            const int row0 = row_base + i * 32 + rq * 8 + hf * 4;
-            int t = row0 % e.Tq, bq = row0 / e.Tq;
-            int off = (e.seq_gb && row0 < a.M) ? e.seq_gb[bq] * e.pos_per_gb : 0;
-#pragma unroll
-            for (int rr = 0; rr < 4; ++rr) {
-              const int r = rq * 4 + rr;
-              const bool live = row0 + rr < a.M;
-              const unsigned ti = (unsigned)(e.pos0 + off + t) * (unsigned)half + (unsigned)dim1;
-              cs[r] = live ? e.cos_t[ti] : 0.f;
-              sn[r] = live ? e.sin_t[ti] : 0.f;
-              if (++t == e.Tq) {
-                t = 0;
-                ++bq;
-                off = (e.seq_gb && row0 + rr + 1 < a.M) ? e.seq_gb[bq] * e.pos_per_gb : 0;
-              }
-            }
+          for (int r = 0; r < 16; ++r) {
+            const bool live = row_base + i * 32 + (r >> 2) * 8 + hf * 4 + (r & 3) < a.M;
+            const unsigned ti = (unsigned)pos_r[r] * (unsigned)half + (unsigned)dim1;   // < 2^31 by construction
+            cs[r] = live ? e.cos_t[ti] : 0.f;
+            sn[r] = live ? e.sin_t[ti] : 0.f;
           }
-          // The pair's other member sits 16 lanes away in the same register.  The same two explicitly rounded
-          // operations per output as EPI_QKV: x1 cos - x2 sin for the first half, x2 cos + x1 sin for its partner.
           float o[16];
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
@@ -632,7 +649,7 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
             const float ps = __fmul_rn(xp, sn[r]);
             o[r] = __fmaf_rn(x, cs[r], up ? ps : -ps);
           }
-          const int c4 = gi * 16 + (lj & 12) + up * half;   // after the transpose: first of this lane's four features
+          const int c4 = f_gi[j] * 16 + (lj & 12) + up * half;   // after the transpose: first of this lane's four features
 #pragma unroll
           for (int rq = 0; rq < 4; rq += 2) {   // two row groups share one transpose: low / high half words
             unsigned w[4];
@@ -643,13 +660,8 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
             for (int h2 = 0; h2 < 2; ++h2) {
               const int row = row_base + i * 32 + (rq + h2) * 8 + hf * 4 + lr;
               if (row >= a.M) continue;
-              size_t oo;
-              if (mat == 0) {
-                oo = (size_t)row * e.d + head * e.Dh + c4;
-              } else {
-                const int b = row / e.Tq, pos = e.pos0 + seq_pos_offset(e.seq_gb, e.pos_per_gb, b) + row % e.Tq;
-                oo = ((size_t)b * e.Tpad + pos) * e.d + head * e.Dh + c4;
-              }
+              const size_t oo = mat == 0 ? (size_t)row * e.d + head * e.Dh + c4
+                                         : ((size_t)seq_st[rq + h2] * e.Tpad + pos_st[rq + h2]) * e.d + head * e.Dh + c4;
               uint2 st;
               st.x = h2 ? (w[0] >> 16) | (w[1] & 0xffff0000u) : (w[0] & 0xffffu) | (w[1] << 16);
               st.y = h2 ? (w[2] >> 16) | (w[3] & 0xffff0000u) : (w[2] & 0xffffu) | (w[3] << 16);
