@@ -761,10 +761,10 @@ static void launch(GemmArgs& a, hipStream_t s) {
 // keep its MFMAs fed (64 flop per loaded byte); 256-wide tiles halve that traffic and win whenever
 // there are enough of them to occupy the 256 CUs.  cost = rounds over the CUs x work per tile /
 // measured relative per-CU rate of the configuration.  256x192 exists because 512 rows x 24576
-// gate/up columns make exactly 256 such tiles, one round with every CU busy, and 128x192 does the
-// same for the 12288 Q/K/V columns.  (With random operands
-// the chip is power limited: the shader clock sits near 1.5-1.6 GHz inside these kernels, and a
-// register-resident MFMA stream alone tops out at 1.78 PFLOP/s.)
+// gate/up columns make exactly 256 such tiles, one round with every CU busy; for the 12288 Q/K/V
+// columns 256x96 (pick_tile_qkv, A in registers) and, where that is not available, 128x192 do the same.
+// (With random operands the chip is power limited: the shader clock sits well below its 2.4 GHz inside
+// these kernels, and a register-resident MFMA stream alone tops out at 1.78 PFLOP/s.)
 static double tile_cost(int M, int N, int bm, int bn, double rate) {
   const double tiles = (double)((M + bm - 1) / bm) * ((N + bn - 1) / bn);
   const double rounds = (double)(((long long)tiles + 255) / 256);
