@@ -64,7 +64,7 @@ void launch_prepare(const int32_t* state, int B, int n_blocks, int ragged, int* 
                     int done_at = 0);   // done_at > 0: also ctl[done_at + b] = sequence b's done flag
 void launch_embed(float* h, const void* emb, int dtype, const int32_t* tokens, RowMap tokmap, int rows, int d,
                   Gate g, hipStream_t s);
-// h (+= part[0] + ... + part[n_parts-1] in that order when given) -> y = rmsnorm(h) * gain, rows taken
+// h (+= the sum part[0] + ... + part[n_parts-1], formed first, in that order, when given) -> y = rmsnorm(h) * gain, rows taken
 // through `src`.  part z is at parts + z * part_stride, laid out like h.  The sum is written back to h
 // when `write_back` is set; the final norm before the LM head leaves h alone (h is dead after it, and
 // two head rows may map to one row of h, so a write-back would race).
@@ -188,7 +188,7 @@ void launch_gemm_partial_bf16(const bf16* A, const bf16* W, float* parts, size_t
 constexpr int kSkinnyRows = 64;
 constexpr int kSkinnyRowsAttn = 64;   // B * Tq up to which attention may chunk the keys across workgroups
 int skinny_splits(int N, int K);
-int wide_splits(int M, int N, int K);   // split-K depth of the wide path's [d, d] / [d, F] projections, at most 8
+int wide_splits(int M, int N, int K);   // partial buffers the wide path's [d, d] / [d, F] projections write, at most 8
 void launch_gemm_skinny_bf16(const bf16* A, const bf16* w0, const bf16* w1, const bf16* w2, int n_sub, float* parts,
                              size_t part_stride, int M, int N, int K, int splits, Gate g, hipStream_t s);
 // sums of the skinny GEMM's partials -> rotated q, K store, V^T store / SiLU(gate) * up

@@ -26,7 +26,9 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
-enum { EPI_PARTIAL = 0, EPI_QKV = 1, EPI_SWIGLU = 2, EPI_LMHEAD = 3, EPI_QKV16 = 4 };
+enum { EPI_PARTIAL = 0, EPI_QKV = 1, EPI_SWIGLU = 2, EPI_LMHEAD = 3, EPI_QKV16 = 4, EPI_PARTIAL_SER = 5 };
+// EPI_PARTIAL_SER is EPI_PARTIAL with GemmArgs::serial honoured (a kernel of its own: the second set of
+// accumulators would cost the plain one registers).
 // EPI_QKV and EPI_QKV16 compute the same Q/K/V projection with the same rotation arithmetic; they differ in
 // how the weight rows are dealt to the MFMA column fragments.  EPI_QKV puts 32 first-half features of a head
 // in one fragment and their rotation partners (feature + Dh/2) in the next, so a lane holds both members of
@@ -45,6 +47,9 @@ struct GemmArgs {
   // EPI_PARTIAL: K range z writes to parts + z * part_stride (fp32 [M, N])
   float* parts;
   size_t part_stride;
+  int serial;           // > 1 (A-in-registers tile only, splits == 1): the workgroup walks `serial` K ranges one
+                        // after the other, each into a fresh accumulator, and writes their sum, formed in
+                        // ascending order: the bits that `serial` workgroups' partials give when the RMSNorm sums them
   int n_sub;            // > 0: the N rows are the rows of B0, B1, B2 stacked, n_sub rows each
   // EPI_SWIGLU
   bf16* act;
@@ -393,12 +398,37 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
     step(setc, std::integral_constant<int, (SET + NS - 1) % 4>{}, KS - 1, smem + ((kt + 1) % NS) * STAGE_BYTES, 0,
          (kt + NS - 1 < nk) ? kt + NS - 1 : -1, kt + NS - 1, 0);
   };
+  constexpr bool SERIAL = AREG && EPI == EPI_PARTIAL_SER;
+  f32x16 tot[SERIAL ? FM : 1][SERIAL ? FN : 1];   // sum of the finished K ranges
+  const int seg = SERIAL ? nk / max(a.serial, 1) : 0;   // stages per K range (a multiple of four)
   if constexpr (AREG) {
     for (int kt = 0; kt < nk; kt += 4) {   // the launcher guarantees nk % 4 == 0
       stage(std::integral_constant<int, 0>{}, kt);
       stage(std::integral_constant<int, 1>{}, kt + 1);
       stage(std::integral_constant<int, 2>{}, kt + 2);
       stage(std::integral_constant<int, 3>{}, kt + 3);
+      if constexpr (SERIAL) {
+        if (a.serial > 1 && (kt + 4) % seg == 0) {   // a K range ends here: bank it and start the next from zero
+          const bool first = kt + 4 == seg;
+#pragma unroll
+          for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+              for (int r = 0; r < 16; ++r) {
+                tot[i][j][r] = first ? acc[i][j][r] : tot[i][j][r] + acc[i][j][r];
+                acc[i][j][r] = 0.f;
+              }
+        }
+      }
+    }
+    if constexpr (SERIAL) {
+      if (a.serial > 1) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+          for (int j = 0; j < FN; ++j) acc[i][j] = tot[i][j];
+      }
     }
   } else {
     for (int kt = 0; kt < nk; ++kt) stage(std::integral_constant<int, 0>{}, kt);
@@ -408,7 +438,7 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
   // ------------------------------------------------------------------------------------------
   // C layout of the 32x32 MFMA: register r of a lane is row (r/4)*8 + hf*4 + r%4, column lj.
   const int row_base = m0 + wm * (BM / WM);
-  if constexpr (EPI == EPI_PARTIAL) {
+  if constexpr (EPI == EPI_PARTIAL || EPI == EPI_PARTIAL_SER) {
     float* out = a.parts + (size_t)z * a.part_stride;
 #pragma unroll
     for (int i = 0; i < FM; ++i)
@@ -824,14 +854,24 @@ void launch_gemm_qkv_bf16(const bf16* A, const bf16* wq, const bf16* wk, const b
   }
 }
 
+static bool partial_serial(int M, int N);
 void launch_gemm_partial_bf16(const bf16* A, const bf16* W, float* parts, size_t part_stride, int M, int N, int K,
                               int splits, Gate g, hipStream_t s) {
   GemmArgs a = {};
   a.A = A; a.B0 = W; a.M = M; a.N = N; a.K = K; a.splits = splits; a.gate = g;
   a.parts = parts; a.part_stride = part_stride;
-  if (splits == 1 && pick_tile(M, N) == 2) launch<256, 256, 32, 4, 2, 4, EPI_PARTIAL>(a, s);
-  else if (splits == 4 && gemm_partial_a_quad_tiled(M, N, K)) launch<256, 128, 64, 4, 1, 4, EPI_PARTIAL, true>(a, s);
-  else launch<128, 128, 64, 2, 2, 4, EPI_PARTIAL>(a, s);
+  if (gemm_partial_a_quad_tiled(M, N, K) && (splits == 4 || (splits == 1 && partial_serial(M, N)))) {
+    if (splits == 1) {
+      a.serial = 4;
+      launch<256, 128, 64, 4, 1, 4, EPI_PARTIAL_SER, true>(a, s);
+    } else {
+      launch<256, 128, 64, 4, 1, 4, EPI_PARTIAL, true>(a, s);
+    }
+  } else if (splits == 1 && pick_tile(M, N) == 2) {
+    launch<256, 256, 32, 4, 2, 4, EPI_PARTIAL>(a, s);
+  } else {
+    launch<128, 128, 64, 2, 2, 4, EPI_PARTIAL>(a, s);
+  }
 }
 
 // Wide path, [d, d] and [d, F] projections: 128 x 128 tiles of these narrow outputs do not fill the
@@ -850,8 +890,13 @@ void launch_gemm_partial_bf16(const bf16* A, const bf16* W, float* parts, size_t
 bool gemm_partial_a_quad_tiled(int M, int N, int K) {
   return M > 256 && N % 128 == 0 && K % 1024 == 0 && K / 4 >= 512 && N % 8 == 0;
 }
+// With about a tile per CU or more, four workgroups per tile buy no parallelism and cost three more partials
+// to write and to fold (2048 rows of the 8B shape: projection 163 us and RMSNorm 43 us against ...): one workgroup
+// then walks the four K ranges itself and writes the one sum.  Same bits either way (GemmArgs::serial), so
+// this may depend on the row count.
+static bool partial_serial(int M, int N) { return ((M + 255) / 256) * ((N + 127) / 128) >= 224; }
 int wide_splits(int M, int N, int K) {
-  if (M > 256 && gemm_partial_a_quad_tiled(M, N, K)) return 4;
+  if (M > 256 && gemm_partial_a_quad_tiled(M, N, K)) return partial_serial(M, N) ? 1 : 4;
   if (M > 256) return (K % 128 == 0 && K / 2 >= 512) ? 2 : 1;
   const int tiles = ((M + 127) / 128) * ((N + 127) / 128);
   int S = 1;

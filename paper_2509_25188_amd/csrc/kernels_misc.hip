@@ -167,8 +167,11 @@ __device__ __forceinline__ float wave_sum(float v) {
 }
 
 // One wavefront per row: the row's sum of squares is a 64-lane butterfly, no LDS.
-// When partial buffers are given the residual update h += part[0] + part[1] + ... (that order) is
-// folded in; part z is at parts + z * part_stride, laid out like h.
+// When partial buffers are given the residual update h += (((part[0] + part[1]) + part[2]) + ...) is folded
+// in: the partials are summed first, in ascending order, and their sum is added to h.  (A projection whose
+// workgroups walk the K ranges one after the other forms the same sum in registers and writes it as its only
+// partial: summing the partials before h is what makes the two bit-identical.)  Part z is at
+// parts + z * part_stride, laid out like h.
 template <typename T>
 __global__ void k_rmsnorm(float* h, const float* parts, int n_parts, size_t part_stride, RowMap src, const T* gain,
                           T* y, int rows, int d, float eps, int wb, Gate g) {
@@ -183,7 +186,9 @@ __global__ void k_rmsnorm(float* h, const float* parts, int n_parts, size_t part
   for (int i = lane; i < d; i += 64) {
     float v = x[i];
     if (n_parts > 0) {
-      for (int z = 0; z < n_parts; ++z) v += a0[z * part_stride + i];
+      float ps = a0[i];
+      for (int z = 1; z < n_parts; ++z) ps += a0[z * part_stride + i];
+      v += ps;
       if (wb) x[i] = v;
     }
     ss += v * v;
@@ -193,8 +198,11 @@ __global__ void k_rmsnorm(float* h, const float* parts, int n_parts, size_t part
   T* o = y + (size_t)r * d;
   for (int i = lane; i < d; i += 64) {
     float v = x[i];
-    if (n_parts > 0 && !wb)
-      for (int z = 0; z < n_parts; ++z) v += a0[z * part_stride + i];
+    if (n_parts > 0 && !wb) {
+      float ps = a0[i];
+      for (int z = 1; z < n_parts; ++z) ps += a0[z * part_stride + i];
+      v += ps;
+    }
     o[i] = from_f<T>(v * inv * to_f<T>(gain[i]));
   }
 }
@@ -218,20 +226,21 @@ __global__ void __launch_bounds__(256) k_rmsnorm_vec(float* h, const float* part
     v[k] = i < d4 ? x[i] : make_float4(0.f, 0.f, 0.f, 0.f);
   }
   if (n_parts > 0) {
+    float4 ps[VPL];
     for (int z = 0; z < n_parts; ++z) {
       const float4* az = reinterpret_cast<const float4*>(parts + z * part_stride + srow * d);
 #pragma unroll
       for (int k = 0; k < VPL; ++k) {
         const int i = lane + 64 * k;
-        if (i < d4) {
-          float4 t = az[i];
-          v[k].x += t.x; v[k].y += t.y; v[k].z += t.z; v[k].w += t.w;
-        }
+        float4 t = i < d4 ? az[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+        if (z == 0) ps[k] = t;
+        else { ps[k].x += t.x; ps[k].y += t.y; ps[k].z += t.z; ps[k].w += t.w; }
       }
     }
 #pragma unroll
     for (int k = 0; k < VPL; ++k) {
       const int i = lane + 64 * k;
+      v[k].x += ps[k].x; v[k].y += ps[k].y; v[k].z += ps[k].z; v[k].w += ps[k].w;
       if (wb && i < d4) x[i] = v[k];
     }
   }
@@ -293,6 +302,9 @@ __global__ void __launch_bounds__(256) k_rmsnorm_row(float* h, const float* part
   // partials four at a time (the few-row path folds eight or more): the loads of a group are in
   // flight together, the adds stay in ascending order
   constexpr int GRP = 4;
+  float4 ps[VPL];
+#pragma unroll
+  for (int k = 0; k < VPL; ++k) ps[k] = make_float4(0.f, 0.f, 0.f, 0.f);
   for (int z0 = 0; z0 < n_parts; z0 += GRP) {
     float4 t[GRP][VPL];
 #pragma unroll
@@ -310,9 +322,14 @@ __global__ void __launch_bounds__(256) k_rmsnorm_row(float* h, const float* part
       if (z0 + z < n_parts) {
 #pragma unroll
         for (int k = 0; k < VPL; ++k) {
-          v[k].x += t[z][k].x; v[k].y += t[z][k].y; v[k].z += t[z][k].z; v[k].w += t[z][k].w;
+          if (z0 + z == 0) ps[k] = t[z][k];
+          else { ps[k].x += t[z][k].x; ps[k].y += t[z][k].y; ps[k].z += t[z][k].z; ps[k].w += t[z][k].w; }
         }
       }
+  }
+  if (n_parts > 0) {   // the partials' sum, then the residual: h + (p0 + p1 + ...)
+#pragma unroll
+    for (int k = 0; k < VPL; ++k) { v[k].x += ps[k].x; v[k].y += ps[k].y; v[k].z += ps[k].z; v[k].w += ps[k].w; }
   }
   float ss = 0.f;
 #pragma unroll

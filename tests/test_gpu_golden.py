@@ -43,9 +43,11 @@ def forced_and_free(case, w, seqs, eng, flt, exempt_frac, batch_rows=None):
         meta, recs, result = Pz.load_trajectory(path_of(case, b))
         assert meta["workload"] == (w.name.split("_L")[0]) and meta["layers"] == w.model.n_layers and meta["seq"] == b
         np.testing.assert_array_equal(np.load(path_of(case, b))["prompt"], prompts[b].cpu().numpy())
-        # logits: the stated tolerance, or 1.5 x the stored noise floor where that is larger (deep random-init
+        # logits: the stated tolerance, or 2 x the stored noise floor where that is larger (the floor is the distance
+        # of one float32 summation order, the oracle's, from exact accumulation; the HIP path is another order, so
+        # floor + floor bounds their distance by the triangle inequality; deep random-init
         # models: the same oracle accumulated in float64 instead of float32 already moves the logits that far)
-        lim = max(Pz.tol_for(w.model), 1.5 * meta["floor_rel_max"])
+        lim = max(Pz.tol_for(w.model), 2.0 * meta["floor_rel_max"])
         for r in recs:
             r["logit_tol"] = lim
         forced = Pz.teacher_forced(eng, [recs], w.prompt_len, cfg, flt, w.model, w.threshold, rep,
@@ -163,7 +165,7 @@ def test_8b_g1024_eotp_two_layers_whole_trajectory_and_steps_saved():
 def test_8b_g256_full_depth_whole_trajectory():
     # the benchmarked workload itself: 32 layers, 512 rows, every step of the oracle's whole trajectory (242
     # steps) teacher-forced, logits compared at the first and last step of every block, then the free-running
-    # decode.  The logit tolerance is 1.5 x the noise floor stored with the trajectory (the same oracle
+    # decode.  The logit tolerance is 2 x the noise floor stored with the trajectory (the same oracle
     # accumulated in float64: 1.9e-2 of the largest logit at this depth), see forced_and_free; at this depth the
     # two oracle evaluations differ by 0.31 logit units, so more positions are near-ties than at two layers
     # (measured 6.8 % exempt).
