@@ -9,6 +9,7 @@ impose every state on l2pd_denoise_step and compare (teacher forcing), and compa
 tokens, step count and decoded length with the oracle's.
 
     python tests/golden/make_trajectories.py <case> [<case> ...]      (see CASES; "all-quick" = the cheap ones)
+    python tests/golden/make_trajectories.py --fill-floor <case> ...  (float64 distance at every sampled step)
 
 Oracle used: bf16 models are evaluated with every matrix-product input rounded to bf16 and float32
 accumulation (the arithmetic of the path under test); at sampled steps (first and last step of every
@@ -275,7 +276,38 @@ def run_case(name: str):
         print(f"  sequence {b}: written {path_of(name, b)} in {time.time() - t0:.0f} s", flush=True)
 
 
+def fill_floor(name: str):
+    """Computes the float64 distance (floor_abs) at every sampled step of an existing file that does not have
+    it yet (the "few" cases store it at every sixth sampled step only) and rewrites the file."""
+    case = CASES[name]
+    w = synth.WORKLOADS[case.workload]
+    if case.layers:
+        w = synth.with_layers(w, case.layers)
+    ora = Oracles(w, need_f64=True)
+    for b in case.seqs:
+        z = dict(np.load(path_of(name, b)))
+        floor = z["floor_abs"].copy()
+        caches = {"main": {}, "f64": {}}
+        for k, i in enumerate(z["smp_idx"]):
+            if np.isfinite(floor[k]):
+                continue
+            t0 = time.time()
+            X, blk = z["X_before"][i].astype(np.int64), int(z["block"][i])
+            lg = ora.block_logits(ora.main, X, blk, caches["main"])
+            # the stored step again (BLAS may block differently with another thread count: equal up to that)
+            np.testing.assert_allclose(lg[:, z["cols_fixed"]], z["lg_fixed"][k], rtol=0, atol=5e-2 * float(z["floor_abs"][0]))
+            l3 = ora.block_logits(ora.f64, X, blk, caches["f64"])
+            floor[k] = np.float32(np.max(np.abs(l3 - lg.astype(np.float64))))
+            z["floor_abs"] = floor
+            np.savez_compressed(path_of(name, b), **z)
+            print(f"  {name} seq {b}: sampled step {i}: floor {floor[k]:.4e} ({time.time() - t0:.0f} s)", flush=True)
+
+
 if __name__ == "__main__":
+    if len(sys.argv) > 2 and sys.argv[1] == "--fill-floor":
+        for n in sys.argv[2:]:
+            fill_floor(n)
+        sys.exit(0)
     names = sys.argv[1:]
     if not names:
         print(__doc__)
