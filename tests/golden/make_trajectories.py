@@ -299,7 +299,9 @@ def fill_floor(name: str):
             l3 = ora.block_logits(ora.f64, X, blk, caches["f64"])
             floor[k] = np.float32(np.max(np.abs(l3 - lg.astype(np.float64))))
             z["floor_abs"] = floor
-            np.savez_compressed(path_of(name, b), **z)
+            tmp = path_of(name, b) + ".tmp.npz"          # replace atomically: a kill must not leave half a file
+            np.savez_compressed(tmp, **z)
+            os.replace(tmp, path_of(name, b))
             print(f"  {name} seq {b}: sampled step {i}: floor {floor[k]:.4e} ({time.time() - t0:.0f} s)", flush=True)
 
 
