@@ -470,7 +470,7 @@ def main():
         result["copy_calibration"] = {"bytes_read_per_launch": n, "bytes_written_per_launch": n, "launches": 4}
     if not args.no_cpu_baseline:
         note("GPU legs done; timing the CPU oracle on a bounded sample")
-        result["cpu_baseline"] = cpu_baseline(w, tokens_per_step, args.seed, n_layers_sample=16)
+        result["cpu_baseline"] = cpu_baseline(w, tokens_per_step, args.seed, n_layers_sample=min(m.n_layers, 32))
     print(json.dumps(result))
 
 
