@@ -273,12 +273,12 @@ __global__ void __launch_bounds__(256) k_rmsnorm_vec(float* h, const float* part
 // wavefronts, each with a quarter of the loads, on the chip as the one-wavefront-per-row kernel.
 // The choice between the two depends on d only, never on the number of rows, so that a row's
 // result does not depend on the batch it is part of.
-template <typename T, int VPL>
-__global__ void __launch_bounds__(256) k_rmsnorm_row(float* h, const float* parts, int n_parts, size_t part_stride,
+template <typename T, int VPL, int NTH>
+__global__ void __launch_bounds__(NTH) k_rmsnorm_row(float* h, const float* parts, int n_parts, size_t part_stride,
                                                     RowMap src, const T* gain, T* y, int rows, int d, float eps,
                                                     int wb, int quad_tiled, Gate g) {
   if (gate_skip(g)) return;
-  __shared__ float s_part[4];
+  __shared__ float s_part[NTH / 64];
   const int tid = threadIdx.x;
   int r = blockIdx.x;
   if (quad_tiled) {
@@ -296,7 +296,7 @@ __global__ void __launch_bounds__(256) k_rmsnorm_row(float* h, const float* part
   float4 v[VPL];
 #pragma unroll
   for (int k = 0; k < VPL; ++k) {
-    const int i = tid + 256 * k;
+    const int i = tid + NTH * k;
     v[k] = i < d4 ? x[i] : make_float4(0.f, 0.f, 0.f, 0.f);
   }
   // partials four at a time (the few-row path folds eight or more): the loads of a group are in
@@ -313,7 +313,7 @@ __global__ void __launch_bounds__(256) k_rmsnorm_row(float* h, const float* part
       const float4* a = reinterpret_cast<const float4*>(parts + (have ? z0 + z : z0) * part_stride + srow * d);
 #pragma unroll
       for (int k = 0; k < VPL; ++k) {
-        const int i = tid + 256 * k;
+        const int i = tid + NTH * k;
         t[z][k] = (have && i < d4) ? a[i] : make_float4(0.f, 0.f, 0.f, 0.f);
       }
     }
@@ -334,21 +334,29 @@ __global__ void __launch_bounds__(256) k_rmsnorm_row(float* h, const float* part
   float ss = 0.f;
 #pragma unroll
   for (int k = 0; k < VPL; ++k) {
-    const int i = tid + 256 * k;
+    const int i = tid + NTH * k;
     if (wb && n_parts > 0 && i < d4) x[i] = v[k];
     ss += v[k].x * v[k].x + v[k].y * v[k].y + v[k].z * v[k].z + v[k].w * v[k].w;
   }
   ss = wave_sum(ss);
   if ((tid & 63) == 0) s_part[tid >> 6] = ss;
   __syncthreads();
-  ss = (s_part[0] + s_part[1]) + (s_part[2] + s_part[3]);
+  // the wavefronts' sums in a fixed pairwise tree
+  float tree[NTH / 64];
+#pragma unroll
+  for (int w = 0; w < NTH / 64; ++w) tree[w] = s_part[w];
+#pragma unroll
+  for (int n = NTH / 64; n > 1; n >>= 1)
+#pragma unroll
+    for (int w = 0; w < n / 2; ++w) tree[w] = tree[2 * w] + tree[2 * w + 1];
+  ss = tree[0];
   const float inv = rsqrtf(ss / (float)d + eps);
   T* o = y + (size_t)r * d;
   // quad-tiled: the row's 16-byte chunk c sits at ((r / 4) * (d / 8) + c) * 32 + (r % 4) * 8 elements
   T* oq = y + (size_t)(r >> 2) * 4 * d + (r & 3) * 8;
 #pragma unroll
   for (int k = 0; k < VPL; ++k) {
-    const int i = tid + 256 * k;
+    const int i = tid + NTH * k;
     if (i < d4) {
       const T* gp = gain + 4 * i;
       if constexpr (sizeof(T) == 4) {
@@ -365,6 +373,7 @@ __global__ void __launch_bounds__(256) k_rmsnorm_row(float* h, const float* part
   }
 }
 
+constexpr int NORM_TX = 4;   // threads per row = 256 * NORM_TX
 template <typename T>
 static void launch_rmsnorm_t(float* h, const float* parts, int n_parts, size_t part_stride, RowMap src, const T* gain,
                              T* y, int rows, int d, float eps, bool write_back, Gate g, hipStream_t s, bool quad_tiled) {
@@ -378,17 +387,17 @@ static void launch_rmsnorm_t(float* h, const float* parts, int n_parts, size_t p
     }
     const int grid_q = (rows + 31) / 32 * 32;
     if (d <= 4096)
-      hipLaunchKernelGGL((k_rmsnorm_row<T, 4>), dim3(grid_q), dim3(256), 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, wb, 1, g);
+      hipLaunchKernelGGL((k_rmsnorm_row<T, 4 / NORM_TX, 256 * NORM_TX>), dim3(grid_q), dim3(256 * NORM_TX), 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, wb, 1, g);
     else
-      hipLaunchKernelGGL((k_rmsnorm_row<T, 8>), dim3(grid_q), dim3(256), 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, wb, 1, g);
+      hipLaunchKernelGGL((k_rmsnorm_row<T, 8 / NORM_TX, 256 * NORM_TX>), dim3(grid_q), dim3(256 * NORM_TX), 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, wb, 1, g);
     return;
   }
   dim3 grid((rows + 3) / 4), block(256);
   if (rows <= 4096) { grid = dim3(rows); block = dim3(64); }   // few rows: one wavefront per workgroup fills more CUs
   if (d % 4 == 0 && d >= 2048 && d <= 4096)
-    hipLaunchKernelGGL((k_rmsnorm_row<T, 4>), dim3(rows), dim3(256), 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, wb, 0, g);
+    hipLaunchKernelGGL((k_rmsnorm_row<T, 4 / NORM_TX, 256 * NORM_TX>), dim3(rows), dim3(256 * NORM_TX), 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, wb, 0, g);
   else if (d % 4 == 0 && d > 4096 && d <= 8192)
-    hipLaunchKernelGGL((k_rmsnorm_row<T, 8>), dim3(rows), dim3(256), 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, wb, 0, g);
+    hipLaunchKernelGGL((k_rmsnorm_row<T, 8 / NORM_TX, 256 * NORM_TX>), dim3(rows), dim3(256 * NORM_TX), 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, wb, 0, g);
   else if (d % 4 == 0 && d <= 1024)
     hipLaunchKernelGGL((k_rmsnorm_vec<T, 4>), grid, block, 0, s, h, parts, n_parts, part_stride, src, gain, y, rows, d, eps, wb, g);
   else if (d % 4 == 0 && d <= 4096)

@@ -109,11 +109,18 @@ def test_8b_b32_prefix_two_layers_trajectories_and_batch_of_32():
     tok, st, dl = eng.generate(prompts, flt, cfg)
     tok, st, dl = tok.cpu().numpy(), st.cpu().numpy(), dl.cpu().numpy()
     stop = (w.bias_from // w.block_len + 1) * w.block_len
-    assert np.all(dl == stop) and not np.any(tok[:, :stop] == w.model.mask_id) and np.all(tok[:, stop:] == w.model.mask_id)
+    # Alg. 3 for every row: decoding stops after the first block that holds an end-of-text token, which the bias
+    # forces in the block of generation position 400; an untrained model may also pick the token by itself in an
+    # earlier block (one chance in 126,464 per position), and then that block is the last
+    for b in range(w.batch):
+        n = int(dl[b])
+        assert n % w.block_len == 0 and 0 < n <= stop
+        assert not np.any(tok[b, :n] == w.model.mask_id) and np.all(tok[b, n:] == w.model.mask_id)
+        assert np.any(tok[b, n - w.block_len:n] == w.model.eos_id) and not np.any(tok[b, :n - w.block_len] == w.model.eos_id)
+    assert np.sum(dl == stop) >= w.batch - 2
     assert len(set(st.tolist())) > 1                                                    # sequences in different states
     for b in (0, 17):
         recs, result, first_exempt = loaded[b]
-        assert int(dl[b]) == result[2]
         Pz.check_generate(tok[b], st[b], dl[b], recs, *result, first_exempt, w.prompt_len, w.block_len,
                           f"8b_b32_prefix_L2 batch of 32, row {b}")
 
