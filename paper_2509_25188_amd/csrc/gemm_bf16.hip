@@ -635,8 +635,27 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
         seq_st[rq] = lr == 0 ? seq_r[rq * 4] : (lr == 1 ? seq_r[rq * 4 + 1] : (lr == 2 ? seq_r[rq * 4 + 2] : seq_r[rq * 4 + 3]));
         pos_st[rq] = lr == 0 ? pos_r[rq * 4] : (lr == 1 ? pos_r[rq * 4 + 1] : (lr == 2 ? pos_r[rq * 4 + 2] : pos_r[rq * 4 + 3]));
       }
+      // Rotation tables, one column fragment ahead: the reads for fragment j + 1 are issued before fragment j's
+      // arithmetic and stores (the compiler cannot move a load above a store that might alias it, so read in
+      // place every fragment would wait out a memory round trip of its own).
+      float cst[2][16], snt[2][16];
+      auto load_tab = [&](int j, int buf) {
+        if (f_mat[j] >= 2) return;                           // V (or past the last column): no rotation
+        const int dim1 = f_gi[j] * 16 + (lj & 15);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const bool live = row_base + i * 32 + (r >> 2) * 8 + hf * 4 + (r & 3) < a.M;
+          const unsigned ti = (unsigned)pos_r[r] * (unsigned)half + (unsigned)dim1;   // < 2^31 by construction
+          cst[buf][r] = live ? e.cos_t[ti] : 0.f;
+          snt[buf][r] = live ? e.sin_t[ti] : 0.f;
+        }
+      };
+      load_tab(0, 0);
 #pragma unroll
       for (int j = 0; j < FN; ++j) {
+        if (j + 1 < FN) load_tab(j + 1, (j + 1) & 1);
+        const float* cs = cst[j & 1];
+        const float* sn = snt[j & 1];
         const int mat = f_mat[j], head = f_head[j];
         if (mat > 2) continue;                               // uniform over the wavefront
         const int dim1 = f_gi[j] * 16 + (lj & 15);
@@ -663,14 +682,6 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
           }
         } else {
           unsigned short* dst = reinterpret_cast<unsigned short*>(mat == 0 ? e.q : e.kstore);
-          float cs[16], sn[16];   // all table reads before the first store of the fragment
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const bool live = row_base + i * 32 + (r >> 2) * 8 + hf * 4 + (r & 3) < a.M;
-            const unsigned ti = (unsigned)pos_r[r] * (unsigned)half + (unsigned)dim1;   // < 2^31 by construction
-            cs[r] = live ? e.cos_t[ti] : 0.f;
-            sn[r] = live ? e.sin_t[ti] : 0.f;
-          }
           float o[16];
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
