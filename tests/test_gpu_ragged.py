@@ -38,7 +38,15 @@ def test_ragged_batch_equals_lock_step_and_oracle_fp32(eotp, eotp_step, mode):
     fdev = {k: v.cuda() for k, v in flt.items()}
     (t0, s0, d0), n_lock = forwards(eng, prompt.cuda(), fdev, cfg_of(w, False))
     (t1, s1, d1), n_rag = forwards(eng, prompt.cuda(), fdev, cfg_of(w, mode))
+    launches, seq_steps = eng.generate_stats()
     assert torch.equal(t0, t1) and torch.equal(s0, s1) and torch.equal(d0, d1)
+    # what the decode enqueued: without compaction every step runs over the whole batch; with it a finished
+    # sequence is dropped once the host has seen it (one to two chunks of four steps late), never earlier
+    assert launches == n_rag
+    if mode == Bd.RAGGED_COMPACT and not eotp_step:
+        assert int(s1.sum()) <= seq_steps <= w.batch * launches
+    else:
+        assert seq_steps == w.batch * launches
     for b in range(w.batch):
         resp, steps, dlen = Pz.oracle_generate(ora, prompt[b].numpy(), w, Pz.np_filter(flt))
         np.testing.assert_array_equal(t1.cpu().numpy()[b], resp)
