@@ -68,7 +68,7 @@ void launch_embed(float* h, const void* emb, int dtype, const int32_t* tokens, R
 // through `src`.  part z is at parts + z * part_stride, laid out like h.  The sum is written back to h
 // when `write_back` is set; the final norm before the LM head leaves h alone (h is dead after it, and
 // two head rows may map to one row of h, so a write-back would race).
-// quad_tiled (bf16, identity row map, d within the one-row-per-workgroup kernels' range): y is written in the
+// quad_tiled (bf16, d within the one-row-per-workgroup kernels' range): y is written in the
 // layout gemm_qkv_a_quad_tiled() describes instead of row-major; the arithmetic is the same.
 void launch_rmsnorm(float* h, const float* parts, int n_parts, size_t part_stride, RowMap src, const void* gain,
                     int dtype, void* y, int rows, int d, float eps, bool write_back, Gate g, hipStream_t s,
@@ -177,6 +177,8 @@ bool gemm_swiglu_a_quad_tiled(int M, int F, int K);
 // the same question for the [N, K] projections that write split-K partials (output and down projection), whose
 // A operands are written by the attention kernel and by the gate/up GEMM's epilogue
 bool gemm_partial_a_quad_tiled(int M, int N, int K);
+// and for the LM head, whose A operand the final RMSNorm writes
+bool gemm_lmhead_a_quad_tiled(int M, int V, int K);
 void launch_gemm_qkv_bf16(const bf16* A, const bf16* wq, const bf16* wk, const bf16* wv, int M, int K,
                           const QkvEpilogue& e, Gate g, hipStream_t s);
 // partial[z][M,N] = A[:, z-th K slice] * W[:, slice]^T, z < splits (1 or 2)

@@ -966,6 +966,7 @@ void launch_gemm_swiglu_bf16(const bf16* A, const bf16* wg, const bf16* wu, bf16
 }
 
 int lmhead_n_part(int V) { return (V + 127) / 128; }
+bool gemm_lmhead_a_quad_tiled(int M, int V, int K) { (void)V; return M > 128 && quad_tiled_widths(K, 64); }
 
 void launch_gemm_lmhead_bf16(const bf16* A, const bf16* W, int M, int V, int K, const LmHeadEpilogue& e, Gate g,
                              hipStream_t s) {
@@ -976,8 +977,10 @@ void launch_gemm_lmhead_bf16(const bf16* A, const bf16* W, int M, int V, int K, 
     launch<32, 128, 64, 1, 4, 4, EPI_LMHEAD>(a, s);
   else if (M <= 128)
     launch<128, 128, 64, 2, 2, 4, EPI_LMHEAD>(a, s);
+  else if (gemm_lmhead_a_quad_tiled(M, V, K))
+    launch<256, 128, 64, 4, 1, 4, EPI_LMHEAD, true>(a, s);   // batched blocks: compute bound, A from registers
   else
-    launch<256, 128, 32, 4, 2, 6, EPI_LMHEAD>(a, s);   // batched blocks: the 1 GB of weights is read once per 256 rows
+    launch<256, 128, 32, 4, 2, 6, EPI_LMHEAD>(a, s);   // the 1 GB of weights is read once per 256 rows
 }
 
 }  // namespace l2pd

@@ -149,7 +149,7 @@ Layout make_layout(const l2pd_model_desc& m, int max_batch, int max_seq, int cac
     L.attn_ws_bytes = attn_chunk_ws_bytes(m.n_heads, m.head_dim);
     L.attn_ws = c.take(L.attn_ws_bytes);
   }
-  L.xn_head = c.take(rows * d * es);   // l2pd_forward may ask for every row
+  L.xn_head = c.take(align_up(rows, 4) * d * es);   // l2pd_forward may ask for every row; quad-tiled layout: rows in fours
   L.part_max = c.take(head_rows * L.n_part * 4);
   L.part_sum = c.take(head_rows * L.n_part * 4);
   L.part_idx = c.take(head_rows * L.n_part * 4);
@@ -360,7 +360,7 @@ void run_head(l2pd_ctx* c, int B, int n_rows_per_seq, RowMap src, float* logits_
     const int sd = c->pend_splits;
     { Timed t(c, L2PD_K_NORM, s);
       launch_rmsnorm(h, sd > 0 ? c->at<float>(L.parts) : nullptr, sd, c->pend_stride, src, c->final_g, m.dtype, xh, hr,
-                     d, m.rms_eps, false, g, s); }
+                     d, m.rms_eps, false, g, s, gemm_lmhead_a_quad_tiled(hr, V, d)); }
     LmHeadEpilogue e = {};
     e.logits = logits_out;
     if (want_parts) {
