@@ -492,24 +492,58 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
     const QkvEpilogue& e = a.qkv;
     const int half = e.Dh / 2, gph = half / 32;
     const bool vec4 = (e.Tq % 4 == 0) && (e.pos0 % 4 == 0) && (e.Tpad % 4 == 0) && (!e.seq_gb || e.pos_per_gb % 4 == 0);
+    const int lr = lj & 3;
+    // which matrix / head / 32-feature group each of the wavefront's fragment pairs belongs to (uniform)
+    int p_mat[FN / 2], p_head[FN / 2], p_gi[FN / 2];
 #pragma unroll
     for (int p = 0; p < FN / 2; ++p) {
-      int G = tile_n * (BN / 64) + wn * (FN / 2) + p;
-      int hg = G / gph, gi = G % gph;
-      int mat = hg / e.H, head = hg % e.H;
-      if (mat > 2) continue;
-      int dim = gi * 32 + lj;   // first-half feature index; partner is dim + half
+      const int G = tile_n * (BN / 64) + wn * (FN / 2) + p;
+      const int hg = G / gph;
+      p_gi[p] = G % gph;
+      p_mat[p] = hg / e.H;
+      p_head[p] = hg % e.H;
+    }
 #pragma unroll
-      for (int i = 0; i < FM; ++i) {
+    for (int i = 0; i < FM; ++i) {
+      // Sequence and position of this lane's 16 rows (register r: row (r/4)*8 + hf*4 + r%4 of the fragment), worked
+      // out once per row fragment and shared by all fragment pairs.
+      int seq_r[16], pos_r[16];
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        const int row0 = row_base + i * 32 + rq * 8 + hf * 4;
+        int t = row0 % e.Tq, bq = row0 / e.Tq;
+        int off = (e.seq_gb && row0 < a.M) ? e.seq_gb[bq] * e.pos_per_gb : 0;
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+          seq_r[rq * 4 + rr] = bq;
+          pos_r[rq * 4 + rr] = e.pos0 + off + t;
+          if (++t == e.Tq) {   // next sequence of the batch
+            t = 0;
+            ++bq;
+            off = (e.seq_gb && row0 + rr + 1 < a.M) ? e.seq_gb[bq] * e.pos_per_gb : 0;
+          }
+        }
+      }
+      // after the transposes a lane stores row `lr` of each group of four
+      int seq_st[4], pos_st[4];
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        seq_st[rq] = lr == 0 ? seq_r[rq * 4] : (lr == 1 ? seq_r[rq * 4 + 1] : (lr == 2 ? seq_r[rq * 4 + 2] : seq_r[rq * 4 + 3]));
+        pos_st[rq] = lr == 0 ? pos_r[rq * 4] : (lr == 1 ? pos_r[rq * 4 + 1] : (lr == 2 ? pos_r[rq * 4 + 2] : pos_r[rq * 4 + 3]));
+      }
+#pragma unroll
+      for (int p = 0; p < FN / 2; ++p) {
+        const int mat = p_mat[p], head = p_head[p], gi = p_gi[p];
+        if (mat > 2) continue;                               // uniform over the wavefront
+        const int dim = gi * 32 + lj;   // first-half feature index; partner is dim + half
         if (mat == 2) {
           // V is stored transposed ([B, H, Dh, Tpad]) so that attention reads keys contiguously
+          unsigned short* vt = reinterpret_cast<unsigned short*>(e.vtstore);
 #pragma unroll
           for (int rq = 0; rq < 4; ++rq) {
-            int row0 = row_base + i * 32 + rq * 8 + hf * 4;
+            const int row0 = row_base + i * 32 + rq * 8 + hf * 4;
             if (vec4 && row0 + 3 < a.M) {
-              int b = row0 / e.Tq, pos = e.pos0 + seq_pos_offset(e.seq_gb, e.pos_per_gb, b) + row0 % e.Tq;
-              size_t o = ((size_t)(b * e.H + head) * e.Dh + dim) * e.Tpad + pos;
-              unsigned short* vt = reinterpret_cast<unsigned short*>(e.vtstore);
+              const size_t o = ((size_t)(seq_r[rq * 4] * e.H + head) * e.Dh + dim) * e.Tpad + pos_r[rq * 4];
               uint2 lo4, hi4;
               lo4.x = pack_bf16(acc[i][2 * p][rq * 4 + 0], acc[i][2 * p][rq * 4 + 1]);
               lo4.y = pack_bf16(acc[i][2 * p][rq * 4 + 2], acc[i][2 * p][rq * 4 + 3]);
@@ -520,43 +554,28 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
             } else {
 #pragma unroll
               for (int rr = 0; rr < 4; ++rr) {
-                int row = row0 + rr;
-                if (row >= a.M) continue;
-                int b = row / e.Tq, pos = e.pos0 + seq_pos_offset(e.seq_gb, e.pos_per_gb, b) + row % e.Tq;
-                size_t o = ((size_t)(b * e.H + head) * e.Dh + dim) * e.Tpad + pos;
-                unsigned short* vt = reinterpret_cast<unsigned short*>(e.vtstore);
+                if (row0 + rr >= a.M) continue;
+                const size_t o = ((size_t)(seq_r[rq * 4 + rr] * e.H + head) * e.Dh + dim) * e.Tpad + pos_r[rq * 4 + rr];
                 vt[o] = f2bf(acc[i][2 * p][rq * 4 + rr]);
                 vt[o + (size_t)half * e.Tpad] = f2bf(acc[i][2 * p + 1][rq * 4 + rr]);
               }
             }
           }
         } else {
-          // Rotation of Q and K.  All table reads of the fragment are issued before its first
+          // Rotation of Q and K.  All table reads of the fragment pair are issued before its first
           // store: the compiler cannot move a load above a store that might alias it, so an
           // interleaved order would pay one memory round trip per element.
           unsigned short* dst = reinterpret_cast<unsigned short*>(mat == 0 ? e.q : e.kstore);
           float cs[16], sn[16];
 #pragma unroll
-          for (int rq = 0; rq < 4; ++rq) {
-            const int row0 = row_base + i * 32 + rq * 8 + hf * 4;
-            int t = row0 % e.Tq, bq = row0 / e.Tq;
-            int off = (e.seq_gb && row0 < a.M) ? e.seq_gb[bq] * e.pos_per_gb : 0;
-#pragma unroll
-            for (int rr = 0; rr < 4; ++rr) {
-              const int r = rq * 4 + rr;
-              const bool live = row0 + rr < a.M;
-              const unsigned ti = (unsigned)(e.pos0 + off + t) * (unsigned)half + (unsigned)dim;   // < 2^31 by construction
-              cs[r] = live ? e.cos_t[ti] : 0.f;
-              sn[r] = live ? e.sin_t[ti] : 0.f;
-              if (++t == e.Tq) {   // next sequence of the batch
-                t = 0;
-                ++bq;
-                off = (e.seq_gb && row0 + rr + 1 < a.M) ? e.seq_gb[bq] * e.pos_per_gb : 0;
-              }
-            }
+          for (int r = 0; r < 16; ++r) {
+            const bool live = row_base + i * 32 + (r >> 2) * 8 + hf * 4 + (r & 3) < a.M;
+            const unsigned ti = (unsigned)pos_r[r] * (unsigned)half + (unsigned)dim;   // < 2^31 by construction
+            cs[r] = live ? e.cos_t[ti] : 0.f;
+            sn[r] = live ? e.sin_t[ti] : 0.f;
           }
           // rotate, round, and turn "one column, four rows" per lane into "four columns, one row"
-          const int lr = lj & 3, c4 = gi * 32 + (lj & ~3);
+          const int c4 = gi * 32 + (lj & ~3);
 #pragma unroll
           for (int rq = 0; rq < 4; ++rq) {
             unsigned w[4];
@@ -573,13 +592,8 @@ __global__ void __launch_bounds__(WM* WN * 64) k_gemm_bf16(GemmArgs a) {
             quad_transpose(w, lane);
             const int row = row_base + i * 32 + rq * 8 + hf * 4 + lr;
             if (row >= a.M) continue;
-            size_t o;
-            if (mat == 0) {
-              o = (size_t)row * e.d + head * e.Dh + c4;
-            } else {
-              const int b = row / e.Tq, pos = e.pos0 + seq_pos_offset(e.seq_gb, e.pos_per_gb, b) + row % e.Tq;
-              o = ((size_t)b * e.Tpad + pos) * e.d + head * e.Dh + c4;
-            }
+            const size_t o = mat == 0 ? (size_t)row * e.d + head * e.Dh + c4
+                                      : ((size_t)seq_st[rq] * e.Tpad + pos_st[rq]) * e.d + head * e.Dh + c4;
             uint2 lo, hi;   // feature c4..c4+3 and its partner c4+half..c4+half+3
             lo.x = (w[0] & 0xffffu) | (w[1] << 16);
             lo.y = (w[2] & 0xffffu) | (w[3] << 16);
